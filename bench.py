@@ -1,0 +1,162 @@
+#!/usr/bin/env python3
+"""Benchmark of the kFkB stage engine on one MI355X.
+
+One step = one whole kFkB iteration of the stage (all micro-batches forward and backward in
+kFkB order, gradient accumulation, transfers) on synthetic data already resident in pinned
+host / device memory.  Workload: the GPT-2-medium-shaped stage (6 blocks, hidden 1024, 16 heads,
+seq 1024, micro-batch 4, 16 micro-batches, bf16 with fp32 gradient accumulation).
+
+Prints ONE JSON line: whole-job samples/s at the best group size k, the per-k table, the roofline
+of the kernel the iteration spends most time in (measured live with HIP events on the library's
+compute stream) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+WORKLOADS = {
+    # name: L, H, heads, T, b, M, dtype, ks
+    "gpt2-medium-stage": dict(L=6, H=1024, heads=16, T=1024, b=4, M=16, dtype="bf16", ks=(1, 2, 4)),
+    "tiny-stage": dict(L=2, H=128, heads=4, T=64, b=2, M=4, dtype="f32", ks=(1, 2)),
+}
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+PEAK_F32_TFLOPS = 157.3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gpt2-medium-stage", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--delay", default="none", choices=["none", "lognormal"],
+                    help="per-transfer injected delay (lognormal: mean 2 ms, sigma 0.5)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build drives one pipeline stage on ONE GPU; --gpus %d is not supported "
+              "(how the path shards over stages is described in DESIGN.md)" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import kfkb_synth as synth
+    import paper_2303_01675_amd as kf
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    kf.load_library()                      # fails loudly if libkfkb.so was not built
+
+    w = WORKLOADS[args.workload]
+    L, H, heads, T, b, M = w["L"], w["H"], w["heads"], w["T"], w["b"], w["M"]
+    dt = kf.BF16 if w["dtype"] == "bf16" else kf.F32
+    t0 = time.time()
+    blocks = synth.stage_weights(L, H, 4 * H, w["dtype"])
+    st = kf.StageBuffers(blocks, dt, heads, T, b, M, max(w["ks"]))
+    for mb in range(M):
+        st.set_inputs_one(mb, synth.microbatch_inputs(mb, b, T, H, w["dtype"]),
+                          synth.microbatch_upstream_grads(mb, b, T, H, w["dtype"]))
+    t_setup = time.time() - t0
+    overlap = kf.stage_side_streams_overlap()
+    if args.delay == "lognormal":
+        d = [synth.delays_lognormal(M, 2.0, 0.5, seed=4242 + i) for i in range(4)]
+        kf.stage_set_delays(*d)
+
+    from oracle import stage_math as osm        # only for the FLOP model and the CPU-baseline leg
+    flops_iter = M * osm.stage_flops(L, b, T, H, causal=True)
+    flops_iter_megatron = M * osm.stage_flops(L, b, T, H, causal=True, megatron=True)
+
+    def step(k):
+        kf.stage_zero_grads()
+        kf.run_kFkB(k, M, 0)
+
+    per_k = {}
+    for k in w["ks"]:
+        for _ in range(args.warmup):
+            step(k)
+        kf.stage_sync()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(k)
+        kf.stage_sync()
+        torch.cuda.synchronize()
+        dt_s = time.perf_counter() - t0
+        per_k[k] = dict(ms_per_step=1e3 * dt_s / args.steps, samples_per_s=M * b * args.steps / dt_s,
+                        tflops=flops_iter * args.steps / dt_s / 1e12,
+                        tflops_megatron=flops_iter_megatron * args.steps / dt_s / 1e12,
+                        activation_gb=kf.stage_activation_bytes(k, M) / 1e9)
+    best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
+
+    # per-kernel timing of the same steps at the best k: HIP start/stop events on the compute stream
+    kf.kfkb_profile(True)
+    for _ in range(args.steps):
+        step(best_k)
+    kf.stage_sync()
+    kf.kfkb_profile(False)
+    stats = kf.kfkb_profile_report()
+    tot_ms = sum(s["total_ms"] for s in stats) or 1.0
+    kernels = []
+    for s in sorted(stats, key=lambda s: -s["total_ms"]):
+        rate = s["work"] / (s["total_ms"] * 1e-3) if s["total_ms"] > 0 else 0.0
+        kernels.append(dict(name=s["name"], bound=s["bound"], launches_per_step=s["launches"] / args.steps,
+                            avg_us=1e3 * s["total_ms"] / max(s["launches"], 1), share=s["total_ms"] / tot_ms,
+                            achieved=(rate / 1e12 if s["bound"] != "hbm" else rate / 1e9),
+                            unit="TFLOP/s" if s["bound"] != "hbm" else "GB/s"))
+    dom = kernels[0]
+    peak = {"mfma": PEAK_BF16_TFLOPS, "hbm": PEAK_HBM_GBS, "alu": PEAK_F32_TFLOPS}[dom["bound"]]
+    roofline = dict(bound=dom["bound"], kernel=dom["name"], achieved=dom["achieved"], peak=peak, unit=dom["unit"],
+                    frac=dom["achieved"] / peak, traffic=None, avg_us=dom["avg_us"], share_of_kernel_time=dom["share"])
+    gemm = [s for s in stats if s["name"].startswith("gemm_bf16")]
+    if gemm:
+        roofline["all_gemm_tflops"] = sum(s["work"] for s in gemm) / (sum(s["total_ms"] for s in gemm) * 1e-3) / 1e12
+        roofline["all_gemm_frac"] = roofline["all_gemm_tflops"] / PEAK_BF16_TFLOPS
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import stage_math as sm
+        x = synth.microbatch_inputs(0, b, T, H, w["dtype"])
+        dy = synth.microbatch_upstream_grads(0, b, T, H, w["dtype"])
+        nsamp = b
+        if args.workload == "gpt2-medium-stage":       # bounded sample: one sample of one micro-batch
+            x, dy, nsamp = x[:1], dy[:1], 1
+        t0 = time.perf_counter()
+        y, caches = sm.stage_fwd(x, blocks, heads, True)
+        sm.stage_bwd(dy, blocks, caches, heads)
+        dt_s = time.perf_counter() - t0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = dict(value=nsamp / dt_s, unit="samples/s", cores=cores, kind="oracle",
+                   sample="forward+backward of %d sample(s) of micro-batch 0 (of %d samples per iteration), float64 numpy"
+                          % (nsamp, M * b), seconds=dt_s)
+
+    best = per_k[best_k]
+    out = {
+        "metric": "stage fwd+bwd samples/sec (kFkB iteration, best k)", "value": best["samples_per_s"],
+        "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w["dtype"], "data": "synthetic",
+        "config": {"workload": args.workload, "layers": L, "hidden": H, "heads": heads, "seq_len": T, "micro_batch": b,
+                   "num_microbatches": M, "global_batch": M * b, "k": best_k, "delay": args.delay,
+                   "side_streams_overlap": bool(overlap)},
+        "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
+        "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,
+        "per_k": {str(k): v for k, v in per_k.items()},
+        "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
+    }
+    st.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

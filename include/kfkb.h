@@ -1,0 +1,235 @@
+/*
+ * kfkb.h - C boundary of the single-GPU kFkB stage engine (gfx950 / MI355X).
+ *
+ * One process owns one GPU and one pipeline stage (the paper's worker model, Section 6.1:
+ * one stage per device).  A stage is a stack of `layers` pre-LN GPT blocks.  The library
+ * runs the stage's forward and backward task nodes (paper Section 2.4) for micro-batches in
+ * the order of a kFkB plan (Sections 1 and 3.2.1: k forwards, then k backwards, units
+ * alternating, early backward between units; k = 1 is 1F1B, k = M is GPipe), accumulates
+ * parameter gradients across micro-batches in fp32 (Section 2.4, gradient-accumulation
+ * nodes), and moves stage inputs / outputs over side streams with an injected per-transfer
+ * delay (Section 5.3: send and receive on streams of their own, successive transfers of a
+ * direction serialised).
+ *
+ * Conventions
+ *   - every function returns 0 on success or a negative KFKB_E_* code; kfkb_last_error()
+ *     gives a message for the calling thread's last failure.  No exception crosses the boundary.
+ *   - "device" pointers are HIP device memory, "host" pointers are ordinary or pinned host
+ *     memory, as stated per argument.  The library never takes ownership: every buffer
+ *     handed in is borrowed until stage_destroy() and is freed by the caller.
+ *   - stage_forward / stage_backward / run_kFkB only enqueue work; stage_sync() waits.
+ *   - all matrices are row-major.  Activations are [tokens, features] with
+ *     tokens = micro_batch * seq and token index = sample * seq + position.
+ *   - not thread-safe: one stage per process, driven from one host thread.
+ */
+#ifndef KFKB_H
+#define KFKB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  KFKB_OK = 0,
+  KFKB_E_ARG = -1,       /* bad argument (shape, k, null pointer) */
+  KFKB_E_STATE = -2,     /* call out of order: backward before forward, forward of a live micro-batch, not bound */
+  KFKB_E_MEMLIMIT = -3,  /* the plan's peak activation bytes exceed mem_limit, or the workspace is too small */
+  KFKB_E_HIP = -4,       /* a HIP runtime call failed */
+  KFKB_E_TIMEOUT = -5    /* stage_sync_timeout() gave up */
+};
+
+enum { KFKB_F32 = 0, KFKB_BF16 = 1 };
+enum { KFKB_OP_F = 0, KFKB_OP_B = 1 };
+
+/* Options fixed before stage_init().  Zero-initialise, then set what differs from the default. */
+typedef struct kfkb_config {
+  int dtype;             /* KFKB_F32 or KFKB_BF16: storage type of weights and activations; all
+                            reductions, statistics and gradient accumulators are fp32 either way */
+  int micro_batch;       /* b: samples per micro-batch (>= 1) */
+  int mlp_ratio;         /* MLP width F = mlp_ratio * hidden; 0 means 4 */
+  int causal;            /* 1: causal attention mask, 0: none */
+  float ln_eps;          /* LayerNorm epsilon; 0 means 1e-5 */
+  int num_stages;        /* S: pipeline depth this stage pretends to sit in; 0 means 1 */
+  int stage_index;       /* s in [0, S): the stage runs w = min(S-1-s, ceil(M/k)) warm-up groups */
+  int max_microbatches;  /* upper bound on num_microbatches of any later run_kFkB (>= 1) */
+} kfkb_config_t;
+
+typedef struct kfkb_op {
+  int op;                /* KFKB_OP_F or KFKB_OP_B */
+  int mb;                /* micro-batch index */
+  double t_start_ms;     /* start / end of the op's kernels on the compute stream, in ms since  */
+  double t_end_ms;       /* the start of the run that logged it                                 */
+} kfkb_op_t;
+
+const char* kfkb_last_error(void);
+
+/* ---- host-only planning (no GPU needed) ------------------------------------------------- */
+
+/* kFkB order of one stage (paper Sections 1, 3.2.1, 5.4).  Writes 2*M ops into out (cap >= 2*M)
+ * and returns 2*M, or a negative error.  w = number of warm-up forward groups (0 for the
+ * last stage).  Inside a group micro-batches run in ascending index. */
+int kfkb_schedule(int k, int num_microbatches, int warmup_groups, kfkb_op_t* out, int cap);
+
+/* Largest number of micro-batches whose activations are alive at once under that plan. */
+int kfkb_peak_live(int k, int num_microbatches, int warmup_groups);
+
+/* Activation bytes one micro-batch holds from its forward to its backward (paper Section 4.1),
+ * for a stage of the given shape; elem_bytes = 4 (fp32) or 2 (bf16). */
+size_t kfkb_activation_bytes_per_microbatch(int layers, int micro_batch, int seq, int hidden, int heads,
+                                            int mlp_width, int elem_bytes);
+
+/* ---- the stage ------------------------------------------------------------------------- */
+
+/* Optional; must precede stage_init.  Copies *cfg. */
+int stage_config(const kfkb_config_t* cfg);
+
+/* Creates the process-global stage.  `weights`: device pointer, one flat buffer in the stage's
+ * dtype holding, per block and in this order,
+ *   ln1_gamma[H] ln1_beta[H] W_qkv[H,3H] b_qkv[3H] W_o[H,H] b_o[H]
+ *   ln2_gamma[H] ln2_beta[H] W_1[H,F] b_1[F] W_2[F,H] b_2[H]
+ * matrices [in, out]; QKV columns ordered [Q | K | V], head j owning columns j*d..(j+1)*d of
+ * each third, d = hidden / heads.  Borrowed until stage_destroy.
+ * Errors: KFKB_E_ARG for hidden % heads != 0 or an unsupported shape (bf16 needs hidden % 128 == 0
+ * and d in {64, 128}; fp32 needs hidden % 8 == 0 and d <= 128); KFKB_E_STATE if a stage exists. */
+int stage_init(const void* weights, int layers, int hidden, int heads, int seq);
+
+/* Number of parameters of the stage (elements of `weights` and of `grad_accum`). */
+size_t stage_param_count(void);
+
+/* Activation bytes of a plan with group size k over num_microbatches (the memory model that
+ * run_kFkB admits plans against): peak_live * bytes per micro-batch. */
+size_t stage_activation_bytes(int k, int num_microbatches);
+
+/* Device bytes the caller must provide to stage_bind for plans up to group size k_max
+ * (activation stash for the peak live count, transfer slots, backward scratch, and the
+ * re-laid-out weight copy the bf16 kernels read). */
+size_t stage_workspace_bytes(int k_max);
+
+/* Hands the library its memory.  workspace: device, >= stage_workspace_bytes(k_max) bytes,
+ * 256-byte aligned.  grad_accum: device, fp32, stage_param_count() elements, same layout as
+ * weights.  host_inputs / host_upstream_grads: pinned host, [max_microbatches][b*T*H] in the
+ * stage dtype, read by the receive stream.  host_outputs / host_input_grads: pinned host, same
+ * shape, written by the send stream.  All borrowed until stage_destroy. */
+int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum,
+               const void* host_inputs, const void* host_upstream_grads,
+               void* host_outputs, void* host_input_grads);
+
+/* Injected delay before each transfer of the next runs, nanoseconds, indexed by micro-batch;
+ * each array has max_microbatches entries (host memory, copied) or is NULL for no delay.
+ * Random delays are drawn by the caller and passed in: the library draws nothing. */
+int stage_set_delays(const int64_t* recv_input_ns, const int64_t* recv_upstream_grad_ns,
+                     const int64_t* send_output_ns, const int64_t* send_input_grad_ns);
+
+/* Rebuilds the library's re-laid-out weight copy after the caller changed `weights`. */
+int stage_refresh_weights(void);
+
+/* Forward task node of micro-batch mb: receive X_mb (if not already received), run the blocks,
+ * stash activations, send Y_mb.  KFKB_E_STATE if mb is live or no stash slot is free. */
+int stage_forward(int mb);
+
+/* Backward task node of micro-batch mb: receive dY_mb, run the blocks in reverse, add the
+ * parameter gradients into grad_accum, send dX_mb, release mb's stash.  KFKB_E_STATE if mb has
+ * no live forward. */
+int stage_backward(int mb);
+
+/* One iteration: builds the kFkB plan for (k, num_microbatches, this stage's warm-up), checks
+ * its activation bytes against mem_limit (bytes of stashed activations; 0 = no limit), then
+ * enqueues every op in plan order with receives issued ahead and sends behind.  k <= 0 picks
+ * the largest k dividing num_microbatches that fits mem_limit and the bound workspace; the
+ * value used is returned by stage_last_k().  Gradients are added to grad_accum (call
+ * stage_zero_grads first for a fresh iteration).
+ * Errors: KFKB_E_ARG (k > M, M > max_microbatches), KFKB_E_MEMLIMIT (before any GPU work). */
+int run_kFkB(int k, int num_microbatches, size_t mem_limit);
+
+int stage_last_k(void);
+
+/* 1 if the library's compute, send and receive streams really run side by side, 0 if the HIP runtime
+ * mapped two of them onto one hardware queue (it has 4 per process; every stream the process creates
+ * takes a share), in which case delayed transfers serialise and timings, not results, are affected.
+ * Measures three 1 ms delay kernels, one per stream; call while the stage is idle. */
+int stage_side_streams_overlap(void);
+int stage_zero_grads(void);               /* enqueues a fill of grad_accum on the compute stream */
+int stage_sync(void);                     /* waits for compute, send and receive streams */
+int stage_sync_timeout(double seconds);   /* same, polling; KFKB_E_TIMEOUT if not done in time */
+int stage_destroy(void);
+
+/* Executed-order log of the ops enqueued since the last run_kFkB began (or since bind): up to
+ * cap entries, returns the count.  Times are resolved from HIP events: call after stage_sync. */
+int stage_get_order(kfkb_op_t* out, int cap);
+
+/* Milliseconds from the start of the last run_kFkB to the completion of its last op or
+ * transfer, measured with HIP events on the library's streams.  Call after stage_sync. */
+double stage_last_run_ms(void);
+
+/* ---- per-kernel timing ------------------------------------------------------------------------ *
+ * While enabled, every kernel launch of the library carries a start and a stop HIP event on the     *
+ * stream it is launched on (the kernel's own begin / end timestamps).  kfkb_profile(1) clears the   *
+ * record and starts collecting, kfkb_profile(0) stops; kfkb_profile_report, called after the work   *
+ * has been synchronised, sums launches, milliseconds and algorithmic work per kernel instantiation.  */
+typedef struct kfkb_kernel_stat {
+  char name[80];        /* kernel template instantiation */
+  int bound;            /* what `work` counts: 0 = matrix-core flops, 1 = HBM bytes, 2 = vector-ALU flops */
+  long long launches;
+  double total_ms;
+  double work;          /* summed over the launches */
+} kfkb_kernel_stat_t;
+int kfkb_profile(int enable);
+int kfkb_profile_report(kfkb_kernel_stat_t* out, int cap);
+
+/* ---- per-kernel entry points (building blocks, used by unit tests and kernel benchmarks) -- *
+ * All pointers are device pointers; dtype is KFKB_F32 or KFKB_BF16 and names the storage type *
+ * of every "T" buffer; `stream` is a hipStream_t (NULL = default stream).  Calls enqueue only. */
+
+enum { KFKB_GEMM_NN = 0,   /* C[M,N] = A[M,K] . B[K,N]                       (forward, fp32 only)   */
+       KFKB_GEMM_NT = 1,   /* C[M,N] = A[M,K] . B[N,K]^T                     (forward bf16, dgrad)  */
+       KFKB_GEMM_TN = 2 }; /* C[M,N] = A[K,M]^T . B[K,N], K = token axis      (wgrad)                */
+enum { KFKB_EPI_NONE = 0,       /* C = acc                                                       */
+       KFKB_EPI_BIAS = 1,       /* C = acc + bias[n]                                             */
+       KFKB_EPI_BIAS_GELU = 2,  /* C = acc + bias[n] (pre-activation), C2 = gelu_tanh(C)         */
+       KFKB_EPI_BIAS_RES = 3,   /* C = acc + bias[n] + residual[m,n]                             */
+       KFKB_EPI_ACCUM = 4,      /* Cacc[m,n] += acc   (fp32 accumulator, fused gradient add)     */
+       KFKB_EPI_GELU_BWD = 5 }; /* C = acc * gelu_tanh'(residual[m,n])   (residual = pre-activation) */
+
+/* bf16: N % 128 == 0, K % 64 == 0 (NT) / M,N % 128 == 0 (TN), any token count. */
+int kfkb_op_gemm(int dtype, int kind, int epilogue, int M, int N, int K, const void* A, const void* B,
+                 const void* bias, const void* residual, void* C, void* C2, float* Cacc, void* stream);
+
+/* y = LN(x) over H per row; mean, rstd: fp32 [rows]. */
+int kfkb_op_layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
+                          float* mean, float* rstd, int rows, int H, float eps, void* stream);
+
+/* dx = LN-backward(dy) + dres (dres may be NULL); dgamma += sum_rows dy*xhat, dbeta += sum_rows dy.
+ * scratch: fp32, kfkb_op_reduce_scratch_floats(H) elements. */
+int kfkb_op_layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean, const float* rstd,
+                          const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta,
+                          float* scratch, int rows, int H, void* stream);
+
+/* out[n] += sum_rows dy[rows, N]  (bias gradient).  scratch as above with H = N. */
+int kfkb_op_colsum_accum(int dtype, const void* dy, float* out, float* scratch, int rows, int N, void* stream);
+size_t kfkb_op_reduce_scratch_floats(int width);
+
+/* du = dg * gelu_tanh'(u), n elements. */
+int kfkb_op_gelu_bwd(int dtype, const void* dg, const void* u, void* du, size_t n, void* stream);
+
+/* Attention over qkv [b*T, 3H] (columns [Q|K|V], head-major inside each third):
+ * o [b*T, H], lse fp32 [b, heads, T] = log-sum-exp of the scaled, masked scores. */
+int kfkb_op_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int b, int T, int H, int heads,
+                          int causal, void* stream);
+
+/* dqkv [b*T, 3H] from do [b*T, H]; needs o and lse of the forward; dsum: fp32 scratch [b, heads, T]. */
+int kfkb_op_attention_bwd(int dtype, const void* qkv, const void* o, const void* d_o, const float* lse,
+                          float* dsum, void* dqkv, int b, int T, int H, int heads, int causal, void* stream);
+
+/* out[c, r] = in[r, c] for a [rows, cols] matrix of the given dtype. */
+int kfkb_op_transpose(int dtype, const void* in, void* out, int rows, int cols, void* stream);
+
+/* One-wave kernel that returns after `ns` nanoseconds of device wall clock (transfer delay). */
+int kfkb_op_delay(int64_t ns, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KFKB_H */

@@ -43,15 +43,16 @@ def receive_plan(order):
 
 
 def simulate(order, k, t_fwd, t_bwd, delay_recv_x, delay_recv_dy, delay_send_y, delay_send_dx,
-             t_copy=0.0):
+             t_copy=0.0, x_slots=None, dy_slots=None):
     """All times in one unit (say ms).  t_fwd / t_bwd: scalars or per-micro-batch lists.
+    x_slots / dy_slots override the pool sizes (defaults: peak live + k, and 2k).
     Returns dict(total=..., start=[...], end=[...], stall=...) with per-op compute times."""
     M = len(order) // 2
     tf = t_fwd if hasattr(t_fwd, "__len__") else [t_fwd] * M
     tb = t_bwd if hasattr(t_bwd, "__len__") else [t_bwd] * M
     live_peak = schedule.peak_live(order)
-    x_free = [0.0] * (live_peak + k)        # times at which input slots become free
-    dy_free = [0.0] * (2 * k)
+    x_free = [0.0] * (x_slots or live_peak + k)     # times at which input slots become free
+    dy_free = [0.0] * (dy_slots or 2 * k)
     plan = receive_plan(order)
     arrive, slot_of = {}, {}
     end_of, sent_y = {}, {}

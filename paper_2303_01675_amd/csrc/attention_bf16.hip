@@ -1,0 +1,491 @@
+// Fused causal attention, bf16 storage, fp32 softmax, on v_mfma_f32_32x32x16_bf16.
+//
+//   forward   per (sample, head, 128 query rows): stream 64-key tiles, online softmax, write O and the
+//             log-sum-exp of every row; the T x T score matrix never exists in memory.
+//   backward  two kernels so that every output element has exactly one writer (no atomics: results
+//             are bit-reproducible):
+//               dq kernel   per 128 query rows, streams key tiles:   dQ = scale * dS K
+//               dkv kernel  per 128 key rows, streams query tiles:   dV = P^T dO,  dK = scale * dS^T Q
+//             both recompute P = exp(scale * Q K^T - lse) and dS = P o (dO V^T - dsum),
+//             dsum = rowsum(dO o O) coming from a small pre-pass.
+//
+// Register / lane plan (one wave owns 32 "own" rows and streams the other operand):
+//   the score tile is produced transposed with respect to the streamed rows, i.e. with the wave's own
+//   row index on the lane (accumulator column = lane % 32) and the streamed rows spread over the 16
+//   accumulator registers.  Per-own-row softmax quantities are then per-lane scalars, and the bf16
+//   rounded tile is, as it sits in registers, the B operand of the next MFMA whose reduction runs
+//   over the streamed rows.  The A operand of that MFMA is a tile read "down the columns" of the
+//   streamed operand in LDS, which the LDS transpose read (ds_read_b64_tr_b16) delivers.
+//   Reduction slot s of lane half hh in a 16-row sub-block corresponds to streamed row
+//   (s / 4) * 8 + hh * 4 + s % 4 on both operands.
+//
+// LDS tiles are [64 rows][D] with the 16-byte chunk index XOR-ed with (row & 7).
+#include "common.h"
+
+namespace kfkb {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <int D>
+struct TileIO {
+  static constexpr int CH = D / 8;            // 16-byte chunks per row
+  static constexpr int NL = D / 32;           // chunks per thread for a 64-row tile
+  // rows row0 .. row0+63 of a [*, ld] matrix, clamped to row_max, columns col0 .. col0+D
+  static __device__ __forceinline__ void load(bf16x8 (&r)[NL], const bf16_t* __restrict__ src, size_t ld, int row0,
+                                              int row_max, int col0) {
+    const int c = threadIdx.x % CH;
+#pragma unroll
+    for (int i = 0; i < NL; i++) {
+      const int row = min(row0 + (int)threadIdx.x / CH + (256 / CH) * i, row_max);
+      r[i] = *reinterpret_cast<const bf16x8*>(src + (size_t)row * ld + col0 + c * 8);
+    }
+  }
+  static __device__ __forceinline__ void store(bf16_t* tile, const bf16x8 (&r)[NL]) {
+    const int c = threadIdx.x % CH;
+#pragma unroll
+    for (int i = 0; i < NL; i++) {
+      const int row = threadIdx.x / CH + (256 / CH) * i;
+      *reinterpret_cast<bf16x8*>(tile + (row * CH + (c ^ (row & 7))) * 8) = r[i];
+    }
+  }
+  // 8 reduction-contiguous values of row `row`, chunk `chunk`
+  static __device__ __forceinline__ bf16x8 frag(const bf16_t* tile, int row, int chunk) {
+    return *reinterpret_cast<const bf16x8*>(tile + (row * CH + (chunk ^ (row & 7))) * 8);
+  }
+  // transpose read: this lane points at (row, col .. col+4) and (row + 8, col .. col+4)
+  static __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* tile, int row, int col) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const bf16_t* p = tile + (row * CH + ((col >> 3) ^ (row & 7))) * 8 + (col & 7);
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * D));
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = lo; u.s.b = hi;
+    return u.v;
+  }
+};
+
+__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int first) {
+  bf16x8 v;
+#pragma unroll
+  for (int s = 0; s < 8; s++) v[s] = (bf16_t)a[first + s];
+  return v;
+}
+__device__ __forceinline__ f32x16 zero16() {
+  f32x16 z;
+#pragma unroll
+  for (int e = 0; e < 16; e++) z[e] = 0.f;
+  return z;
+}
+// streamed-row offset (inside a 32-row tile) of accumulator register r for lane half hh
+__device__ __forceinline__ int acc_row(int r, int hh) { return (r >> 2) * 8 + hh * 4 + (r & 3); }
+
+// ------------------------------------------------------------------------------------------------
+// forward
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+                                                            float* __restrict__ lse, int T, int H, int heads,
+                                                            int causal, float scale_log2) {
+  using IO = TileIO<D>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);     // [2][64][D]
+  bf16_t* Vs = Ks + 2 * 64 * D;                     // [2][64][D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hh = lane >> 5, l32 = lane & 31;
+  const int tr_row = hh * 4 + ((lane & 15) >> 2);
+  const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  const int qb = gridDim.x - 1 - blockIdx.x;        // heaviest (latest) query blocks first
+  const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
+  const size_t ld = 3 * (size_t)H;
+  const bf16_t* base = qkv + (size_t)bi * T * ld;
+  const int q0 = qb * 128, qw0 = q0 + wave * 32;
+  const int i = qw0 + l32;
+  const int ic = min(i, T - 1);
+
+  bf16x8 qf[D / 16];
+#pragma unroll
+  for (int ds = 0; ds < D / 16; ds++)
+    qf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)ic * ld + hd * D + ds * 16 + hh * 8);
+
+  const int nkv_all = (T + 63) / 64;
+  const int nkv = causal ? min(nkv_all, (min(q0 + 127, T - 1)) / 64 + 1) : nkv_all;
+
+  f32x16 oacc[D / 32];
+#pragma unroll
+  for (int t = 0; t < D / 32; t++) oacc[t] = zero16();
+  float mrun = -INFINITY, lsum = 0.f;
+
+  bf16x8 rk[IO::NL], rv[IO::NL];
+  IO::load(rk, base, ld, 0, T - 1, H + hd * D);
+  IO::load(rv, base, ld, 0, T - 1, 2 * H + hd * D);
+  IO::store(Ks, rk);
+  IO::store(Vs, rv);
+  __syncthreads();
+  for (int kb = 0; kb < nkv; kb++) {
+    const int cur = kb & 1, j0 = kb * 64;
+    if (kb + 1 < nkv) {
+      IO::load(rk, base, ld, j0 + 64, T - 1, H + hd * D);
+      IO::load(rv, base, ld, j0 + 64, T - 1, 2 * H + hd * D);
+    }
+    const bf16_t* Kt = Ks + cur * 64 * D;
+    const bf16_t* Vt = Vs + cur * 64 * D;
+    if (!(causal && j0 > qw0 + 31)) {               // wave-uniform: some key of the tile is visible
+      f32x16 st[2] = {zero16(), zero16()};
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int ds = 0; ds < D / 16; ds++)
+          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt], 0, 0, 0);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int j = j0 + jt * 32 + acc_row(r, hh);
+          float t = st[jt][r] * scale_log2;
+          if (j >= T || (causal && j > i)) t = -INFINITY;
+          st[jt][r] = t;
+          mx = fmaxf(mx, t);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(fmaxf(mrun, mx), -1e30f);
+      const float alpha = exp2f(mrun - mnew);
+      float ps = 0.f;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const float p = exp2f(st[jt][r] - mnew);
+          st[jt][r] = p;
+          ps += p;
+        }
+      lsum = lsum * alpha + ps;
+      mrun = mnew;
+#pragma unroll
+      for (int t = 0; t < D / 32; t++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) oacc[t][e] *= alpha;
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int t16 = 0; t16 < 2; t16++) {
+          const bf16x8 pb = pack8(st[jt], t16 * 8);
+#pragma unroll
+          for (int t = 0; t < D / 32; t++)
+            oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Vt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, oacc[t], 0, 0, 0);
+        }
+    }
+    if (kb + 1 < nkv) {
+      IO::store(Ks + (cur ^ 1) * 64 * D, rk);
+      IO::store(Vs + (cur ^ 1) * 64 * D, rv);
+    }
+    __syncthreads();
+  }
+  lsum += __shfl_xor(lsum, 32, 64);
+  if (i < T) {
+    const float inv = 1.0f / lsum;
+    bf16_t* orow = o + ((size_t)bi * T + i) * H + hd * D;
+#pragma unroll
+    for (int t = 0; t < D / 32; t++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; e++) v[e] = (bf16_t)(oacc[t][q * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(orow + t * 32 + q * 8 + hh * 4) = v;
+      }
+    if (hh == 0) lse[((size_t)bi * heads + hd) * T + i] = (mrun + log2f(lsum)) * kLn2;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dQ: own rows = queries, streamed rows = keys
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                                               const float* __restrict__ lse, const float* __restrict__ dsum,
+                                                               bf16_t* __restrict__ dqkv, int T, int H, int heads,
+                                                               int causal, float scale) {
+  using IO = TileIO<D>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);
+  bf16_t* Vs = Ks + 2 * 64 * D;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hh = lane >> 5, l32 = lane & 31;
+  const int tr_row = hh * 4 + ((lane & 15) >> 2);
+  const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
+  const size_t ld = 3 * (size_t)H;
+  const bf16_t* base = qkv + (size_t)bi * T * ld;
+  const int q0 = qb * 128, qw0 = q0 + wave * 32;
+  const int i = qw0 + l32;
+  const int ic = min(i, T - 1);
+  const float scale_log2 = scale * kLog2e;
+
+  bf16x8 qf[D / 16], dof[D / 16];
+#pragma unroll
+  for (int ds = 0; ds < D / 16; ds++) {
+    qf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)ic * ld + hd * D + ds * 16 + hh * 8);
+    dof[ds] = *reinterpret_cast<const bf16x8*>(d_o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
+  }
+  const float lse_i = lse[((size_t)bi * heads + hd) * T + ic] * kLog2e;
+  const float dsum_i = dsum[((size_t)bi * heads + hd) * T + ic];
+
+  const int nkv_all = (T + 63) / 64;
+  const int nkv = causal ? min(nkv_all, (min(q0 + 127, T - 1)) / 64 + 1) : nkv_all;
+  f32x16 dq[D / 32];
+#pragma unroll
+  for (int t = 0; t < D / 32; t++) dq[t] = zero16();
+
+  bf16x8 rk[IO::NL], rv[IO::NL];
+  IO::load(rk, base, ld, 0, T - 1, H + hd * D);
+  IO::load(rv, base, ld, 0, T - 1, 2 * H + hd * D);
+  IO::store(Ks, rk);
+  IO::store(Vs, rv);
+  __syncthreads();
+  for (int kb = 0; kb < nkv; kb++) {
+    const int cur = kb & 1, j0 = kb * 64;
+    if (kb + 1 < nkv) {
+      IO::load(rk, base, ld, j0 + 64, T - 1, H + hd * D);
+      IO::load(rv, base, ld, j0 + 64, T - 1, 2 * H + hd * D);
+    }
+    const bf16_t* Kt = Ks + cur * 64 * D;
+    const bf16_t* Vt = Vs + cur * 64 * D;
+    if (!(causal && j0 > qw0 + 31)) {
+      f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int ds = 0; ds < D / 16; ds++) {
+          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt], 0, 0, 0);
+          dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Vt, jt * 32 + l32, ds * 2 + hh), dof[ds], dp[jt], 0, 0, 0);
+        }
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int j = j0 + jt * 32 + acc_row(r, hh);
+          float p = exp2f(st[jt][r] * scale_log2 - lse_i);
+          if (j >= T || (causal && j > i)) p = 0.f;
+          st[jt][r] = p * (dp[jt][r] - dsum_i);
+        }
+#pragma unroll
+      for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+        for (int t16 = 0; t16 < 2; t16++) {
+          const bf16x8 dsb = pack8(st[jt], t16 * 8);
+#pragma unroll
+          for (int t = 0; t < D / 32; t++)
+            dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Kt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dq[t], 0, 0, 0);
+        }
+    }
+    if (kb + 1 < nkv) {
+      IO::store(Ks + (cur ^ 1) * 64 * D, rk);
+      IO::store(Vs + (cur ^ 1) * 64 * D, rv);
+    }
+    __syncthreads();
+  }
+  if (i < T) {
+    bf16_t* row = dqkv + ((size_t)bi * T + i) * ld + hd * D;
+#pragma unroll
+    for (int t = 0; t < D / 32; t++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; e++) v[e] = (bf16_t)(dq[t][q * 4 + e] * scale);
+        *reinterpret_cast<bf16x4*>(row + t * 32 + q * 8 + hh * 4) = v;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// backward, dK and dV: own rows = keys, streamed rows = queries
+// ------------------------------------------------------------------------------------------------
+template <int D>
+__global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+                                                                const float* __restrict__ lse, const float* __restrict__ dsum,
+                                                                bf16_t* __restrict__ dqkv, int T, int H, int heads,
+                                                                int causal, float scale) {
+  using IO = TileIO<D>;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem);     // [2][64][D]
+  bf16_t* Os = Qs + 2 * 64 * D;                     // [2][64][D]   (dO tiles)
+  float* Ls = reinterpret_cast<float*>(Os + 2 * 64 * D);   // [2][64] lse * log2(e)
+  float* Ss = Ls + 2 * 64;                                 // [2][64] dsum
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hh = lane >> 5, l32 = lane & 31;
+  const int tr_row = hh * 4 + ((lane & 15) >> 2);
+  const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  const int kb = blockIdx.x;                        // early key blocks see the most queries: they come first
+  const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
+  const size_t ld = 3 * (size_t)H;
+  const bf16_t* base = qkv + (size_t)bi * T * ld;
+  const bf16_t* dobase = d_o + (size_t)bi * T * H;
+  const float* lbase = lse + ((size_t)bi * heads + hd) * T;
+  const float* sbase = dsum + ((size_t)bi * heads + hd) * T;
+  const int j0 = kb * 128, jw0 = j0 + wave * 32;
+  const int j = jw0 + l32;
+  const int jc = min(j, T - 1);
+  const float scale_log2 = scale * kLog2e;
+
+  bf16x8 kf[D / 16], vf[D / 16];
+#pragma unroll
+  for (int ds = 0; ds < D / 16; ds++) {
+    kf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)jc * ld + H + hd * D + ds * 16 + hh * 8);
+    vf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)jc * ld + 2 * H + hd * D + ds * 16 + hh * 8);
+  }
+  f32x16 dk[D / 32], dv[D / 32];
+#pragma unroll
+  for (int t = 0; t < D / 32; t++) { dk[t] = zero16(); dv[t] = zero16(); }
+
+  const int nq = (T + 63) / 64;
+  const int ib0 = causal ? j0 / 64 : 0;
+  bf16x8 rq[IO::NL], ro[IO::NL];
+  float rstat = 0.f;
+  auto load_stats = [&](int i0) {
+    if (threadIdx.x < 64) rstat = lbase[min(i0 + (int)threadIdx.x, T - 1)] * kLog2e;
+    else if (threadIdx.x < 128) rstat = sbase[min(i0 + (int)threadIdx.x - 64, T - 1)];
+  };
+  auto store_stats = [&](int st) {
+    if (threadIdx.x < 64) Ls[st * 64 + threadIdx.x] = rstat;
+    else if (threadIdx.x < 128) Ss[st * 64 + threadIdx.x - 64] = rstat;
+  };
+  if (ib0 < nq) {
+    IO::load(rq, base, ld, ib0 * 64, T - 1, hd * D);
+    IO::load(ro, dobase, (size_t)H, ib0 * 64, T - 1, hd * D);
+    load_stats(ib0 * 64);
+    IO::store(Qs, rq);
+    IO::store(Os, ro);
+    store_stats(0);
+  }
+  __syncthreads();
+  for (int ib = ib0; ib < nq; ib++) {
+    const int cur = (ib - ib0) & 1, i0 = ib * 64;
+    if (ib + 1 < nq) {
+      IO::load(rq, base, ld, i0 + 64, T - 1, hd * D);
+      IO::load(ro, dobase, (size_t)H, i0 + 64, T - 1, hd * D);
+      load_stats(i0 + 64);
+    }
+    const bf16_t* Qt = Qs + cur * 64 * D;
+    const bf16_t* Ot = Os + cur * 64 * D;
+    if (!(causal && i0 + 63 < jw0)) {               // wave-uniform: some query of the tile sees these keys
+      f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
+#pragma unroll
+      for (int it = 0; it < 2; it++)
+#pragma unroll
+        for (int ds = 0; ds < D / 16; ds++) {
+          st[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Qt, it * 32 + l32, ds * 2 + hh), kf[ds], st[it], 0, 0, 0);
+          dp[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Ot, it * 32 + l32, ds * 2 + hh), vf[ds], dp[it], 0, 0, 0);
+        }
+#pragma unroll
+      for (int it = 0; it < 2; it++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+          const int il = it * 32 + acc_row(r, hh);
+          const int i = i0 + il;
+          float p = exp2f(st[it][r] * scale_log2 - Ls[cur * 64 + il]);
+          if (i >= T || j >= T || (causal && j > i)) p = 0.f;
+          st[it][r] = p;
+          dp[it][r] = p * (dp[it][r] - Ss[cur * 64 + il]);
+        }
+#pragma unroll
+      for (int it = 0; it < 2; it++)
+#pragma unroll
+        for (int t16 = 0; t16 < 2; t16++) {
+          const bf16x8 pb = pack8(st[it], t16 * 8);
+          const bf16x8 dsb = pack8(dp[it], t16 * 8);
+#pragma unroll
+          for (int t = 0; t < D / 32; t++) {
+            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, dv[t], 0, 0, 0);
+            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dk[t], 0, 0, 0);
+          }
+        }
+    }
+    if (ib + 1 < nq) {
+      IO::store(Qs + (cur ^ 1) * 64 * D, rq);
+      IO::store(Os + (cur ^ 1) * 64 * D, ro);
+      store_stats(cur ^ 1);
+    }
+    __syncthreads();
+  }
+  if (j < T) {
+    bf16_t* krow = dqkv + ((size_t)bi * T + j) * ld + H + hd * D;
+    bf16_t* vrow = dqkv + ((size_t)bi * T + j) * ld + 2 * H + hd * D;
+#pragma unroll
+    for (int t = 0; t < D / 32; t++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        bf16x4 a, b;
+#pragma unroll
+        for (int e = 0; e < 4; e++) { a[e] = (bf16_t)(dk[t][q * 4 + e] * scale); b[e] = (bf16_t)dv[t][q * 4 + e]; }
+        *reinterpret_cast<bf16x4*>(krow + t * 32 + q * 8 + hh * 4) = a;
+        *reinterpret_cast<bf16x4*>(vrow + t * 32 + q * 8 + hh * 4) = b;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+hipError_t launch_attn_dsum(int dt, const void* o, const void* d_o, float* dsum, int b, int T, int H, int heads, hipStream_t s);
+
+template <typename K>
+static hipError_t set_smem(K kern, size_t bytes, bool& done) {
+  if (done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+  if (e == hipSuccess) done = true;
+  return e;
+}
+
+template <int D>
+static hipError_t fwd_d(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s) {
+  static bool attr = false;
+  const size_t smem = (size_t)4 * 64 * D * sizeof(bf16_t);
+  hipError_t e = set_smem(attn_fwd_bf16_kernel<D>, smem, attr);
+  if (e != hipSuccess) return e;
+  const float scale_log2 = kLog2e / sqrtf((float)D);
+  const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
+  klaunch(attn_fwd_bf16_kernel<D>, dim3((T + 127) / 128, b * heads), dim3(256), smem, s, PK_ATTN_FWD + D / 128, 4.0 * pairs * D,
+          qkv, o, lse, T, H, heads, causal, scale_log2);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t bwd_d(const bf16_t* qkv, const bf16_t* d_o, const float* lse, const float* dsum, bf16_t* dqkv, int b,
+                        int T, int H, int heads, int causal, hipStream_t s) {
+  static bool attr1 = false, attr2 = false;
+  const size_t smem1 = (size_t)4 * 64 * D * sizeof(bf16_t);
+  const size_t smem2 = smem1 + 4 * 64 * sizeof(float);
+  hipError_t e = set_smem(attn_bwd_dq_bf16_kernel<D>, smem1, attr1);
+  if (e != hipSuccess) return e;
+  e = set_smem(attn_bwd_dkv_bf16_kernel<D>, smem2, attr2);
+  if (e != hipSuccess) return e;
+  const float scale = 1.0f / sqrtf((float)D);
+  const dim3 grid((T + 127) / 128, b * heads);
+  const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
+  klaunch(attn_bwd_dkv_bf16_kernel<D>, grid, dim3(256), smem2, s, PK_ATTN_DKV + D / 128, 8.0 * pairs * D, qkv, d_o, lse, dsum, dqkv,
+          T, H, heads, causal, scale);
+  klaunch(attn_bwd_dq_bf16_kernel<D>, grid, dim3(256), smem1, s, PK_ATTN_DQ + D / 128, 6.0 * pairs * D, qkv, d_o, lse, dsum, dqkv, T,
+          H, heads, causal, scale);
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_fwd_bf16(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads,
+                                     int causal, hipStream_t s) {
+  if (b <= 0 || T <= 0) return hipSuccess;
+  return (H / heads == 64) ? fwd_d<64>(qkv, o, lse, b, T, H, heads, causal, s)
+                           : fwd_d<128>(qkv, o, lse, b, T, H, heads, causal, s);
+}
+
+hipError_t launch_attention_bwd_bf16(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse,
+                                     float* dsum, bf16_t* dqkv, int b, int T, int H, int heads, int causal,
+                                     hipStream_t s) {
+  if (b <= 0 || T <= 0) return hipSuccess;
+  hipError_t e = launch_attn_dsum(DT_BF16, o, d_o, dsum, b, T, H, heads, s);
+  if (e != hipSuccess) return e;
+  return (H / heads == 64) ? bwd_d<64>(qkv, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s)
+                           : bwd_d<128>(qkv, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s);
+}
+
+}  // namespace kfkb

@@ -1,0 +1,139 @@
+// Internal helpers shared by the HIP translation units of libkfkb (not part of the C boundary).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace kfkb {
+
+typedef __bf16 bf16_t;
+typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
+typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// ---- bf16 <-> fp32 (round to nearest even on the way down) -----------------------------------
+__device__ __forceinline__ float bf2f(bf16_t v) { return (float)v; }
+__device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)f; }
+
+template <typename T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return (bf16_t)v; }
+
+// 8 consecutive elements of T <-> 8 floats, vector loads (16 B for bf16, 2 x 16 B for fp32).
+template <typename T> struct Vec8;
+template <> struct Vec8<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4*>(p + 4) = make_float4(v[4], v[5], v[6], v[7]);
+  }
+};
+template <> struct Vec8<bf16_t> {
+  static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (float)a[i];
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float (&v)[8]) {
+    bf16x8 a;
+#pragma unroll
+    for (int i = 0; i < 8; i++) a[i] = (bf16_t)v[i];
+    *reinterpret_cast<bf16x8*>(p) = a;
+  }
+};
+
+// ---- wave64 reductions --------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- GELU, tanh form: 0.5 u (1 + tanh(c0 (u + c1 u^3))) ----------------------------------------
+// tanh(z) = 1 - 2 / (1 + exp(2 z)); expf overflow to +inf gives exactly 1, underflow gives -1.
+__device__ __forceinline__ float tanh_f(float z) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * z)); }
+__device__ __forceinline__ float gelu_f(float u) {
+  const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
+  return 0.5f * u * (1.0f + tanh_f(z));
+}
+__device__ __forceinline__ float gelu_grad_f(float u) {
+  const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
+  const float t = tanh_f(z);
+  const float dz = 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * u * u);
+  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dz;
+}
+
+// ---- optional per-kernel timing -------------------------------------------------------------------
+// When collection is on, a launch goes through hipExtLaunchKernelGGL with a start and a stop event,
+// which carry the kernel's own begin / end timestamps; otherwise it is a plain launch.
+// `work` is the launch's algorithmic work: flops for the matrix-core kernels, bytes for the
+// bandwidth-bound ones.  Keys name kernel instantiations (see prof_key_name in engine.hip).
+enum ProfClass { PK_GEMM_NT = 1000, PK_GEMM_TN = 2000, PK_ATTN_FWD = 3000, PK_ATTN_DQ = 3100, PK_ATTN_DKV = 3200,
+                 PK_ATTN_DSUM = 3300, PK_LN_FWD = 4000, PK_LN_BWD_DX = 4100, PK_COLSUM = 4200, PK_COLSUM_XHAT = 4300,
+                 PK_COLSUM_FINAL = 4400, PK_GELU_BWD = 4500, PK_GEMM_F32 = 5000, PK_ATTN_F32 = 5100 };
+bool prof_acquire(int key, double work, hipEvent_t* e0, hipEvent_t* e1);
+
+template <typename... KArgs, typename... Args>
+inline void klaunch(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t smem, hipStream_t s, int key, double work,
+                    Args... args) {
+  hipEvent_t e0, e1;
+  if (prof_acquire(key, work, &e0, &e1)) hipExtLaunchKernelGGL(kern, grid, block, (unsigned)smem, s, e0, e1, 0, (KArgs)args...);
+  else hipLaunchKernelGGL(kern, grid, block, (unsigned)smem, s, (KArgs)args...);
+}
+
+// ---- launch-side declarations (definitions in the .hip files) ----------------------------------
+enum { DT_F32 = 0, DT_BF16 = 1 };
+static inline size_t dt_bytes(int dt) { return dt == DT_BF16 ? 2 : 4; }
+
+// Rows of partial column sums that the two-stage column reductions write before their
+// finishing pass (fixed, so results do not depend on the launch).
+constexpr int kReduceParts = 256;
+
+hipError_t launch_ln_fwd(int dt, const void* x, const void* gamma, const void* beta, void* y, float* mean,
+                         float* rstd, int rows, int H, float eps, hipStream_t s);
+hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta,
+                         float* scratch, int rows, int H, hipStream_t s);
+hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratch, int rows, int N, hipStream_t s);
+hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
+hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int cols, hipStream_t s);
+hipError_t launch_delay(int64_t ns, hipStream_t s);
+
+struct GemmArgs {
+  int kind, epilogue, M, N, K;
+  const void *A, *B, *bias, *residual;
+  void *C, *C2;
+  float* Cacc;
+};
+hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);   // NT and TN only
+const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported
+
+hipError_t launch_attention_fwd_f32(const float* qkv, float* o, float* lse, int b, int T, int H, int heads,
+                                    int causal, hipStream_t s);
+hipError_t launch_attention_bwd_f32(const float* qkv, const float* o, const float* d_o, const float* lse,
+                                    float* dsum, float* dqkv, int b, int T, int H, int heads, int causal,
+                                    hipStream_t s);
+hipError_t launch_attention_fwd_bf16(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads,
+                                     int causal, hipStream_t s);
+hipError_t launch_attention_bwd_bf16(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse,
+                                     float* dsum, bf16_t* dqkv, int b, int T, int H, int heads, int causal,
+                                     hipStream_t s);
+
+}  // namespace kfkb

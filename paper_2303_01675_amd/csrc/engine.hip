@@ -1,0 +1,937 @@
+// Host side of libkfkb: the process-global stage, the kFkB planner, the transfer engine and the
+// C entry points declared in include/kfkb.h.  Every arithmetic step runs in the HIP kernels of the
+// other translation units; this file only sequences them on three HIP streams.
+#include "common.h"
+#include "../../include/kfkb.h"
+
+#include <algorithm>
+#include <chrono>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <thread>
+#include <vector>
+
+using namespace kfkb;
+
+// ---- per-kernel timing (see common.h) -------------------------------------------------------------
+namespace {
+struct ProfRec { int key; double work; hipEvent_t e0, e1; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_pool;      // events created so far, reused run after run
+size_t g_prof_next = 0;
+
+void prof_key_name(int key, char* out, size_t cap, int* bound) {
+  static const char* epi[] = {"none", "bias", "bias_gelu", "bias_res", "accum", "gelu_bwd"};
+  *bound = 1;
+  if (key >= PK_GEMM_NT && key < PK_ATTN_FWD) {
+    const bool tn = key >= PK_GEMM_TN;
+    const int r = key - (tn ? PK_GEMM_TN : PK_GEMM_NT);
+    *bound = 0;
+    snprintf(out, cap, "gemm_bf16_%s_kernel<%d,%d,%s>", tn ? "tn" : "nt", r >= 100 ? 256 : 128, r >= 100 ? 256 : 128, epi[r % 100]);
+  } else if (key >= PK_ATTN_FWD && key < PK_ATTN_DSUM) {
+    const int cls = (key - PK_ATTN_FWD) / 100;
+    *bound = 0;
+    snprintf(out, cap, "%s<%d>", cls == 0 ? "attn_fwd_bf16_kernel" : cls == 1 ? "attn_bwd_dq_bf16_kernel" : "attn_bwd_dkv_bf16_kernel", (key - PK_ATTN_FWD) % 100 ? 128 : 64);
+  } else if (key >= PK_ATTN_DSUM && key < PK_LN_FWD) snprintf(out, cap, "attn_dsum_kernel");
+  else if (key >= PK_LN_FWD && key < PK_LN_BWD_DX) snprintf(out, cap, "ln_fwd_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_FWD) / 4);
+  else if (key >= PK_LN_BWD_DX && key < PK_COLSUM) snprintf(out, cap, "ln_bwd_dx_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_BWD_DX) / 4);
+  else if (key >= PK_COLSUM && key < PK_COLSUM_XHAT) snprintf(out, cap, "colsum_partial_kernel<%s,false>", key - PK_COLSUM == 4 ? "float" : "bf16");
+  else if (key >= PK_COLSUM_XHAT && key < PK_COLSUM_FINAL) snprintf(out, cap, "colsum_partial_kernel<%s,true>", key - PK_COLSUM_XHAT == 4 ? "float" : "bf16");
+  else if (key == PK_COLSUM_FINAL) snprintf(out, cap, "colsum_final_kernel");
+  else if (key >= PK_GELU_BWD && key < PK_GEMM_F32) snprintf(out, cap, "gelu_bwd_kernel<%s>", key - PK_GELU_BWD == 4 ? "float" : "bf16");
+  else if (key >= PK_GEMM_F32 && key < PK_ATTN_F32) { *bound = 2; snprintf(out, cap, "gemm_f32_kernel<%s>", epi[key - PK_GEMM_F32]); }
+  else snprintf(out, cap, "kernel_%d", key);
+}
+}  // namespace
+
+namespace kfkb {
+bool prof_acquire(int key, double work, hipEvent_t* e0, hipEvent_t* e1) {
+  if (!g_prof_on) return false;
+  while (g_prof_pool.size() < g_prof_next + 2) {
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return false;
+    g_prof_pool.push_back(e);
+  }
+  *e0 = g_prof_pool[g_prof_next++];
+  *e1 = g_prof_pool[g_prof_next++];
+  g_prof_recs.push_back(ProfRec{key, work, *e0, *e1});
+  return true;
+}
+}  // namespace kfkb
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIPCHK(expr)                                                                                   \
+  do {                                                                                                 \
+    hipError_t e_ = (expr);                                                                            \
+    if (e_ != hipSuccess) return fail(KFKB_E_HIP, "%s failed: %s", #expr, hipGetErrorString(e_));      \
+  } while (0)
+
+inline size_t align_up(size_t v, size_t a = 256) { return (v + a - 1) / a * a; }
+
+// ---- planning (host only) ----------------------------------------------------------------------
+// Group-level state machine: fill w forward groups, then alternate one forward group with the oldest
+// pending backward group, then drain.  Inside a group micro-batches ascend.
+int build_order(int k, int M, int w, std::vector<kfkb_op_t>& out) {
+  out.clear();
+  const int G = (M + k - 1) / k;
+  w = std::min(w, G);
+  int fg = 0, bg = 0;
+  auto emit = [&](int op, int g) {
+    for (int mb = g * k; mb < std::min(M, (g + 1) * k); mb++) out.push_back(kfkb_op_t{op, mb, 0.0, 0.0});
+  };
+  while (bg < G) {
+    if (fg < G && fg - bg < w) {
+      emit(KFKB_OP_F, fg++);
+    } else if (fg < G) {
+      emit(KFKB_OP_F, fg++);
+      emit(KFKB_OP_B, bg++);
+    } else {
+      emit(KFKB_OP_B, bg++);
+    }
+  }
+  return (int)out.size();
+}
+
+int peak_live_of(const std::vector<kfkb_op_t>& order) {
+  int live = 0, peak = 0;
+  for (const auto& o : order) {
+    live += o.op == KFKB_OP_F ? 1 : -1;
+    peak = std::max(peak, live);
+  }
+  return peak;
+}
+
+// Receive list: the order's units with every forward unit moved ahead of the backward unit before it
+// (stage inputs are sent one schedule unit ahead by the upstream neighbour).
+void build_receive_plan(const std::vector<kfkb_op_t>& order, std::vector<kfkb_op_t>& plan) {
+  std::vector<std::vector<kfkb_op_t>> units;
+  for (const auto& o : order) {
+    if (!units.empty() && units.back().back().op == o.op) units.back().push_back(o);
+    else units.push_back({o});
+  }
+  for (size_t i = 0; i + 1 < units.size();) {
+    if (units[i][0].op == KFKB_OP_B && units[i + 1][0].op == KFKB_OP_F) {
+      std::swap(units[i], units[i + 1]);
+      i += 2;
+    } else {
+      i += 1;
+    }
+  }
+  plan.clear();
+  for (const auto& u : units) plan.insert(plan.end(), u.begin(), u.end());
+}
+
+// ---- the stage ---------------------------------------------------------------------------------
+struct BlockParams {          // element offsets inside one block's parameter run
+  size_t ln1_g, ln1_b, w_qkv, b_qkv, w_o, b_o, ln2_g, ln2_b, w_1, b_1, w_2, b_2, total;
+};
+
+struct MbState {
+  int x_slot = -1, dy_slot = -1, stash = -1, y_buf = -1, dx_buf = -1;
+  bool x_issued = false, dy_issued = false, fwd_done = false, bwd_done = false;
+};
+
+struct Pool {                 // device buffers handed round between transfers and compute
+  std::vector<char*> buf;
+  std::vector<hipEvent_t> release;   // event after which the buffer may be overwritten (or null)
+  std::vector<int> free_list;
+  // all buffers free again; release events are kept, so work of an earlier iteration that still reads
+  // or sends a buffer is waited for before the buffer is overwritten
+  void reset() { free_list.clear(); for (int i = (int)buf.size() - 1; i >= 0; i--) free_list.push_back(i); }
+  int take() { if (free_list.empty()) return -1; int s = free_list.back(); free_list.pop_back(); return s; }
+  void give(int s, hipEvent_t ev) { release[s] = ev; free_list.insert(free_list.begin(), s); }
+};
+
+struct Stage {
+  bool inited = false, bound = false;
+  kfkb_config_t cfg{};
+  int dt = 0, L = 0, H = 0, heads = 0, d = 0, T = 0, b = 0, F = 0, m = 0, Mmax = 0;
+  size_t n = 0, esz = 4;
+  BlockParams po{};
+  const char* weights = nullptr;
+  float* grad = nullptr;
+  const char* h_in = nullptr; const char* h_up = nullptr; char* h_out = nullptr; char* h_ingrad = nullptr;
+  // workspace carve-up
+  char* ws = nullptr; size_t ws_bytes = 0; int k_bound = 0; int n_stash = 0;
+  char* wt = nullptr;                        // bf16 only: weight matrices stored [out, in]
+  std::vector<char*> stash; std::vector<int> stash_free;
+  Pool xs, dys, ys, dxs;
+  char* t_n[4] = {nullptr, nullptr, nullptr, nullptr}; char* t_mf = nullptr; char* t_3n = nullptr;
+  float* dsum = nullptr; float* red = nullptr;
+  size_t stash_block_bytes = 0, stash_bytes = 0;
+  // streams and events
+  hipStream_t sc = nullptr, ss = nullptr, sr = nullptr;
+  std::vector<hipEvent_t> ev_x, ev_dy, ev_f0, ev_f1, ev_b0, ev_b1, ev_ys, ev_dxs;
+  hipEvent_t ev_epoch = nullptr, ev_run_end = nullptr;
+  bool epoch_valid = false, run_timed = false;
+  std::vector<int64_t> dl_x, dl_dy, dl_y, dl_dx;
+  std::vector<MbState> mb;
+  struct LogEntry { int op, mb; };
+  std::vector<LogEntry> log;
+  int last_k = 0;
+};
+
+Stage g;
+kfkb_config_t g_cfg_pending{};
+bool g_cfg_set = false;
+
+size_t stash_block_bytes_of(const Stage& s) {
+  // a, qkv(3), o, x1, c, y : 8 n ; u, g : 2 m F ; LN statistics 4 m floats ; lse b*heads*T floats
+  return align_up((8 * s.n + 2 * (size_t)s.m * s.F) * s.esz) + align_up((4 * (size_t)s.m + (size_t)s.b * s.heads * s.T) * 4);
+}
+
+int warmup_for(const Stage& s, int k, int M) {
+  const int S = std::max(1, s.cfg.num_stages);
+  const int G = (M + k - 1) / k;
+  return std::min(std::max(0, S - 1 - s.cfg.stage_index), G);
+}
+
+int peak_live_for(const Stage& s, int k, int M) {
+  return std::min((warmup_for(s, k, M) + 1) * k, M);
+}
+
+size_t red_floats(const Stage& s) { return (size_t)64 * 2 * std::max(s.F, 3 * s.H); }
+
+struct Carve { size_t wt, stash, xs, dys, ys, dxs, tn, tmf, t3n, dsum, red, total; int n_stash, n_x, n_io; };
+
+Carve carve_for(const Stage& s, int k_max) {
+  Carve c{};
+  const int live = peak_live_for(s, k_max, s.Mmax);
+  c.n_stash = live; c.n_x = std::min(live + k_max, std::max(s.Mmax, 1)) ; c.n_io = std::min(2 * k_max, std::max(s.Mmax, 1));
+  const size_t act = align_up(s.n * s.esz);
+  size_t off = 0;
+  c.wt = off;
+  if (s.dt == DT_BF16) off += align_up((size_t)s.L * ((size_t)4 * s.H * s.H + 2 * (size_t)s.H * s.F) * 2);
+  c.stash = off; off += (size_t)c.n_stash * s.L * stash_block_bytes_of(s);
+  c.xs = off; off += (size_t)c.n_x * act;
+  c.dys = off; off += (size_t)c.n_io * act;
+  c.ys = off; off += (size_t)c.n_io * act;
+  c.dxs = off; off += (size_t)c.n_io * act;
+  c.tn = off; off += 4 * act;
+  c.tmf = off; off += align_up((size_t)s.m * s.F * s.esz);
+  c.t3n = off; off += align_up(3 * s.n * s.esz);
+  c.dsum = off; off += align_up((size_t)s.b * s.heads * s.T * 4);
+  c.red = off; off += align_up(red_floats(s) * 4);
+  c.total = off;
+  return c;
+}
+
+inline const char* wptr(const Stage& s, int l, size_t off) { return s.weights + ((size_t)l * s.po.total + off) * s.esz; }
+inline float* gptr(const Stage& s, int l, size_t off) { return s.grad + (size_t)l * s.po.total + off; }
+
+// pointers into one (slot, block) of the stash
+struct StashView { char *a, *qkv, *o, *x1, *c, *y, *u, *gact; float *mean1, *rstd1, *mean2, *rstd2, *lse; };
+StashView view(const Stage& s, int slot, int l) {
+  char* p = s.stash[slot] + (size_t)l * s.stash_block_bytes;
+  const size_t nb = s.n * s.esz, fb = (size_t)s.m * s.F * s.esz;
+  StashView v;
+  v.a = p; v.qkv = p + nb; v.o = p + 4 * nb; v.x1 = p + 5 * nb; v.c = p + 6 * nb; v.y = p + 7 * nb;
+  v.u = p + 8 * nb; v.gact = p + 8 * nb + fb;
+  float* st = reinterpret_cast<float*>(p + align_up(8 * nb + 2 * fb));
+  v.mean1 = st; v.rstd1 = st + s.m; v.mean2 = st + 2 * s.m; v.rstd2 = st + 3 * s.m; v.lse = st + 4 * (size_t)s.m;
+  return v;
+}
+
+// re-laid-out weight matrices of block l (bf16): [out, in]
+struct WtView { const char *qkv, *o, *w1, *w2; };
+WtView wt_view(const Stage& s, int l) {
+  const size_t H = s.H, F = s.F;
+  const size_t per = (3 * H * H + H * H + 2 * H * F) * 2;
+  const char* p = s.wt + (size_t)l * per;
+  return WtView{p, p + 3 * H * H * 2, p + 4 * H * H * 2, p + (4 * H * H + H * F) * 2};
+}
+
+int gemm(const Stage& s, int kind, int epi, int M, int N, int K, const void* A, const void* B, const void* bias,
+         const void* res, void* C, void* C2, float* Cacc) {
+  GemmArgs a{kind, epi, M, N, K, A, B, bias, res, C, C2, Cacc};
+  if (s.dt == DT_BF16) {
+    const char* why = gemm_bf16_check(a);
+    if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
+    HIPCHK(launch_gemm_bf16(a, s.sc));
+  } else {
+    HIPCHK(launch_gemm_f32(a, s.sc));
+  }
+  return 0;
+}
+
+// forward linear map y = x W + b (+ epilogue): fp32 reads W [in,out] as given, bf16 reads the [out,in] copy
+int linear_fwd(const Stage& s, int epi, int in, int out, const void* x, const void* W, const void* Wt, const void* bias,
+               const void* res, void* y, void* y2) {
+  if (s.dt == DT_BF16) return gemm(s, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr);
+  return gemm(s, KFKB_GEMM_NN, epi, s.m, out, in, x, W, bias, res, y, y2, nullptr);
+}
+
+int refresh_weights() {
+  if (g.dt != DT_BF16) return 0;
+  for (int l = 0; l < g.L; l++) {
+    WtView w = wt_view(g, l);
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_qkv), (void*)w.qkv, g.H, 3 * g.H, g.sc));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_o), (void*)w.o, g.H, g.H, g.sc));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_1), (void*)w.w1, g.H, g.F, g.sc));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_2), (void*)w.w2, g.F, g.H, g.sc));
+  }
+  return 0;
+}
+
+int attention_fwd(const Stage& s, const void* qkv, void* o, float* lse) {
+  if (s.dt == DT_BF16) HIPCHK(launch_attention_fwd_bf16((const bf16_t*)qkv, (bf16_t*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+  else HIPCHK(launch_attention_fwd_f32((const float*)qkv, (float*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+  return 0;
+}
+int attention_bwd(const Stage& s, const void* qkv, const void* o, const void* d_o, const float* lse, void* dqkv) {
+  if (s.dt == DT_BF16)
+    HIPCHK(launch_attention_bwd_bf16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, s.dsum, (bf16_t*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+  else
+    HIPCHK(launch_attention_bwd_f32((const float*)qkv, (const float*)o, (const float*)d_o, lse, s.dsum, (float*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+  return 0;
+}
+
+#define TRY(expr) do { int rc_ = (expr); if (rc_ != 0) return rc_; } while (0)
+
+// ---- the stage computation: forward and backward of all blocks for one micro-batch -----------
+int compute_forward(int slot, const char* x_in, char* y_out) {
+  const Stage& s = g;
+  const char* x = x_in;
+  for (int l = 0; l < s.L; l++) {
+    StashView v = view(s, slot, l);
+    WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{nullptr, nullptr, nullptr, nullptr};
+    char* y = (l == s.L - 1) ? y_out : v.y;
+    HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, s.sc));
+    TRY(linear_fwd(s, KFKB_EPI_BIAS, s.H, 3 * s.H, v.a, wptr(s, l, s.po.w_qkv), w.qkv, wptr(s, l, s.po.b_qkv), nullptr, v.qkv, nullptr));
+    TRY(attention_fwd(s, v.qkv, v.o, v.lse));
+    TRY(linear_fwd(s, KFKB_EPI_BIAS_RES, s.H, s.H, v.o, wptr(s, l, s.po.w_o), w.o, wptr(s, l, s.po.b_o), x, v.x1, nullptr));
+    HIPCHK(launch_ln_fwd(s.dt, v.x1, wptr(s, l, s.po.ln2_g), wptr(s, l, s.po.ln2_b), v.c, v.mean2, v.rstd2, s.m, s.H, s.cfg.ln_eps, s.sc));
+    TRY(linear_fwd(s, KFKB_EPI_BIAS_GELU, s.H, s.F, v.c, wptr(s, l, s.po.w_1), w.w1, wptr(s, l, s.po.b_1), nullptr, v.u, v.gact));
+    TRY(linear_fwd(s, KFKB_EPI_BIAS_RES, s.F, s.H, v.gact, wptr(s, l, s.po.w_2), w.w2, wptr(s, l, s.po.b_2), v.x1, y, nullptr));
+    x = y;
+  }
+  return 0;
+}
+
+int compute_backward(int slot, const char* x_in, const char* dy_in, char* dx_out) {
+  const Stage& s = g;
+  const char* dy = dy_in;
+  char* du = s.t_mf;
+  char* dc = s.t_n[0];
+  char* dx1 = s.t_n[1];
+  char* d_o = s.t_n[0];          // dc is dead once dx1 exists
+  char* da = s.t_n[0];           // d_o is dead once dqkv exists
+  char* dqkv = s.t_3n;
+  for (int l = s.L - 1; l >= 0; l--) {
+    StashView v = view(s, slot, l);
+    const char* x = (l == 0) ? x_in : view(s, slot, l - 1).y;
+    char* dx = (l == 0) ? dx_out : s.t_n[2 + (l & 1)];
+    // y = x1 + g W2 + b2
+    HIPCHK(launch_colsum_accum(s.dt, dy, gptr(s, l, s.po.b_2), s.red, s.m, s.H, s.sc));
+    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.F, s.H, s.m, v.gact, dy, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_2)));
+    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
+    // u = c W1 + b1
+    HIPCHK(launch_colsum_accum(s.dt, du, gptr(s, l, s.po.b_1), s.red, s.m, s.F, s.sc));
+    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, s.F, s.m, v.c, du, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_1)));
+    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr));
+    // c = LN2(x1), plus the residual path
+    HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), s.red, s.m, s.H, s.sc));
+    // x1 = x + o Wo + bo
+    HIPCHK(launch_colsum_accum(s.dt, dx1, gptr(s, l, s.po.b_o), s.red, s.m, s.H, s.sc));
+    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, s.H, s.m, v.o, dx1, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_o)));
+    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr));
+    // o = attention(qkv)
+    TRY(attention_bwd(s, v.qkv, v.o, d_o, v.lse, dqkv));
+    // qkv = a Wqkv + bqkv
+    HIPCHK(launch_colsum_accum(s.dt, dqkv, gptr(s, l, s.po.b_qkv), s.red, s.m, 3 * s.H, s.sc));
+    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, 3 * s.H, s.m, v.a, dqkv, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_qkv)));
+    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
+    // a = LN1(x), plus the residual path
+    HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), s.red, s.m, s.H, s.sc));
+    dy = dx;
+  }
+  return 0;
+}
+
+// ---- transfers ---------------------------------------------------------------------------------
+// Receive X_mb (op F) or dY_mb (op B) into a free slot.  Returns 0 issued, 1 not possible yet.
+int issue_recv(int op, int mbi) {
+  MbState& st = g.mb[mbi];
+  const size_t bytes = g.n * g.esz;
+  if (op == KFKB_OP_F) {
+    if (st.x_issued) return 0;
+    const int slot = g.xs.take();
+    if (slot < 0) return 1;
+    if (g.xs.release[slot]) HIPCHK(hipStreamWaitEvent(g.sr, g.xs.release[slot], 0));
+    HIPCHK(launch_delay(g.dl_x[mbi], g.sr));
+    HIPCHK(hipMemcpyAsync(g.xs.buf[slot], g.h_in + (size_t)mbi * bytes, bytes, hipMemcpyHostToDevice, g.sr));
+    HIPCHK(hipEventRecord(g.ev_x[mbi], g.sr));
+    st.x_slot = slot; st.x_issued = true;
+    return 0;
+  }
+  if (st.dy_issued) return 0;
+  if (!st.fwd_done) return 1;                        // the neighbour echoes: dY_mb follows the arrival of Y_mb
+  const int slot = g.dys.take();
+  if (slot < 0) return 1;
+  if (g.dys.release[slot]) HIPCHK(hipStreamWaitEvent(g.sr, g.dys.release[slot], 0));
+  HIPCHK(hipStreamWaitEvent(g.sr, g.ev_ys[mbi], 0));
+  HIPCHK(launch_delay(g.dl_dy[mbi], g.sr));
+  HIPCHK(hipMemcpyAsync(g.dys.buf[slot], g.h_up + (size_t)mbi * bytes, bytes, hipMemcpyHostToDevice, g.sr));
+  HIPCHK(hipEventRecord(g.ev_dy[mbi], g.sr));
+  st.dy_slot = slot; st.dy_issued = true;
+  return 0;
+}
+
+int begin_log_epoch() {
+  HIPCHK(hipEventRecord(g.ev_epoch, g.sc));
+  g.epoch_valid = true;
+  g.log.clear();
+  return 0;
+}
+
+int do_forward(int mbi) {
+  MbState& st = g.mb[mbi];
+  if (st.fwd_done && !st.bwd_done) return fail(KFKB_E_STATE, "forward of micro-batch %d while it is live", mbi);
+  if (st.fwd_done) return fail(KFKB_E_STATE, "forward of micro-batch %d issued twice in this iteration", mbi);
+  if (!st.x_issued) {
+    int rc = issue_recv(KFKB_OP_F, mbi);
+    if (rc < 0) return rc;
+    if (rc == 1) return fail(KFKB_E_STATE, "no free input slot for micro-batch %d", mbi);
+  }
+  if (g.stash_free.empty()) return fail(KFKB_E_STATE, "no free activation slot for micro-batch %d (peak live = %d)", mbi, g.n_stash);
+  const int ybuf = g.ys.take();
+  if (ybuf < 0) return fail(KFKB_E_STATE, "no free output buffer for micro-batch %d", mbi);
+  st.stash = g.stash_free.back(); g.stash_free.pop_back();
+  st.y_buf = ybuf;
+  if (!g.epoch_valid) TRY(begin_log_epoch());
+  HIPCHK(hipStreamWaitEvent(g.sc, g.ev_x[mbi], 0));
+  if (g.ys.release[ybuf]) HIPCHK(hipStreamWaitEvent(g.sc, g.ys.release[ybuf], 0));
+  HIPCHK(hipEventRecord(g.ev_f0[mbi], g.sc));
+  TRY(compute_forward(st.stash, g.xs.buf[st.x_slot], g.ys.buf[ybuf]));
+  HIPCHK(hipEventRecord(g.ev_f1[mbi], g.sc));
+  g.log.push_back({KFKB_OP_F, mbi});
+  // send Y_mb as soon as the forward has delivered it
+  const size_t bytes = g.n * g.esz;
+  HIPCHK(hipStreamWaitEvent(g.ss, g.ev_f1[mbi], 0));
+  HIPCHK(launch_delay(g.dl_y[mbi], g.ss));
+  HIPCHK(hipMemcpyAsync(g.h_out + (size_t)mbi * bytes, g.ys.buf[ybuf], bytes, hipMemcpyDeviceToHost, g.ss));
+  HIPCHK(hipEventRecord(g.ev_ys[mbi], g.ss));
+  g.ys.give(ybuf, g.ev_ys[mbi]);
+  st.fwd_done = true;
+  return 0;
+}
+
+int do_backward(int mbi) {
+  MbState& st = g.mb[mbi];
+  if (!st.fwd_done || st.bwd_done) return fail(KFKB_E_STATE, "backward of micro-batch %d without a live forward", mbi);
+  if (!st.dy_issued) {
+    int rc = issue_recv(KFKB_OP_B, mbi);
+    if (rc < 0) return rc;
+    if (rc == 1) return fail(KFKB_E_STATE, "no free gradient slot for micro-batch %d", mbi);
+  }
+  const int dxbuf = g.dxs.take();
+  if (dxbuf < 0) return fail(KFKB_E_STATE, "no free input-gradient buffer for micro-batch %d", mbi);
+  HIPCHK(hipStreamWaitEvent(g.sc, g.ev_dy[mbi], 0));
+  if (g.dxs.release[dxbuf]) HIPCHK(hipStreamWaitEvent(g.sc, g.dxs.release[dxbuf], 0));
+  HIPCHK(hipEventRecord(g.ev_b0[mbi], g.sc));
+  TRY(compute_backward(st.stash, g.xs.buf[st.x_slot], g.dys.buf[st.dy_slot], g.dxs.buf[dxbuf]));
+  HIPCHK(hipEventRecord(g.ev_b1[mbi], g.sc));
+  g.log.push_back({KFKB_OP_B, mbi});
+  const size_t bytes = g.n * g.esz;
+  HIPCHK(hipStreamWaitEvent(g.ss, g.ev_b1[mbi], 0));
+  HIPCHK(launch_delay(g.dl_dx[mbi], g.ss));
+  HIPCHK(hipMemcpyAsync(g.h_ingrad + (size_t)mbi * bytes, g.dxs.buf[dxbuf], bytes, hipMemcpyDeviceToHost, g.ss));
+  HIPCHK(hipEventRecord(g.ev_dxs[mbi], g.ss));
+  g.dxs.give(dxbuf, g.ev_dxs[mbi]);
+  // early release: the micro-batch's activations and its input slots return to their pools
+  g.stash_free.push_back(st.stash);
+  g.xs.give(st.x_slot, g.ev_b1[mbi]);
+  g.dys.give(st.dy_slot, g.ev_b1[mbi]);
+  st.stash = st.x_slot = st.dy_slot = -1;
+  st.bwd_done = true;
+  return 0;
+}
+
+int live_count() {
+  int live = 0;
+  for (const auto& m : g.mb) live += (m.fwd_done && !m.bwd_done) ? 1 : 0;
+  return live;
+}
+
+void reset_iteration_state() {
+  for (auto& m : g.mb) m = MbState{};
+  g.xs.reset(); g.dys.reset(); g.ys.reset(); g.dxs.reset();
+  g.stash_free.clear();
+  for (int i = g.n_stash - 1; i >= 0; i--) g.stash_free.push_back(i);
+}
+
+int make_events(std::vector<hipEvent_t>& v, int n) {
+  v.resize(n);
+  for (auto& e : v) HIPCHK(hipEventCreate(&e));
+  return 0;
+}
+
+}  // namespace
+
+// =================================================================================================
+extern "C" {
+
+const char* kfkb_last_error(void) { return g_err.c_str(); }
+
+int kfkb_schedule(int k, int num_microbatches, int warmup_groups, kfkb_op_t* out, int cap) {
+  if (k < 1 || num_microbatches < 1 || k > num_microbatches || warmup_groups < 0)
+    return fail(KFKB_E_ARG, "kfkb_schedule needs 1 <= k <= M and w >= 0 (k=%d M=%d w=%d)", k, num_microbatches, warmup_groups);
+  if (out == nullptr || cap < 2 * num_microbatches) return fail(KFKB_E_ARG, "kfkb_schedule: output too small");
+  std::vector<kfkb_op_t> order;
+  const int n = build_order(k, num_microbatches, warmup_groups, order);
+  std::copy(order.begin(), order.end(), out);
+  return n;
+}
+
+int kfkb_peak_live(int k, int num_microbatches, int warmup_groups) {
+  if (k < 1 || num_microbatches < 1 || k > num_microbatches || warmup_groups < 0)
+    return fail(KFKB_E_ARG, "kfkb_peak_live needs 1 <= k <= M and w >= 0");
+  std::vector<kfkb_op_t> order;
+  build_order(k, num_microbatches, warmup_groups, order);
+  return peak_live_of(order);
+}
+
+size_t kfkb_activation_bytes_per_microbatch(int layers, int micro_batch, int seq, int hidden, int heads, int mlp_width,
+                                            int elem_bytes) {
+  const size_t m = (size_t)micro_batch * seq, n = m * hidden;
+  return (size_t)layers * ((8 * n + 2 * m * mlp_width) * elem_bytes + (4 * m + (size_t)micro_batch * heads * seq) * 4);
+}
+
+int stage_config(const kfkb_config_t* cfg) {
+  if (cfg == nullptr) return fail(KFKB_E_ARG, "stage_config: null config");
+  if (g.inited) return fail(KFKB_E_STATE, "stage_config after stage_init");
+  g_cfg_pending = *cfg;
+  g_cfg_set = true;
+  return 0;
+}
+
+int stage_init(const void* weights, int layers, int hidden, int heads, int seq) {
+  if (g.inited) return fail(KFKB_E_STATE, "a stage already exists; call stage_destroy first");
+  kfkb_config_t c{};
+  if (g_cfg_set) c = g_cfg_pending;
+  if (c.micro_batch == 0) c.micro_batch = 1;
+  if (c.mlp_ratio == 0) c.mlp_ratio = 4;
+  if (c.ln_eps == 0.f) c.ln_eps = 1e-5f;
+  if (c.num_stages == 0) c.num_stages = 1;
+  if (c.max_microbatches == 0) c.max_microbatches = 1;
+  if (weights == nullptr) return fail(KFKB_E_ARG, "stage_init: null weights");
+  if (layers < 1 || hidden < 1 || heads < 1 || seq < 1 || c.micro_batch < 1 || c.mlp_ratio < 1 || c.max_microbatches < 1)
+    return fail(KFKB_E_ARG, "stage_init: sizes must be positive");
+  if (c.dtype != KFKB_F32 && c.dtype != KFKB_BF16) return fail(KFKB_E_ARG, "stage_init: unknown dtype %d", c.dtype);
+  if (c.stage_index < 0 || c.stage_index >= c.num_stages) return fail(KFKB_E_ARG, "stage_init: stage_index outside [0, num_stages)");
+  if (hidden % heads != 0) return fail(KFKB_E_ARG, "stage_init: hidden %d not divisible by heads %d", hidden, heads);
+  const int d = hidden / heads;
+  if (c.dtype == KFKB_BF16) {
+    if (hidden % 128 != 0) return fail(KFKB_E_ARG, "stage_init: bf16 needs hidden %% 128 == 0 (got %d)", hidden);
+    if (d != 64 && d != 128) return fail(KFKB_E_ARG, "stage_init: bf16 needs head size 64 or 128 (got %d)", d);
+  } else {
+    if (hidden % 8 != 0) return fail(KFKB_E_ARG, "stage_init: fp32 needs hidden %% 8 == 0 (got %d)", hidden);
+    if (d > 128) return fail(KFKB_E_ARG, "stage_init: fp32 needs head size <= 128 (got %d)", d);
+    if (seq > 4096) return fail(KFKB_E_ARG, "stage_init: fp32 path supports seq <= 4096");
+  }
+  if (hidden > 8192) return fail(KFKB_E_ARG, "stage_init: hidden > 8192 is not supported");
+  Stage s;
+  s.cfg = c; s.dt = c.dtype; s.L = layers; s.H = hidden; s.heads = heads; s.d = d; s.T = seq; s.b = c.micro_batch;
+  s.F = c.mlp_ratio * hidden; s.m = s.b * s.T; s.n = (size_t)s.m * s.H; s.esz = dt_bytes(s.dt); s.Mmax = c.max_microbatches;
+  const size_t H = hidden, F = s.F;
+  BlockParams& p = s.po;
+  size_t o = 0;
+  p.ln1_g = o; o += H; p.ln1_b = o; o += H; p.w_qkv = o; o += H * 3 * H; p.b_qkv = o; o += 3 * H;
+  p.w_o = o; o += H * H; p.b_o = o; o += H; p.ln2_g = o; o += H; p.ln2_b = o; o += H;
+  p.w_1 = o; o += H * F; p.b_1 = o; o += F; p.w_2 = o; o += F * H; p.b_2 = o; o += H; p.total = o;
+  s.weights = (const char*)weights;
+  s.stash_block_bytes = stash_block_bytes_of(s);
+  s.mb.assign(s.Mmax, MbState{});
+  s.dl_x.assign(s.Mmax, 0); s.dl_dy.assign(s.Mmax, 0); s.dl_y.assign(s.Mmax, 0); s.dl_dx.assign(s.Mmax, 0);
+  g = s;
+  HIPCHK(hipStreamCreateWithFlags(&g.sc, hipStreamNonBlocking));
+  HIPCHK(hipStreamCreateWithFlags(&g.ss, hipStreamNonBlocking));
+  HIPCHK(hipStreamCreateWithFlags(&g.sr, hipStreamNonBlocking));
+  TRY(make_events(g.ev_x, g.Mmax)); TRY(make_events(g.ev_dy, g.Mmax));
+  TRY(make_events(g.ev_f0, g.Mmax)); TRY(make_events(g.ev_f1, g.Mmax));
+  TRY(make_events(g.ev_b0, g.Mmax)); TRY(make_events(g.ev_b1, g.Mmax));
+  TRY(make_events(g.ev_ys, g.Mmax)); TRY(make_events(g.ev_dxs, g.Mmax));
+  HIPCHK(hipEventCreate(&g.ev_epoch));
+  HIPCHK(hipEventCreate(&g.ev_run_end));
+  g.inited = true;
+  return 0;
+}
+
+size_t stage_param_count(void) { return g.inited ? (size_t)g.L * g.po.total : 0; }
+
+size_t stage_activation_bytes(int k, int num_microbatches) {
+  if (!g.inited || k < 1 || num_microbatches < 1 || k > num_microbatches) return 0;
+  return (size_t)peak_live_for(g, k, num_microbatches) *
+         kfkb_activation_bytes_per_microbatch(g.L, g.b, g.T, g.H, g.heads, g.F, (int)g.esz);
+}
+
+size_t stage_workspace_bytes(int k_max) {
+  if (!g.inited || k_max < 1) return 0;
+  return carve_for(g, std::min(k_max, g.Mmax)).total;
+}
+
+int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum, const void* host_inputs,
+               const void* host_upstream_grads, void* host_outputs, void* host_input_grads) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_bind before stage_init");
+  if (!workspace || !grad_accum || !host_inputs || !host_upstream_grads || !host_outputs || !host_input_grads)
+    return fail(KFKB_E_ARG, "stage_bind: null pointer");
+  if (((uintptr_t)workspace & 255) != 0) return fail(KFKB_E_ARG, "stage_bind: workspace must be 256-byte aligned");
+  int kb = 0;
+  for (int k = 1; k <= g.Mmax; k++) {
+    if (carve_for(g, k).total <= workspace_bytes) kb = k; else break;
+  }
+  if (kb == 0) return fail(KFKB_E_MEMLIMIT, "stage_bind: workspace of %zu bytes is smaller than stage_workspace_bytes(1) = %zu", workspace_bytes, carve_for(g, 1).total);
+  if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_bind while micro-batches are live");
+  const Carve c = carve_for(g, kb);
+  g.ws = (char*)workspace; g.ws_bytes = workspace_bytes; g.k_bound = kb; g.n_stash = c.n_stash;
+  g.grad = grad_accum;
+  g.h_in = (const char*)host_inputs; g.h_up = (const char*)host_upstream_grads;
+  g.h_out = (char*)host_outputs; g.h_ingrad = (char*)host_input_grads;
+  const size_t act = align_up(g.n * g.esz);
+  g.wt = g.ws + c.wt;
+  g.stash.resize(c.n_stash);
+  for (int i = 0; i < c.n_stash; i++) g.stash[i] = g.ws + c.stash + (size_t)i * g.L * g.stash_block_bytes;
+  auto fill_pool = [&](Pool& p, size_t off, int cnt) {
+    p.buf.resize(cnt); p.release.assign(cnt, nullptr);
+    for (int i = 0; i < cnt; i++) p.buf[i] = g.ws + off + (size_t)i * act;
+  };
+  fill_pool(g.xs, c.xs, c.n_x); fill_pool(g.dys, c.dys, c.n_io); fill_pool(g.ys, c.ys, c.n_io); fill_pool(g.dxs, c.dxs, c.n_io);
+  for (int i = 0; i < 4; i++) g.t_n[i] = g.ws + c.tn + (size_t)i * act;
+  g.t_mf = g.ws + c.tmf; g.t_3n = g.ws + c.t3n;
+  g.dsum = reinterpret_cast<float*>(g.ws + c.dsum);
+  g.red = reinterpret_cast<float*>(g.ws + c.red);
+  reset_iteration_state();
+  g.epoch_valid = false; g.run_timed = false; g.log.clear();
+  g.bound = true;
+  TRY(refresh_weights());
+  HIPCHK(hipStreamSynchronize(g.sc));
+  return 0;
+}
+
+int stage_set_delays(const int64_t* recv_input_ns, const int64_t* recv_upstream_grad_ns, const int64_t* send_output_ns,
+                     const int64_t* send_input_grad_ns) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_set_delays before stage_init");
+  auto set = [&](std::vector<int64_t>& v, const int64_t* src) {
+    for (int i = 0; i < g.Mmax; i++) v[i] = src ? std::max<int64_t>(0, src[i]) : 0;
+  };
+  set(g.dl_x, recv_input_ns); set(g.dl_dy, recv_upstream_grad_ns); set(g.dl_y, send_output_ns); set(g.dl_dx, send_input_grad_ns);
+  return 0;
+}
+
+int stage_refresh_weights(void) {
+  if (!g.bound) return fail(KFKB_E_STATE, "stage_refresh_weights before stage_bind");
+  return refresh_weights();
+}
+
+int stage_forward(int mb) {
+  if (!g.bound) return fail(KFKB_E_STATE, "stage_forward before stage_bind");
+  if (mb < 0 || mb >= g.Mmax) return fail(KFKB_E_ARG, "stage_forward: micro-batch %d outside [0, %d)", mb, g.Mmax);
+  if (g.mb[mb].fwd_done && g.mb[mb].bwd_done) g.mb[mb] = MbState{};     // a finished micro-batch may run again
+  g.run_timed = false;
+  return do_forward(mb);
+}
+
+int stage_backward(int mb) {
+  if (!g.bound) return fail(KFKB_E_STATE, "stage_backward before stage_bind");
+  if (mb < 0 || mb >= g.Mmax) return fail(KFKB_E_ARG, "stage_backward: micro-batch %d outside [0, %d)", mb, g.Mmax);
+  g.run_timed = false;
+  return do_backward(mb);
+}
+
+int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
+  if (!g.bound) return fail(KFKB_E_STATE, "run_kFkB before stage_bind");
+  const int M = num_microbatches;
+  if (M < 1 || M > g.Mmax) return fail(KFKB_E_ARG, "run_kFkB: num_microbatches %d outside [1, %d]", M, g.Mmax);
+  if (k > M) return fail(KFKB_E_ARG, "run_kFkB: k = %d exceeds the number of micro-batches %d", k, M);
+  if (live_count() != 0) return fail(KFKB_E_STATE, "run_kFkB while micro-batches are live");
+  auto fits = [&](int kk, bool& over_limit) {
+    over_limit = mem_limit != 0 && stage_activation_bytes(kk, M) > mem_limit;
+    return !over_limit && kk <= g.k_bound && peak_live_for(g, kk, M) <= g.n_stash;
+  };
+  bool over = false;
+  if (k <= 0) {                                       // largest admissible group size dividing M
+    int best = 0;
+    for (int kk = 1; kk <= M; kk++) {
+      bool o2;
+      if (M % kk == 0 && fits(kk, o2)) best = kk;
+    }
+    if (best == 0) return fail(KFKB_E_MEMLIMIT, "run_kFkB: no group size fits mem_limit = %zu bytes and the bound workspace", mem_limit);
+    k = best;
+  } else if (!fits(k, over)) {
+    if (over) return fail(KFKB_E_MEMLIMIT, "run_kFkB: plan k=%d needs %zu activation bytes, limit is %zu", k, stage_activation_bytes(k, M), mem_limit);
+    return fail(KFKB_E_MEMLIMIT, "run_kFkB: plan k=%d needs a workspace of stage_workspace_bytes(%d) = %zu bytes, %zu bound", k, k, stage_workspace_bytes(k), g.ws_bytes);
+  }
+  std::vector<kfkb_op_t> order, plan;
+  build_order(k, M, warmup_for(g, k, M), order);
+  build_receive_plan(order, plan);
+  reset_iteration_state();
+  g.last_k = k;
+  TRY(begin_log_epoch());
+  HIPCHK(hipStreamWaitEvent(g.ss, g.ev_epoch, 0));
+  HIPCHK(hipStreamWaitEvent(g.sr, g.ev_epoch, 0));
+  size_t rp = 0;
+  for (const auto& op : order) {
+    while (rp < plan.size()) {                        // receives run ahead as far as slots and the echo allow
+      const int rc = issue_recv(plan[rp].op, plan[rp].mb);
+      if (rc < 0) return rc;
+      if (rc == 1) break;
+      rp++;
+    }
+    if (op.op == KFKB_OP_F) TRY(do_forward(op.mb)); else TRY(do_backward(op.mb));
+  }
+  // the run ends when the last transfer has landed
+  hipEvent_t tail_s = g.ev_dxs[order.back().mb];
+  HIPCHK(hipStreamWaitEvent(g.sc, tail_s, 0));
+  HIPCHK(hipEventRecord(g.ev_run_end, g.sc));
+  g.run_timed = true;
+  return 0;
+}
+
+int stage_last_k(void) { return g.last_k; }
+
+int stage_side_streams_overlap(void) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_side_streams_overlap before stage_init");
+  HIPCHK(hipStreamSynchronize(g.sc)); HIPCHK(hipStreamSynchronize(g.ss)); HIPCHK(hipStreamSynchronize(g.sr));
+  for (int rep = 0; rep < 2; rep++) {                 // first round warms the launch path up
+    const auto t0 = std::chrono::steady_clock::now();
+    for (hipStream_t s : {g.sc, g.ss, g.sr}) HIPCHK(launch_delay(rep == 0 ? 1000 : 1000000, s));
+    for (hipStream_t s : {g.sc, g.ss, g.sr}) HIPCHK(hipStreamSynchronize(s));
+    const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+    if (rep == 1) return ms < 1.8 ? 1 : 0;
+  }
+  return 0;
+}
+
+int stage_zero_grads(void) {
+  if (!g.bound) return fail(KFKB_E_STATE, "stage_zero_grads before stage_bind");
+  HIPCHK(launch_fill_zero(g.grad, (size_t)g.L * g.po.total, g.sc));
+  return 0;
+}
+
+int stage_sync(void) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_sync before stage_init");
+  HIPCHK(hipStreamSynchronize(g.sc));
+  HIPCHK(hipStreamSynchronize(g.sr));
+  HIPCHK(hipStreamSynchronize(g.ss));
+  return 0;
+}
+
+int stage_sync_timeout(double seconds) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_sync_timeout before stage_init");
+  const auto t0 = std::chrono::steady_clock::now();
+  for (;;) {
+    bool done = true;
+    for (hipStream_t s : {g.sc, g.sr, g.ss}) {
+      hipError_t e = hipStreamQuery(s);
+      if (e == hipErrorNotReady) done = false;
+      else if (e != hipSuccess) return fail(KFKB_E_HIP, "hipStreamQuery failed: %s", hipGetErrorString(e));
+    }
+    if (done) return 0;
+    if (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > seconds)
+      return fail(KFKB_E_TIMEOUT, "stage_sync_timeout: work still pending after %.3f s", seconds);
+    std::this_thread::sleep_for(std::chrono::microseconds(200));
+  }
+}
+
+int stage_get_order(kfkb_op_t* out, int cap) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_get_order before stage_init");
+  if (out == nullptr && cap > 0) return fail(KFKB_E_ARG, "stage_get_order: null output");
+  const int n = std::min<int>(cap, (int)g.log.size());
+  for (int i = 0; i < n; i++) {
+    const auto& e = g.log[i];
+    float t0 = 0.f, t1 = 0.f;
+    hipEvent_t a = e.op == KFKB_OP_F ? g.ev_f0[e.mb] : g.ev_b0[e.mb];
+    hipEvent_t b = e.op == KFKB_OP_F ? g.ev_f1[e.mb] : g.ev_b1[e.mb];
+    HIPCHK(hipEventElapsedTime(&t0, g.ev_epoch, a));
+    HIPCHK(hipEventElapsedTime(&t1, g.ev_epoch, b));
+    out[i] = kfkb_op_t{e.op, e.mb, (double)t0, (double)t1};
+  }
+  return n;
+}
+
+double stage_last_run_ms(void) {
+  if (!g.inited || !g.run_timed) return -1.0;
+  float ms = 0.f;
+  if (hipEventElapsedTime(&ms, g.ev_epoch, g.ev_run_end) != hipSuccess) return -1.0;
+  return (double)ms;
+}
+
+int stage_destroy(void) {
+  if (!g.inited) return 0;
+  hipStreamSynchronize(g.sc); hipStreamSynchronize(g.sr); hipStreamSynchronize(g.ss);
+  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs})
+    for (auto e : *v) hipEventDestroy(e);
+  hipEventDestroy(g.ev_epoch); hipEventDestroy(g.ev_run_end);
+  hipStreamDestroy(g.sc); hipStreamDestroy(g.ss); hipStreamDestroy(g.sr);
+  g = Stage{};
+  g_cfg_set = false;
+  return 0;
+}
+
+// ---- per-kernel timing ----------------------------------------------------------------------------
+int kfkb_profile(int enable) {
+  g_prof_on = enable != 0;
+  if (g_prof_on) { g_prof_recs.clear(); g_prof_next = 0; }
+  return 0;
+}
+
+int kfkb_profile_report(kfkb_kernel_stat_t* out, int cap) {
+  if (out == nullptr && cap > 0) return fail(KFKB_E_ARG, "kfkb_profile_report: null output");
+  std::vector<int> keys;
+  std::vector<kfkb_kernel_stat_t> st;
+  for (const auto& r : g_prof_recs) {
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, r.e0, r.e1));
+    size_t i = 0;
+    for (; i < keys.size(); i++) if (keys[i] == r.key) break;
+    if (i == keys.size()) {
+      keys.push_back(r.key);
+      kfkb_kernel_stat_t z{};
+      prof_key_name(r.key, z.name, sizeof z.name, &z.bound);
+      st.push_back(z);
+    }
+    st[i].launches += 1; st[i].total_ms += ms; st[i].work += r.work;
+  }
+  const int n = std::min<int>(cap, (int)st.size());
+  for (int i = 0; i < n; i++) out[i] = st[i];
+  return n;
+}
+
+// ---- per-kernel entry points --------------------------------------------------------------------
+#define CHECK_DT(dt) if ((dt) != KFKB_F32 && (dt) != KFKB_BF16) return fail(KFKB_E_ARG, "unknown dtype %d", (dt))
+
+int kfkb_op_gemm(int dtype, int kind, int epilogue, int M, int N, int K, const void* A, const void* B, const void* bias,
+                 const void* residual, void* C, void* C2, float* Cacc, void* stream) {
+  CHECK_DT(dtype);
+  if (kind < KFKB_GEMM_NN || kind > KFKB_GEMM_TN || epilogue < KFKB_EPI_NONE || epilogue > KFKB_EPI_GELU_BWD)
+    return fail(KFKB_E_ARG, "kfkb_op_gemm: bad kind or epilogue");
+  if (M < 0 || N < 0 || K < 0 || !A || !B) return fail(KFKB_E_ARG, "kfkb_op_gemm: bad shape or null operand");
+  const bool need_bias = epilogue == KFKB_EPI_BIAS || epilogue == KFKB_EPI_BIAS_GELU || epilogue == KFKB_EPI_BIAS_RES;
+  const bool need_res = epilogue == KFKB_EPI_BIAS_RES || epilogue == KFKB_EPI_GELU_BWD;
+  if ((need_bias && !bias) || (need_res && !residual) || (epilogue == KFKB_EPI_BIAS_GELU && !C2) ||
+      (epilogue == KFKB_EPI_ACCUM ? !Cacc : !C))
+    return fail(KFKB_E_ARG, "kfkb_op_gemm: epilogue %d misses an operand", epilogue);
+  if (M == 0 || N == 0) return 0;
+  GemmArgs a{kind, epilogue, M, N, K, A, B, bias, residual, C, C2, Cacc};
+  if (dtype == KFKB_BF16) {
+    const char* why = gemm_bf16_check(a);
+    if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
+    HIPCHK(launch_gemm_bf16(a, (hipStream_t)stream));
+  } else {
+    HIPCHK(launch_gemm_f32(a, (hipStream_t)stream));
+  }
+  return 0;
+}
+
+static int check_rows(const char* who, int dtype, int rows, int H) {
+  if (rows < 0 || H < 8 || H % 8 != 0 || H > 8192 * 4) return fail(KFKB_E_ARG, "%s: need rows >= 0 and width %% 8 == 0 (rows=%d width=%d)", who, rows, H);
+  (void)dtype;
+  return 0;
+}
+
+int kfkb_op_layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y, float* mean, float* rstd,
+                          int rows, int H, float eps, void* stream) {
+  CHECK_DT(dtype);
+  TRY(check_rows("kfkb_op_layernorm_fwd", dtype, rows, H));
+  if (H > 8192) return fail(KFKB_E_ARG, "kfkb_op_layernorm_fwd: H > 8192");
+  if (rows == 0) return 0;
+  if (!x || !gamma || !beta || !y || !mean || !rstd) return fail(KFKB_E_ARG, "kfkb_op_layernorm_fwd: null pointer");
+  HIPCHK(launch_ln_fwd(dtype, x, gamma, beta, y, mean, rstd, rows, H, eps, (hipStream_t)stream));
+  return 0;
+}
+
+int kfkb_op_layernorm_bwd(int dtype, const void* dy, const void* x, const float* mean, const float* rstd, const void* gamma,
+                          const void* dres, void* dx, float* dgamma, float* dbeta, float* scratch, int rows, int H,
+                          void* stream) {
+  CHECK_DT(dtype);
+  TRY(check_rows("kfkb_op_layernorm_bwd", dtype, rows, H));
+  if (H > 8192) return fail(KFKB_E_ARG, "kfkb_op_layernorm_bwd: H > 8192");
+  if (rows == 0) return 0;
+  if (!dy || !x || !mean || !rstd || !gamma || !dx || !dgamma || !dbeta || !scratch) return fail(KFKB_E_ARG, "kfkb_op_layernorm_bwd: null pointer");
+  HIPCHK(launch_ln_bwd(dtype, dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, (hipStream_t)stream));
+  return 0;
+}
+
+int kfkb_op_colsum_accum(int dtype, const void* dy, float* out, float* scratch, int rows, int N, void* stream) {
+  CHECK_DT(dtype);
+  TRY(check_rows("kfkb_op_colsum_accum", dtype, rows, N));
+  if (rows == 0) return 0;
+  if (!dy || !out || !scratch) return fail(KFKB_E_ARG, "kfkb_op_colsum_accum: null pointer");
+  HIPCHK(launch_colsum_accum(dtype, dy, out, scratch, rows, N, (hipStream_t)stream));
+  return 0;
+}
+
+size_t kfkb_op_reduce_scratch_floats(int width) { return width > 0 ? (size_t)64 * 2 * width : 0; }
+
+int kfkb_op_gelu_bwd(int dtype, const void* dg, const void* u, void* du, size_t n, void* stream) {
+  CHECK_DT(dtype);
+  if (n % 8 != 0) return fail(KFKB_E_ARG, "kfkb_op_gelu_bwd: element count must be a multiple of 8");
+  if (n && (!dg || !u || !du)) return fail(KFKB_E_ARG, "kfkb_op_gelu_bwd: null pointer");
+  HIPCHK(launch_gelu_bwd(dtype, dg, u, du, n, (hipStream_t)stream));
+  return 0;
+}
+
+static int check_attn(const char* who, int dtype, int b, int T, int H, int heads) {
+  if (b < 0 || T < 0 || H < 1 || heads < 1 || H % heads != 0) return fail(KFKB_E_ARG, "%s: bad shape", who);
+  const int d = H / heads;
+  if (dtype == KFKB_BF16 && d != 64 && d != 128) return fail(KFKB_E_ARG, "%s: bf16 needs head size 64 or 128 (got %d)", who, d);
+  if (dtype == KFKB_F32 && (d > 128 || T > 4096)) return fail(KFKB_E_ARG, "%s: fp32 needs head size <= 128 and T <= 4096", who);
+  return 0;
+}
+
+int kfkb_op_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int b, int T, int H, int heads, int causal,
+                          void* stream) {
+  CHECK_DT(dtype);
+  TRY(check_attn("kfkb_op_attention_fwd", dtype, b, T, H, heads));
+  if (b == 0 || T == 0) return 0;
+  if (!qkv || !o || !lse) return fail(KFKB_E_ARG, "kfkb_op_attention_fwd: null pointer");
+  if (dtype == KFKB_BF16) HIPCHK(launch_attention_fwd_bf16((const bf16_t*)qkv, (bf16_t*)o, lse, b, T, H, heads, causal, (hipStream_t)stream));
+  else HIPCHK(launch_attention_fwd_f32((const float*)qkv, (float*)o, lse, b, T, H, heads, causal, (hipStream_t)stream));
+  return 0;
+}
+
+int kfkb_op_attention_bwd(int dtype, const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum,
+                          void* dqkv, int b, int T, int H, int heads, int causal, void* stream) {
+  CHECK_DT(dtype);
+  TRY(check_attn("kfkb_op_attention_bwd", dtype, b, T, H, heads));
+  if (b == 0 || T == 0) return 0;
+  if (!qkv || !o || !d_o || !lse || !dsum || !dqkv) return fail(KFKB_E_ARG, "kfkb_op_attention_bwd: null pointer");
+  if (dtype == KFKB_BF16)
+    HIPCHK(launch_attention_bwd_bf16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, dsum, (bf16_t*)dqkv, b, T, H, heads, causal, (hipStream_t)stream));
+  else
+    HIPCHK(launch_attention_bwd_f32((const float*)qkv, (const float*)o, (const float*)d_o, lse, dsum, (float*)dqkv, b, T, H, heads, causal, (hipStream_t)stream));
+  return 0;
+}
+
+int kfkb_op_transpose(int dtype, const void* in, void* out, int rows, int cols, void* stream) {
+  CHECK_DT(dtype);
+  if (rows < 0 || cols < 0) return fail(KFKB_E_ARG, "kfkb_op_transpose: negative size");
+  if (rows == 0 || cols == 0) return 0;
+  if (!in || !out) return fail(KFKB_E_ARG, "kfkb_op_transpose: null pointer");
+  HIPCHK(launch_transpose(dtype, in, out, rows, cols, (hipStream_t)stream));
+  return 0;
+}
+
+int kfkb_op_delay(int64_t ns, void* stream) {
+  if (ns < 0) return fail(KFKB_E_ARG, "kfkb_op_delay: negative delay");
+  HIPCHK(launch_delay(ns, (hipStream_t)stream));
+  return 0;
+}
+
+}  // extern "C"

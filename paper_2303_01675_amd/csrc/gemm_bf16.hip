@@ -1,0 +1,385 @@
+// bf16 GEMMs of the stage on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+//
+//   NT:  C[M,N] = A[M,K] . B[N,K]^T     both operands contiguous along the reduction axis
+//        (forward with the weight copy stored [out,in]; input gradients with the weights as given)
+//   TN:  C[M,N] = A[K,M]^T . B[K,N]     both operands strided along the reduction axis, which is
+//        the token axis (weight gradients: A = layer input, B = output gradient)
+//
+// One work-group = 256 threads = 2 x 2 waves computes a BM x BN tile in 64-deep slices.  Slices go
+// global -> registers -> LDS (two LDS stages, one barrier per slice).  NT tiles are stored
+// [row][64] with the 16-byte chunk index XOR-ed by (row & 7) so that both the 16-byte stores and
+// the 16-byte fragment reads are bank-conflict free.  TN tiles are stored as they lie in memory,
+// [reduction row][BM + 16], and fragments are fetched with the LDS transpose read
+// (ds_read_b64_tr_b16), which hands every lane four reduction-consecutive values of its column.
+//
+// The MFMA is issued with its operands swapped (A operand <- B tile, B operand <- A tile): the
+// accumulator of lane l then holds, for output row m = l % 32, four consecutive output columns per
+// register quad, so the epilogue reads bias / residual and writes C with 8-byte (bf16) or 16-byte
+// (fp32 accumulate) vectors.
+//
+// Block index -> tile: consecutive block ids land on different XCDs (8 of them, each with its own
+// L2), so block b works on tile (b % 8) * ceil(tiles/8) + b / 8: every XCD owns a contiguous run of
+// the tile order, and that order walks groups of four tile-rows column by column.
+#include "common.h"
+#include "../../include/kfkb.h"
+
+namespace kfkb {
+
+constexpr int BK = 64;
+
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool& valid) {
+  const int nt = tiles_m * tiles_n;
+  const int per_xcd = (nt + 7) / 8;
+  const int t = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  valid = t < nt;
+  constexpr int GM = 4;
+  const int group = t / (GM * tiles_n);
+  const int first_m = group * GM;
+  const int gsz = min(GM, tiles_m - first_m);
+  const int in_group = t - group * GM * tiles_n;
+  tm = first_m + in_group % gsz;
+  tn = in_group / gsz;
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, int n, int N, const bf16_t* __restrict__ bias,
+                                              const bf16_t* __restrict__ residual, bf16_t* __restrict__ C,
+                                              bf16_t* __restrict__ C2, float* __restrict__ Cacc) {
+  float v[4] = {acc[q * 4 + 0], acc[q * 4 + 1], acc[q * 4 + 2], acc[q * 4 + 3]};
+  const size_t o = (size_t)m * N + n;
+  if (EPI == KFKB_EPI_ACCUM) {
+    float4* p = reinterpret_cast<float4*>(Cacc + o);
+    float4 c = *p;
+    c.x += v[0]; c.y += v[1]; c.z += v[2]; c.w += v[3];
+    *p = c;
+    return;
+  }
+  if (EPI == KFKB_EPI_BIAS || EPI == KFKB_EPI_BIAS_GELU || EPI == KFKB_EPI_BIAS_RES) {
+    const bf16x4 b = *reinterpret_cast<const bf16x4*>(bias + n);
+#pragma unroll
+    for (int e = 0; e < 4; e++) v[e] += (float)b[e];
+  }
+  if (EPI == KFKB_EPI_BIAS_RES) {
+    const bf16x4 r = *reinterpret_cast<const bf16x4*>(residual + o);
+#pragma unroll
+    for (int e = 0; e < 4; e++) v[e] += (float)r[e];
+  }
+  if (EPI == KFKB_EPI_GELU_BWD) {
+    const bf16x4 r = *reinterpret_cast<const bf16x4*>(residual + o);
+#pragma unroll
+    for (int e = 0; e < 4; e++) v[e] *= gelu_grad_f((float)r[e]);
+  }
+  bf16x4 out;
+#pragma unroll
+  for (int e = 0; e < 4; e++) out[e] = (bf16_t)v[e];
+  *reinterpret_cast<bf16x4*>(C + o) = out;
+  if (EPI == KFKB_EPI_BIAS_GELU) {
+    bf16x4 g;
+#pragma unroll
+    for (int e = 0; e < 4; e++) g[e] = (bf16_t)gelu_f((float)out[e]);   // gelu of the stored (rounded) pre-activation
+    *reinterpret_cast<bf16x4*>(C2 + o) = g;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// NT kernel
+// ------------------------------------------------------------------------------------------------
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                           const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
+                                                           const bf16_t* __restrict__ residual, bf16_t* __restrict__ C,
+                                                           bf16_t* __restrict__ C2, float* __restrict__ Cacc,
+                                                           int tiles_m, int tiles_n) {
+  constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 accumulator tiles per wave
+  constexpr int LA = BM / 32, LB = BN / 32;          // 16-byte chunks each thread moves per slice
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][BM][64]
+  bf16_t* Bs = As + 2 * BM * BK;                                      // [2][BN][64]
+
+  int tm, tn; bool valid;
+  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
+  if (!valid) return;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+
+  const int lc = tid & 7, lr = tid >> 3;             // chunk column, first row of this thread's loads
+  const bf16_t* Ag[LA]; const bf16_t* Bg[LB];
+#pragma unroll
+  for (int i = 0; i < LA; i++) Ag[i] = A + (size_t)min(m0 + lr + 32 * i, M - 1) * K + lc * 8;
+#pragma unroll
+  for (int i = 0; i < LB; i++) Bg[i] = B + (size_t)(n0 + lr + 32 * i) * K + lc * 8;
+
+  bf16x8 ra[LA], rb[LB];
+  auto load_global = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < LA; i++) ra[i] = *reinterpret_cast<const bf16x8*>(Ag[i] + kt * BK);
+#pragma unroll
+    for (int i = 0; i < LB; i++) rb[i] = *reinterpret_cast<const bf16x8*>(Bg[i] + kt * BK);
+  };
+  auto store_lds = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < LA; i++) {
+      const int r = lr + 32 * i;
+      *reinterpret_cast<bf16x8*>(As + ((st * BM + r) * 8 + (lc ^ (r & 7))) * 8) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < LB; i++) {
+      const int r = lr + 32 * i;
+      *reinterpret_cast<bf16x8*>(Bs + ((st * BN + r) * 8 + (lc ^ (r & 7))) * 8) = rb[i];
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  const int nk = K / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  const int frow = lane & 31, fhalf = lane >> 5;
+  for (int kt = 0; kt < nk; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) load_global(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++) {
+        const int r = wm0 + i * 32 + frow;
+        fa[i] = *reinterpret_cast<const bf16x8*>(As + ((cur * BM + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; j++) {
+        const int r = wn0 + j * 32 + frow;
+        fb[j] = *reinterpret_cast<const bf16x8*>(Bs + ((cur * BN + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(cur ^ 1);
+    __syncthreads();
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int m = m0 + wm0 + i * 32 + frow;
+    if (m < M) {
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+          epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, bias, residual, C, C2, Cacc);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// TN kernel: C[M,N] (+)= A[K,M]^T B[K,N]; the reduction axis K (tokens) may be ragged.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* p, int row_stride) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * row_stride));
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo; u.s.b = hi;
+  return u.v;
+}
+
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                           const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+                                                           float* __restrict__ Cacc, int tiles_m, int tiles_n) {
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int SA = BM + 16, SB = BN + 16;          // LDS row strides (elements): +32 bytes per row
+  constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
+  constexpr int LA = BM / 32, LB = BN / 32;          // chunks per thread per slice
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][64][SA]
+  bf16_t* Bs = As + 2 * BK * SA;                                      // [2][64][SB]
+
+  int tm, tn; bool valid;
+  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
+  if (!valid) return;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+
+  bf16x8 ra[LA], rb[LB];
+  auto load_global = [&](int kt) {
+#pragma unroll
+    for (int i = 0; i < LA; i++) {
+      const int c = tid % CA, r = tid / CA + (256 / CA) * i;
+      const int k = kt * BK + r;
+      bf16x8 z;
+#pragma unroll
+      for (int e = 0; e < 8; e++) z[e] = (bf16_t)0.f;
+      ra[i] = (k < K) ? *reinterpret_cast<const bf16x8*>(A + (size_t)k * M + m0 + c * 8) : z;
+    }
+#pragma unroll
+    for (int i = 0; i < LB; i++) {
+      const int c = tid % CB, r = tid / CB + (256 / CB) * i;
+      const int k = kt * BK + r;
+      bf16x8 z;
+#pragma unroll
+      for (int e = 0; e < 8; e++) z[e] = (bf16_t)0.f;
+      rb[i] = (k < K) ? *reinterpret_cast<const bf16x8*>(B + (size_t)k * N + n0 + c * 8) : z;
+    }
+  };
+  auto store_lds = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < LA; i++) {
+      const int c = tid % CA, r = tid / CA + (256 / CA) * i;
+      *reinterpret_cast<bf16x8*>(As + (st * BK + r) * SA + c * 8) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < LB; i++) {
+      const int c = tid % CB, r = tid / CB + (256 / CB) * i;
+      *reinterpret_cast<bf16x8*>(Bs + (st * BK + r) * SB + c * 8) = rb[i];
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  // transpose-read geometry: 16-lane group g covers columns (g & 1) * 16 .. + 16 and the reduction
+  // half g >> 1; inside the group lane j points at row j / 4, columns (j % 4) * 4 .. + 4.
+  const int g16 = lane >> 4, j16 = lane & 15;
+  const int tr_row = (g16 >> 1) * 8 + (j16 >> 2);
+  const int tr_col = (g16 & 1) * 16 + (j16 & 3) * 4;
+
+  const int nk = (K + BK - 1) / BK;
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt++) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) load_global(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ks++) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+        fa[i] = lds_tr_frag(As + (cur * BK + ks * 16 + tr_row) * SA + wm0 + i * 32 + tr_col, SA);
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+        fb[j] = lds_tr_frag(Bs + (cur * BK + ks * 16 + tr_row) * SB + wn0 + j * 32 + tr_col, SB);
+#pragma unroll
+      for (int i = 0; i < TM; i++)
+#pragma unroll
+        for (int j = 0; j < TN; j++)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) store_lds(cur ^ 1);
+    __syncthreads();
+  }
+
+  const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int m = m0 + wm0 + i * 32 + frow;
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+        epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, nullptr, nullptr, C, nullptr, Cacc);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+const char* gemm_bf16_check(const GemmArgs& g) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return "bf16 GEMM: empty shape";
+  if (g.kind == KFKB_GEMM_NT) {
+    if (g.N % 128 != 0) return "bf16 NT GEMM needs N % 128 == 0";
+    if (g.K % 64 != 0) return "bf16 NT GEMM needs K % 64 == 0";
+  } else if (g.kind == KFKB_GEMM_TN) {
+    if (g.M % 128 != 0 || g.N % 128 != 0) return "bf16 TN GEMM needs M % 128 == 0 and N % 128 == 0";
+    if (g.epilogue != KFKB_EPI_ACCUM && g.epilogue != KFKB_EPI_NONE) return "bf16 TN GEMM supports epilogues NONE and ACCUM";
+  } else {
+    return "bf16 GEMM supports the NT and TN forms";
+  }
+  return nullptr;
+}
+
+template <int BM, int BN, int EPI>
+static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
+  const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+  const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_NT + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
+          (const bf16_t*)g.A, (const bf16_t*)g.B, (const bf16_t*)g.bias, (const bf16_t*)g.residual, (bf16_t*)g.C,
+          (bf16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int EPI>
+static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
+  const int tiles_m = g.M / BM, tiles_n = g.N / BN;
+  const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+  const size_t smem = (size_t)2 * BK * (BM + 16 + BN + 16) * sizeof(bf16_t);
+  auto kern = gemm_bf16_tn_kernel<BM, BN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
+          (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, g.Cacc, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+// Large tiles when they still give every CU a tile; small tiles otherwise.
+static bool use_big_tiles(int M, int N, bool m_must_divide) {
+  if (N % 256 != 0) return false;
+  if (m_must_divide && M % 256 != 0) return false;
+  const long tiles = (long)((M + 255) / 256) * (N / 256);
+  return tiles >= 224;
+}
+
+template <int EPI>
+static hipError_t launch_nt_epi(const GemmArgs& g, hipStream_t s) {
+  if (use_big_tiles(g.M, g.N, false)) return launch_nt<256, 256, EPI>(g, s);
+  return launch_nt<128, 128, EPI>(g, s);
+}
+
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
+  if (g.kind == KFKB_GEMM_NT) {
+    switch (g.epilogue) {
+      case KFKB_EPI_NONE: return launch_nt_epi<KFKB_EPI_NONE>(g, s);
+      case KFKB_EPI_BIAS: return launch_nt_epi<KFKB_EPI_BIAS>(g, s);
+      case KFKB_EPI_BIAS_GELU: return launch_nt_epi<KFKB_EPI_BIAS_GELU>(g, s);
+      case KFKB_EPI_BIAS_RES: return launch_nt_epi<KFKB_EPI_BIAS_RES>(g, s);
+      case KFKB_EPI_ACCUM: return launch_nt_epi<KFKB_EPI_ACCUM>(g, s);
+      default: return launch_nt_epi<KFKB_EPI_GELU_BWD>(g, s);
+    }
+  }
+  const bool big = use_big_tiles(g.M, g.N, true);
+  if (g.epilogue == KFKB_EPI_ACCUM)
+    return big ? launch_tn<256, 256, KFKB_EPI_ACCUM>(g, s) : launch_tn<128, 128, KFKB_EPI_ACCUM>(g, s);
+  return big ? launch_tn<256, 256, KFKB_EPI_NONE>(g, s) : launch_tn<128, 128, KFKB_EPI_NONE>(g, s);
+}
+
+}  // namespace kfkb

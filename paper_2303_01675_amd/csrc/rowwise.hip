@@ -1,0 +1,341 @@
+// Bandwidth-bound kernels of the stage: LayerNorm forward / backward, GELU backward, column sums
+// (bias and LayerNorm parameter gradients), fills, transposes and the transfer-delay kernel.
+// All statistics and sums are fp32; storage type T is float or bf16.  wave64 throughout.
+#include "common.h"
+#include <algorithm>
+
+namespace kfkb {
+
+// ------------------------------------------------------------------------------------------------
+// LayerNorm forward: one wave per row, the row lives in registers between the two passes.
+// Lane l owns the 8-element chunks l, l+64, l+128, ...  (H % 8 == 0, H <= 512 * NCH).
+// ------------------------------------------------------------------------------------------------
+template <typename T, int NCH>
+__global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
+                                                     const T* __restrict__ beta, T* __restrict__ y,
+                                                     float* __restrict__ mean, float* __restrict__ rstd,
+                                                     int rows, int H, float eps) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nchunks = H >> 3;
+  const T* xr = x + (size_t)row * H;
+  float v[NCH][8];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+      Vec8<T>::load(xr + c * 8, v[i]);
+#pragma unroll
+      for (int e = 0; e < 8; e++) s += v[i][e];
+    }
+  }
+  const float mu = wave_sum(s) / (float)H;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) { const float d = v[i][e] - mu; q += d * d; }
+    }
+  }
+  const float rs = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
+  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  T* yr = y + (size_t)row * H;
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+      float g[8], b[8], o[8];
+      Vec8<T>::load(gamma + c * 8, g);
+      Vec8<T>::load(beta + c * 8, b);
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = (v[i][e] - mu) * rs * g[e] + b[e];
+      Vec8<T>::store(yr + c * 8, o);
+    }
+  }
+}
+
+// LayerNorm backward, input gradient:  g = dy*gamma;  dx = rstd (g - mean(g) - xhat mean(g xhat)) [+ dres]
+template <typename T, int NCH>
+__global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                        const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                        const T* __restrict__ gamma, const T* __restrict__ dres,
+                                                        T* __restrict__ dx, int rows, int H) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int nchunks = H >> 3;
+  const float mu = mean[row], rs = rstd[row];
+  const T* xr = x + (size_t)row * H;
+  const T* dyr = dy + (size_t)row * H;
+  float xh[NCH][8], g[NCH][8];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+      float gm[8];
+      Vec8<T>::load(xr + c * 8, xh[i]);
+      Vec8<T>::load(dyr + c * 8, g[i]);
+      Vec8<T>::load(gamma + c * 8, gm);
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        xh[i][e] = (xh[i][e] - mu) * rs;
+        g[i][e] *= gm[e];
+        s1 += g[i][e];
+        s2 += g[i][e] * xh[i][e];
+      }
+    }
+  }
+  const float m1 = wave_sum(s1) / (float)H;
+  const float m2 = wave_sum(s2) / (float)H;
+  T* dxr = dx + (size_t)row * H;
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) o[e] = rs * (g[i][e] - m1 - xh[i][e] * m2);
+      if (dres != nullptr) {
+        float r[8];
+        Vec8<T>::load(dres + (size_t)row * H + c * 8, r);
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] += r[e];
+      }
+      Vec8<T>::store(dxr + c * 8, o);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Column sums in two deterministic passes.
+//   pass 1: block (colblock, part) sums rows [part*rpp, (part+1)*rpp) of 256 columns; a thread owns
+//           8 adjacent columns and every 8th row; the 8 row-lanes meet in LDS in fixed order.
+//           XHAT = true additionally sums dy * (x - mean) * rstd   (LayerNorm gamma gradient).
+//           partial layout: [part][2][width]  (slot 0: sum dy, slot 1: sum dy*xhat)
+//   pass 2: one thread per column adds the parts in ascending order into the fp32 gradient.
+// ------------------------------------------------------------------------------------------------
+template <typename T, bool XHAT>
+__global__ void __launch_bounds__(256) colsum_partial_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                             const float* __restrict__ mean,
+                                                             const float* __restrict__ rstd,
+                                                             float* __restrict__ partial, int rows, int width,
+                                                             int rows_per_part) {
+  __shared__ float red[2][8][256 + 8];
+  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int col = blockIdx.x * 256 + cg * 8;
+  const int part = blockIdx.y;
+  const int r0 = part * rows_per_part;
+  const int r1 = min(rows, r0 + rows_per_part);
+  float a[8], b[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) { a[e] = 0.f; b[e] = 0.f; }
+  if (col < width) {
+    for (int r = r0 + rl; r < r1; r += 8) {
+      float d[8];
+      Vec8<T>::load(dy + (size_t)r * width + col, d);
+#pragma unroll
+      for (int e = 0; e < 8; e++) a[e] += d[e];
+      if (XHAT) {
+        float xv[8];
+        Vec8<T>::load(x + (size_t)r * width + col, xv);
+        const float mu = mean[r], rs = rstd[r];
+#pragma unroll
+        for (int e = 0; e < 8; e++) b[e] += d[e] * ((xv[e] - mu) * rs);
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; e++) { red[0][rl][cg * 8 + e] = a[e]; red[1][rl][cg * 8 + e] = b[e]; }
+  __syncthreads();
+  const int c = threadIdx.x;
+  if (blockIdx.x * 256 + c < width) {
+    float sa = 0.f, sb = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) { sa += red[0][j][c]; sb += red[1][j][c]; }
+    float* p = partial + (size_t)part * 2 * width;
+    p[blockIdx.x * 256 + c] = sa;
+    if (XHAT) p[width + blockIdx.x * 256 + c] = sb;
+  }
+}
+
+__global__ void colsum_final_kernel(const float* __restrict__ partial, int parts, int width, float* __restrict__ out0,
+                                    float* __restrict__ out1) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= width) return;
+  float s0 = 0.f, s1 = 0.f;
+  for (int p = 0; p < parts; p++) {
+    s0 += partial[(size_t)p * 2 * width + c];
+    if (out1 != nullptr) s1 += partial[(size_t)p * 2 * width + width + c];
+  }
+  out0[c] += s0;
+  if (out1 != nullptr) out1[c] += s1;
+}
+
+static inline int reduce_parts(int rows) { return std::max(1, std::min(64, (rows + 31) / 32)); }
+
+template <typename T, bool XHAT>
+static hipError_t colsum_launch(const T* dy, const T* x, const float* mean, const float* rstd, float* out_sum,
+                                float* out_xhat, float* scratch, int rows, int width, hipStream_t s) {
+  const int parts = reduce_parts(rows);
+  const int rpp = (rows + parts - 1) / parts;
+  dim3 grid((width + 255) / 256, parts);
+  const double bytes = (double)rows * width * sizeof(T) * (XHAT ? 2 : 1);
+  klaunch(colsum_partial_kernel<T, XHAT>, grid, dim3(256), 0, s, (XHAT ? PK_COLSUM_XHAT : PK_COLSUM) + (int)sizeof(T), bytes, dy, x,
+          mean, rstd, scratch, rows, width, rpp);
+  klaunch(colsum_final_kernel, dim3((width + 255) / 256), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * width * 4 * (XHAT ? 2 : 1),
+          scratch, parts, width, out_sum, XHAT ? out_xhat : (float*)nullptr);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(256) gelu_bwd_kernel(const T* __restrict__ dg, const T* __restrict__ u,
+                                                       T* __restrict__ du, size_t nvec) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < nvec; i += stride) {
+    float a[8], b[8], o[8];
+    Vec8<T>::load(dg + i * 8, a);
+    Vec8<T>::load(u + i * 8, b);
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = a[e] * gelu_grad_f(b[e]);
+    Vec8<T>::store(du + i * 8, o);
+  }
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ p, size_t n) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  const size_t n4 = n >> 2;
+  float4* p4 = reinterpret_cast<float4*>(p);
+  for (size_t j = i; j < n4; j += stride) p4[j] = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (size_t j = (n4 << 2) + i; j < n; j += stride) p[j] = 0.f;
+}
+
+template <typename U>
+__global__ void __launch_bounds__(256) transpose_kernel(const U* __restrict__ in, U* __restrict__ out, int rows, int cols) {
+  __shared__ U tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+#pragma unroll
+  for (int j = 0; j < 32; j += 8) {
+    const int r = r0 + ty + j, c = c0 + tx;
+    if (r < rows && c < cols) tile[ty + j][tx] = in[(size_t)r * cols + c];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 32; j += 8) {
+    const int c = c0 + ty + j, r = r0 + tx;
+    if (r < rows && c < cols) out[(size_t)c * rows + r] = tile[tx][ty + j];
+  }
+}
+
+// Returns after `ticks` ticks of the 100 MHz device wall clock.  One wave; it sleeps between polls
+// and always terminates because the clock is monotonic and `ticks` is bounded by the host.
+__global__ void delay_kernel(long long ticks) {
+  const long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+}
+
+// ------------------------------------------------------------------------------------------------
+// launchers
+// ------------------------------------------------------------------------------------------------
+static inline int nch_for(int H) { const int n = (H + 511) / 512; return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : n <= 8 ? 8 : 16; }
+
+#define KFKB_NCH_SWITCH(NCHV, ...)                                                     \
+  switch (NCHV) {                                                                      \
+    case 1: { constexpr int NCH = 1; __VA_ARGS__; break; }                             \
+    case 2: { constexpr int NCH = 2; __VA_ARGS__; break; }                             \
+    case 4: { constexpr int NCH = 4; __VA_ARGS__; break; }                             \
+    case 8: { constexpr int NCH = 8; __VA_ARGS__; break; }                             \
+    default: { constexpr int NCH = 16; __VA_ARGS__; break; }                           \
+  }
+
+template <typename T>
+static hipError_t ln_fwd_t(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows, int H,
+                           float eps, hipStream_t s) {
+  const dim3 grid((rows + 3) / 4);
+  const double bytes = 2.0 * rows * H * sizeof(T);
+  KFKB_NCH_SWITCH(nch_for(H), klaunch(ln_fwd_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_FWD + NCH * 4 + (int)sizeof(T) / 4, bytes, x, g, b, y, mean, rstd, rows, H, eps));
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_fwd(int dt, const void* x, const void* gamma, const void* beta, void* y, float* mean,
+                         float* rstd, int rows, int H, float eps, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (dt == DT_BF16)
+    return ln_fwd_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, mean, rstd, rows, H, eps, s);
+  return ln_fwd_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd, rows, H, eps, s);
+}
+
+template <typename T>
+static hipError_t ln_bwd_t(const T* dy, const T* x, const float* mean, const float* rstd, const T* gamma,
+                           const T* dres, T* dx, float* dgamma, float* dbeta, float* scratch, int rows, int H,
+                           hipStream_t s) {
+  const dim3 grid((rows + 3) / 4);
+  const double bytes = (dres ? 4.0 : 3.0) * rows * H * sizeof(T);
+  KFKB_NCH_SWITCH(nch_for(H), klaunch(ln_bwd_dx_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_BWD_DX + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, rows, H));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return colsum_launch<T, true>(dy, x, mean, rstd, dbeta, dgamma, scratch, rows, H, s);
+}
+
+hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mean, const float* rstd,
+                         const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta,
+                         float* scratch, int rows, int H, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (dt == DT_BF16)
+    return ln_bwd_t<bf16_t>((const bf16_t*)dy, (const bf16_t*)x, mean, rstd, (const bf16_t*)gamma, (const bf16_t*)dres,
+                            (bf16_t*)dx, dgamma, dbeta, scratch, rows, H, s);
+  return ln_bwd_t<float>((const float*)dy, (const float*)x, mean, rstd, (const float*)gamma, (const float*)dres,
+                         (float*)dx, dgamma, dbeta, scratch, rows, H, s);
+}
+
+hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratch, int rows, int N, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  if (dt == DT_BF16)
+    return colsum_launch<bf16_t, false>((const bf16_t*)dy, nullptr, nullptr, nullptr, out, nullptr, scratch, rows, N, s);
+  return colsum_launch<float, false>((const float*)dy, nullptr, nullptr, nullptr, out, nullptr, scratch, rows, N, s);
+}
+
+hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size_t n, hipStream_t s) {
+  const size_t nvec = n / 8;
+  if (nvec == 0) return hipSuccess;
+  const int grid = (int)std::min<size_t>((nvec + 255) / 256, 8192);
+  if (dt == DT_BF16)
+    klaunch(gelu_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 2, 3.0 * n * 2, (const bf16_t*)dg, (const bf16_t*)u, (bf16_t*)du, nvec);
+  else
+    klaunch(gelu_bwd_kernel<float>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 4, 3.0 * n * 4, (const float*)dg, (const float*)u, (float*)du, nvec);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  const int grid = (int)std::min<size_t>((n / 4 + 255) / 256 + 1, 4096);
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(grid), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int cols, hipStream_t s) {
+  if (rows <= 0 || cols <= 0) return hipSuccess;
+  const dim3 grid((cols + 31) / 32, (rows + 31) / 32);
+  if (dt == DT_BF16)
+    hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, rows, cols);
+  else
+    hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)in, (uint32_t*)out, rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_delay(int64_t ns, hipStream_t s) {
+  if (ns <= 0) return hipSuccess;
+  if (ns > 2000000000LL) ns = 2000000000LL;                   // never spin longer than two seconds
+  hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, s, (long long)(ns / 10));
+  return hipGetLastError();
+}
+
+}  // namespace kfkb

@@ -10,7 +10,6 @@ import torch.nn.functional as TF
 import kfkb_synth as synth
 from oracle import stage_math as sm
 
-torch.set_default_dtype(torch.float64)
 
 
 def _rel(a, b):
@@ -41,7 +40,7 @@ def test_layernorm_bwd_rows_sum_to_zero_and_match_autograd():
     dx1, _, _ = sm.layernorm_bwd(dy, cache, np.ones(12))
     assert np.abs(dx1.sum(-1)).max() < 1e-12          # shift invariance of LN
     xt = torch.from_numpy(x).requires_grad_(); gt = torch.from_numpy(g).requires_grad_()
-    bt = torch.zeros(12, requires_grad=True)
+    bt = torch.zeros(12, dtype=torch.float64, requires_grad=True)
     TF.layer_norm(xt, (12,), gt, bt, 1e-5).backward(torch.from_numpy(dy))
     assert _rel(dx, xt.grad.numpy()) < 1e-12
     assert _rel(dg, gt.grad.numpy()) < 1e-12
