@@ -30,7 +30,9 @@ void prof_key_name(int key, char* out, size_t cap, int* bound) {
     const bool tn = key >= PK_GEMM_TN;
     const int r = key - (tn ? PK_GEMM_TN : PK_GEMM_NT);
     *bound = 0;
-    snprintf(out, cap, "gemm_bf16_%s_kernel<%d,%d,%s>", tn ? "tn" : "nt", r >= 100 ? 256 : 128, r >= 100 ? 256 : 128, epi[r % 100]);
+    const bool staged = r >= 200;
+    const int tile = (r % 200) >= 100 ? 256 : 128;
+    snprintf(out, cap, "gemm_bf16_%s_kernel<%d,%d,%s>", tn ? (staged ? "tn_staged" : "tn") : "nt", tile, tile, epi[r % 100]);
   } else if (key >= PK_ATTN_FWD && key < PK_ATTN_DSUM) {
     const int cls = (key - PK_ATTN_FWD) / 100;
     *bound = 0;

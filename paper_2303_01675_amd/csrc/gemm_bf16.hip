@@ -82,7 +82,55 @@ __device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, i
 }
 
 // ------------------------------------------------------------------------------------------------
-// NT kernel
+// Shared pieces of the two pipelined kernels.
+//
+// Pipeline (per work-group, two LDS stages, ONE barrier per 64-deep slice):
+//   slices are fetched with direct global->LDS loads (global_load_lds_dwordx4: no registers, no LDS
+//   store instructions); a wave instruction fills 1 KiB of LDS linearly, so the swizzle is applied on
+//   the global side: the lane that owns LDS position p fetches the logical chunk that belongs there.
+//   Inside a slice the fragments of k-step s+1 are read while the MFMAs of k-step s issue.  Before the
+//   last k-step of slice t every wave waits for its own loads of slice t+1, all waves meet, the loads
+//   of slice t+2 are issued into the stage slice t occupied (its last fragments are in registers by
+//   then), and the first fragments of slice t+1 are read during the last MFMAs of slice t.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ void dma16(const bf16_t* g, bf16_t* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+// s_waitcnt encodings (gfx9 layout: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
+__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+__device__ __forceinline__ void wait_vm0_lgkm0() { __builtin_amdgcn_s_waitcnt(0x0070); }
+
+template <int TM, int TN>
+__device__ __forceinline__ void mfma_step(f32x16 (&acc)[TM][TN], const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+}
+
+// scheduling hints for one k-step: READS LDS reads (and LOADS direct global->LDS loads) are issued one
+// per MFMA at the front of the step, the remaining MFMAs run at the end and cover the LDS latency of the
+// last reads before the next step needs them.
+template <int I, int SLOTS, int READS, int LOADS>
+__device__ __forceinline__ void interleave_slot() {
+  if constexpr (I < SLOTS) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, (READS + SLOTS - 1 - I) / SLOTS, 0);
+    if constexpr (LOADS > 0) __builtin_amdgcn_sched_group_barrier(0x020, (LOADS + SLOTS - 1 - I) / SLOTS, 0);
+    interleave_slot<I + 1, SLOTS, READS, LOADS>();
+  }
+}
+template <int MFMAS, int READS, int LOADS>
+__device__ __forceinline__ void interleave_hint() {
+  constexpr int SLOTS = READS < MFMAS ? READS : MFMAS - 1;      // MFMAs that carry memory instructions
+  interleave_slot<0, SLOTS, READS, LOADS>();
+  __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - SLOTS, 0);
+}
+
+// ------------------------------------------------------------------------------------------------
+// NT kernel.  LDS tile [rows][64]: 8 chunks of 16 bytes per row, chunk index XOR (row & 7).
 // ------------------------------------------------------------------------------------------------
 template <int BM, int BN, int EPI>
 __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
@@ -91,8 +139,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
                                                            bf16_t* __restrict__ C2, float* __restrict__ Cacc,
                                                            int tiles_m, int tiles_n) {
   constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 accumulator tiles per wave
-  constexpr int LA = BM / 32, LB = BN / 32;          // 16-byte chunks each thread moves per slice
-  extern __shared__ __attribute__((aligned(16))) char smem[];
+  constexpr int GA = BM / 32, GB = BN / 32;          // 8-row groups (1 KiB) each wave fetches per slice
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][BM][64]
   bf16_t* Bs = As + 2 * BM * BK;                                      // [2][BN][64]
 
@@ -103,30 +151,29 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
 
-  const int lc = tid & 7, lr = tid >> 3;             // chunk column, first row of this thread's loads
-  const bf16_t* Ag[LA]; const bf16_t* Bg[LB];
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;   // LDS position (lrow, lane & 7) holds logical chunk lchunk
+  const bf16_t* Ag[GA]; const bf16_t* Bg[GB];
 #pragma unroll
-  for (int i = 0; i < LA; i++) Ag[i] = A + (size_t)min(m0 + lr + 32 * i, M - 1) * K + lc * 8;
+  for (int i = 0; i < GA; i++) Ag[i] = A + (size_t)min(m0 + (i * 4 + wave) * 8 + lrow, M - 1) * K + lchunk * 8;
 #pragma unroll
-  for (int i = 0; i < LB; i++) Bg[i] = B + (size_t)(n0 + lr + 32 * i) * K + lc * 8;
-
-  bf16x8 ra[LA], rb[LB];
-  auto load_global = [&](int kt) {
+  for (int i = 0; i < GB; i++) Bg[i] = B + (size_t)(n0 + (i * 4 + wave) * 8 + lrow) * K + lchunk * 8;
+  auto issue = [&](int kt, int st) {
 #pragma unroll
-    for (int i = 0; i < LA; i++) ra[i] = *reinterpret_cast<const bf16x8*>(Ag[i] + kt * BK);
+    for (int i = 0; i < GA; i++) dma16(Ag[i] + kt * BK, As + st * BM * BK + (i * 4 + wave) * 512);
 #pragma unroll
-    for (int i = 0; i < LB; i++) rb[i] = *reinterpret_cast<const bf16x8*>(Bg[i] + kt * BK);
+    for (int i = 0; i < GB; i++) dma16(Bg[i] + kt * BK, Bs + st * BN * BK + (i * 4 + wave) * 512);
   };
-  auto store_lds = [&](int st) {
+  const int frow = lane & 31, fhalf = lane >> 5;
+  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
 #pragma unroll
-    for (int i = 0; i < LA; i++) {
-      const int r = lr + 32 * i;
-      *reinterpret_cast<bf16x8*>(As + ((st * BM + r) * 8 + (lc ^ (r & 7))) * 8) = ra[i];
+    for (int i = 0; i < TM; i++) {
+      const int r = wm0 + i * 32 + frow;
+      fa[i] = *reinterpret_cast<const bf16x8*>(As + ((st * BM + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
     }
 #pragma unroll
-    for (int i = 0; i < LB; i++) {
-      const int r = lr + 32 * i;
-      *reinterpret_cast<bf16x8*>(Bs + ((st * BN + r) * 8 + (lc ^ (r & 7))) * 8) = rb[i];
+    for (int j = 0; j < TN; j++) {
+      const int r = wn0 + j * 32 + frow;
+      fb[j] = *reinterpret_cast<const bf16x8*>(Bs + ((st * BN + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
     }
   };
 
@@ -139,35 +186,36 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
-  load_global(0);
-  store_lds(0);
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  issue(0, 0);
+  wait_vm0();
   __syncthreads();
-  const int frow = lane & 31, fhalf = lane >> 5;
-  for (int kt = 0; kt < nk; kt++) {
+  if (nk > 1) issue(1, 1);
+  read_frags(0, 0, fa0, fb0);
+  // one slice; `more` = slice kt+2 exists (fetch it), `next` = slice kt+1 exists (start on its fragments)
+  auto slice = [&](int kt, bool more, bool next) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) load_global(kt + 1);
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ks++) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; i++) {
-        const int r = wm0 + i * 32 + frow;
-        fa[i] = *reinterpret_cast<const bf16x8*>(As + ((cur * BM + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
-      }
-#pragma unroll
-      for (int j = 0; j < TN; j++) {
-        const int r = wn0 + j * 32 + frow;
-        fb[j] = *reinterpret_cast<const bf16x8*>(Bs + ((cur * BN + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
-      }
-#pragma unroll
-      for (int i = 0; i < TM; i++)
-#pragma unroll
-        for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) store_lds(cur ^ 1);
+    read_frags(cur, 1, fa1, fb1);
+    mfma_step<TM, TN>(acc, fa0, fb0);
+    interleave_hint<TM * TN, TM + TN, 0>();
+    read_frags(cur, 2, fa0, fb0);
+    mfma_step<TM, TN>(acc, fa1, fb1);
+    interleave_hint<TM * TN, TM + TN, 0>();
+    read_frags(cur, 3, fa1, fb1);
+    mfma_step<TM, TN>(acc, fa0, fb0);
+    interleave_hint<TM * TN, TM + TN, 0>();
+    wait_vm0_lgkm0();                  // own loads of slice kt+1 have landed; last fragments of slice kt are in registers
     __syncthreads();
-  }
+    if (more) issue(kt + 2, cur);
+    if (next) read_frags(cur ^ 1, 0, fa0, fb0);
+    mfma_step<TM, TN>(acc, fa1, fb1);
+    if (more) interleave_hint<TM * TN, TM + TN, GA + GB>();
+    else if (next) interleave_hint<TM * TN, TM + TN, 0>();
+  };
+  int kt = 0;
+  for (; kt + 2 < nk; kt++) slice(kt, true, true);
+  if (kt + 1 < nk) { slice(kt, false, true); kt++; }
+  slice(kt, false, false);
 
 #pragma unroll
   for (int i = 0; i < TM; i++) {
@@ -183,7 +231,130 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
 }
 
 // ------------------------------------------------------------------------------------------------
-// TN kernel: C[M,N] (+)= A[K,M]^T B[K,N]; the reduction axis K (tokens) may be ragged.
+// TN kernel, K % 64 == 0.  LDS tile [64 reduction rows][BM] as it lies in memory, the 16-byte chunk
+// index XOR 2 * (row & 3): the four rows a 16-lane transpose read touches land in four different
+// 32-byte slots of a 128-byte bank window.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ bf16x8 lds_tr_pair(const bf16_t* p, int second_offset) {
+  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + second_offset));
+  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  u.s.a = lo; u.s.b = hi;
+  return u.v;
+}
+
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                           const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+                                                           float* __restrict__ Cacc, int tiles_m, int tiles_n) {
+  constexpr int TM = BM / 64, TN = BN / 64;
+  constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
+  constexpr int RA = 64 / CA, RB = 64 / CB;          // tile rows one wave instruction (1 KiB) covers
+  constexpr int GA = BM / 32, GB = BN / 32;          // wave instructions per wave per slice
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][64][BM]
+  bf16_t* Bs = As + 2 * BK * BM;                                      // [2][64][BN]
+
+  int tm, tn; bool valid;
+  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
+  if (!valid) return;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+
+  // wave instruction g (0 .. 4*GA) of a slice covers tile rows g*RA .. +RA; lane -> (row, physical chunk)
+  const bf16_t* Ag[GA]; const bf16_t* Bg[GB];
+#pragma unroll
+  for (int i = 0; i < GA; i++) {
+    const int row = (i * 4 + wave) * RA + lane / CA, pc = lane % CA;
+    Ag[i] = A + (size_t)row * M + m0 + (pc ^ (2 * (row & 3))) * 8;
+  }
+#pragma unroll
+  for (int i = 0; i < GB; i++) {
+    const int row = (i * 4 + wave) * RB + lane / CB, pc = lane % CB;
+    Bg[i] = B + (size_t)row * N + n0 + (pc ^ (2 * (row & 3))) * 8;
+  }
+  auto issue = [&](int kt, int st) {
+#pragma unroll
+    for (int i = 0; i < GA; i++) dma16(Ag[i] + (size_t)kt * BK * M, As + st * BK * BM + (i * 4 + wave) * 512);
+#pragma unroll
+    for (int i = 0; i < GB; i++) dma16(Bg[i] + (size_t)kt * BK * N, Bs + st * BK * BN + (i * 4 + wave) * 512);
+  };
+  // transpose-read geometry: 16-lane group g covers columns (g & 1) * 16 .. + 16 and the reduction half
+  // g >> 1; inside the group lane j points at row j / 4, columns (j % 4) * 4 .. + 4.
+  const int g16 = lane >> 4, j16 = lane & 15;
+  const int tr_row = (g16 >> 1) * 8 + (j16 >> 2);
+  const int tr_col = (g16 & 1) * 16 + (j16 & 3) * 4;
+  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
+    const int row = ks * 16 + tr_row, sw = 2 * (row & 3);
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      const int col = wm0 + i * 32 + tr_col;
+      fa[i] = lds_tr_pair(As + (st * BK + row) * BM + (((col >> 3) ^ sw) << 3) + (col & 7), 4 * BM);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; j++) {
+      const int col = wn0 + j * 32 + tr_col;
+      fb[j] = lds_tr_pair(Bs + (st * BK + row) * BN + (((col >> 3) ^ sw) << 3) + (col & 7), 4 * BN);
+    }
+  };
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+
+  const int nk = K / BK;
+  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  issue(0, 0);
+  wait_vm0();
+  __syncthreads();
+  if (nk > 1) issue(1, 1);
+  read_frags(0, 0, fa0, fb0);
+  // one slice; `more` = slice kt+2 exists (fetch it), `next` = slice kt+1 exists (start on its fragments)
+  auto slice = [&](int kt, bool more, bool next) {
+    const int cur = kt & 1;
+    read_frags(cur, 1, fa1, fb1);
+    mfma_step<TM, TN>(acc, fa0, fb0);
+    interleave_hint<TM * TN, 2 * (TM + TN), 0>();
+    read_frags(cur, 2, fa0, fb0);
+    mfma_step<TM, TN>(acc, fa1, fb1);
+    interleave_hint<TM * TN, 2 * (TM + TN), 0>();
+    read_frags(cur, 3, fa1, fb1);
+    mfma_step<TM, TN>(acc, fa0, fb0);
+    interleave_hint<TM * TN, 2 * (TM + TN), 0>();
+    wait_vm0_lgkm0();                  // own loads of slice kt+1 have landed; last fragments of slice kt are in registers
+    __syncthreads();
+    if (more) issue(kt + 2, cur);
+    if (next) read_frags(cur ^ 1, 0, fa0, fb0);
+    mfma_step<TM, TN>(acc, fa1, fb1);
+    if (more) interleave_hint<TM * TN, 2 * (TM + TN), GA + GB>();
+    else if (next) interleave_hint<TM * TN, 2 * (TM + TN), 0>();
+  };
+  int kt = 0;
+  for (; kt + 2 < nk; kt++) slice(kt, true, true);
+  if (kt + 1 < nk) { slice(kt, false, true); kt++; }
+  slice(kt, false, false);
+
+  const int frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int m = m0 + wm0 + i * 32 + frow;
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++)
+        epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, nullptr, nullptr, C, nullptr, Cacc);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// TN kernel, register-staged variant: accepts a ragged reduction length K (zero-fills the tail).
+// Tiles are stored [reduction row][BM + 16].
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* p, int row_stride) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -195,7 +366,7 @@ __device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* p, int row_stride) {
 }
 
 template <int BM, int BN, int EPI>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+__global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                            float* __restrict__ Cacc, int tiles_m, int tiles_n) {
   constexpr int TM = BM / 64, TN = BN / 64;
@@ -335,10 +506,28 @@ static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
 }
 
 template <int BM, int BN, int EPI>
-static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
+static hipError_t launch_tn_staged(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   const size_t smem = (size_t)2 * BK * (BM + 16 + BN + 16) * sizeof(bf16_t);
+  auto kern = gemm_bf16_tn_staged_kernel<BM, BN, EPI>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + 200 + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
+          (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, g.Cacc, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int EPI>
+static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
+  if (g.K % BK != 0) return launch_tn_staged<BM, BN, EPI>(g, s);
+  const int tiles_m = g.M / BM, tiles_n = g.N / BN;
+  const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
+  const size_t smem = (size_t)2 * BK * (BM + BN) * sizeof(bf16_t);
   auto kern = gemm_bf16_tn_kernel<BM, BN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
