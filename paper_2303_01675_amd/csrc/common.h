@@ -123,6 +123,7 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);   // NT and TN only
+hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s);   // up to 4 wgrads, one launch
 const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported
 
 hipError_t launch_attention_fwd_f32(const float* qkv, float* o, float* lse, int b, int T, int H, int heads,

@@ -30,6 +30,7 @@ void prof_key_name(int key, char* out, size_t cap, int* bound) {
     const bool tn = key >= PK_GEMM_TN;
     const int r = key - (tn ? PK_GEMM_TN : PK_GEMM_NT);
     *bound = 0;
+    if (tn && r == 300) { snprintf(out, cap, "gemm_bf16_tn_grouped_kernel<128,128>"); return; }
     const bool staged = r >= 200;
     const int tile = (r % 200) >= 100 ? 256 : 128;
     snprintf(out, cap, "gemm_bf16_%s_kernel<%d,%d,%s>", tn ? (staged ? "tn_staged" : "tn") : "nt", tile, tile, epi[r % 100]);
@@ -335,32 +336,48 @@ int compute_backward(int slot, const char* x_in, const char* dy_in, char* dx_out
   char* d_o = s.t_n[0];          // dc is dead once dx1 exists
   char* da = s.t_n[0];           // d_o is dead once dqkv exists
   char* dqkv = s.t_3n;
+  // the four weight-gradient products of a block are issued together once their operands exist (all of
+  // them outlive the block's backward): one launch fills the chip where each alone would not
+  GemmArgs wg[4];
+  auto wgrad = [&](int i, int in, int out, const void* x, const void* dyv, float* acc) {
+    wg[i] = GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, in, out, s.m, x, dyv, nullptr, nullptr, nullptr, nullptr, acc};
+  };
   for (int l = s.L - 1; l >= 0; l--) {
     StashView v = view(s, slot, l);
     const char* x = (l == 0) ? x_in : view(s, slot, l - 1).y;
     char* dx = (l == 0) ? dx_out : s.t_n[2 + (l & 1)];
     // y = x1 + g W2 + b2
     HIPCHK(launch_colsum_accum(s.dt, dy, gptr(s, l, s.po.b_2), s.red, s.m, s.H, s.sc));
-    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.F, s.H, s.m, v.gact, dy, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_2)));
+    wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
     // u = c W1 + b1
     HIPCHK(launch_colsum_accum(s.dt, du, gptr(s, l, s.po.b_1), s.red, s.m, s.F, s.sc));
-    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, s.F, s.m, v.c, du, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_1)));
+    wgrad(1, s.H, s.F, v.c, du, gptr(s, l, s.po.w_1));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr));
     // c = LN2(x1), plus the residual path
     HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), s.red, s.m, s.H, s.sc));
     // x1 = x + o Wo + bo
     HIPCHK(launch_colsum_accum(s.dt, dx1, gptr(s, l, s.po.b_o), s.red, s.m, s.H, s.sc));
-    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, s.H, s.m, v.o, dx1, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_o)));
+    wgrad(3, s.H, s.H, v.o, dx1, gptr(s, l, s.po.w_o));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr));
     // o = attention(qkv)
     TRY(attention_bwd(s, v.qkv, v.o, d_o, v.lse, dqkv));
     // qkv = a Wqkv + bqkv
     HIPCHK(launch_colsum_accum(s.dt, dqkv, gptr(s, l, s.po.b_qkv), s.red, s.m, 3 * s.H, s.sc));
-    TRY(gemm(s, KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, 3 * s.H, s.m, v.a, dqkv, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_qkv)));
+    wgrad(0, s.H, 3 * s.H, v.a, dqkv, gptr(s, l, s.po.w_qkv));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
     // a = LN1(x), plus the residual path
     HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), s.red, s.m, s.H, s.sc));
+    // du, dx1, dqkv and this block's dy are still intact here; the next block overwrites them
+    if (s.dt == DT_BF16) {
+      for (int i = 0; i < 4; i++) {
+        const char* why = gemm_bf16_check(wg[i]);
+        if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
+      }
+      HIPCHK(launch_gemm_bf16_tn_group(wg, 4, s.sc));
+    } else {
+      for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], s.sc));
+    }
     dy = dx;
   }
   return 0;

@@ -27,11 +27,8 @@ namespace kfkb {
 
 constexpr int BK = 64;
 
-__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool& valid) {
-  const int nt = tiles_m * tiles_n;
-  const int per_xcd = (nt + 7) / 8;
-  const int t = (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
-  valid = t < nt;
+// position t of the tile order -> tile coordinates: groups of four tile-rows, column by column
+__device__ __forceinline__ void tile_from_linear(int t, int tiles_m, int tiles_n, int& tm, int& tn) {
   constexpr int GM = 4;
   const int group = t / (GM * tiles_n);
   const int first_m = group * GM;
@@ -39,6 +36,16 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
   const int in_group = t - group * GM * tiles_n;
   tm = first_m + in_group % gsz;
   tn = in_group / gsz;
+}
+// block -> position in the tile order such that every XCD owns a contiguous run of it
+__device__ __forceinline__ int linear_of_block(int total_tiles) {
+  const int per_xcd = (total_tiles + 7) / 8;
+  return (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+}
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool& valid) {
+  const int t = linear_of_block(tiles_m * tiles_n);
+  valid = t < tiles_m * tiles_n;
+  tile_from_linear(t, tiles_m, tiles_n, tm, tn);
 }
 
 template <int EPI>
@@ -245,20 +252,14 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const bf16_t* p, int second_offset
 }
 
 template <int BM, int BN, int EPI>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                           const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
-                                                           float* __restrict__ Cacc, int tiles_m, int tiles_n) {
+__device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                        bf16_t* __restrict__ C, float* __restrict__ Cacc, int tm, int tn, char* smem) {
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
   constexpr int RA = 64 / CA, RB = 64 / CB;          // tile rows one wave instruction (1 KiB) covers
   constexpr int GA = BM / 32, GB = BN / 32;          // wave instructions per wave per slice
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
   bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][64][BM]
   bf16_t* Bs = As + 2 * BK * BM;                                      // [2][64][BN]
-
-  int tm, tn; bool valid;
-  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
-  if (!valid) return;
   const int m0 = tm * BM, n0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
@@ -350,6 +351,36 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
       for (int q = 0; q < 4; q++)
         epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, nullptr, nullptr, C, nullptr, Cacc);
   }
+}
+
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
+                                                           const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+                                                           float* __restrict__ Cacc, int tiles_m, int tiles_n) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int tm, tn; bool valid;
+  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
+  if (!valid) return;
+  tn_tile<BM, BN, EPI>(M, N, K, A, B, C, Cacc, tm, tn, smem);
+}
+
+// Several weight-gradient products that share the reduction length K (the token axis) in one launch:
+// a backward pass of one block has four of them, each too small to fill the chip on its own.
+struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const bf16_t* A; const bf16_t* B; float* Cacc; };
+struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
+
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int t = linear_of_block(grp.total_tiles);
+  if (t >= grp.total_tiles) return;
+  int i = 0;
+#pragma unroll
+  for (int q = 1; q < 4; q++) if (q < grp.count && t >= grp.p[q].first_tile) i = q;
+  const TnProblem pr = grp.p[i];
+  int tm, tn;
+  tile_from_linear(t - pr.first_tile, pr.tiles_m, pr.tiles_n, tm, tn);
+  tn_tile<BM, BN, KFKB_EPI_ACCUM>(pr.M, pr.N, grp.K, pr.A, pr.B, nullptr, pr.Cacc, tm, tn, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -537,6 +568,43 @@ static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
   }
   klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
           (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, g.Cacc, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  bool groupable = n <= 4;
+  for (int i = 0; i < n; i++)
+    groupable = groupable && g[i].kind == KFKB_GEMM_TN && g[i].epilogue == KFKB_EPI_ACCUM && g[i].K == g[0].K &&
+                g[i].K % BK == 0 && g[i].M % 128 == 0 && g[i].N % 128 == 0;
+  if (!groupable) {
+    for (int i = 0; i < n; i++) {
+      hipError_t e = launch_gemm_bf16(g[i], s);
+      if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+  }
+  constexpr int BM = 128, BN = 128;
+  TnGroup grp{};
+  grp.count = n; grp.K = g[0].K;
+  double flops = 0;
+  for (int i = 0; i < n; i++) {
+    TnProblem& p = grp.p[i];
+    p.M = g[i].M; p.N = g[i].N; p.tiles_m = g[i].M / BM; p.tiles_n = g[i].N / BN; p.first_tile = grp.total_tiles;
+    p.A = (const bf16_t*)g[i].A; p.B = (const bf16_t*)g[i].B; p.Cacc = g[i].Cacc;
+    grp.total_tiles += p.tiles_m * p.tiles_n;
+    flops += 2.0 * g[i].M * g[i].N * g[i].K;
+  }
+  const int grid = ((grp.total_tiles + 7) / 8) * 8;
+  const size_t smem = (size_t)2 * BK * (BM + BN) * sizeof(bf16_t);
+  auto kern = gemm_bf16_tn_grouped_kernel<BM, BN>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + 300, flops, grp);
   return hipGetLastError();
 }
 

@@ -163,17 +163,29 @@ __global__ void __launch_bounds__(256) colsum_partial_kernel(const T* __restrict
   }
 }
 
-__global__ void colsum_final_kernel(const float* __restrict__ partial, int parts, int width, float* __restrict__ out0,
-                                    float* __restrict__ out1) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= width) return;
+// 32 columns per block; 8 threads share a column, each adds every 8th part in ascending order, and the
+// eight partial sums meet in LDS in fixed order: the result does not depend on timing.
+__global__ void __launch_bounds__(256) colsum_final_kernel(const float* __restrict__ partial, int parts, int width,
+                                                           float* __restrict__ out0, float* __restrict__ out1) {
+  __shared__ float red[2][8][32];
+  const int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
   float s0 = 0.f, s1 = 0.f;
-  for (int p = 0; p < parts; p++) {
-    s0 += partial[(size_t)p * 2 * width + c];
-    if (out1 != nullptr) s1 += partial[(size_t)p * 2 * width + width + c];
+  if (c < width) {
+    for (int p = pl; p < parts; p += 8) {
+      s0 += partial[(size_t)p * 2 * width + c];
+      if (out1 != nullptr) s1 += partial[(size_t)p * 2 * width + width + c];
+    }
   }
-  out0[c] += s0;
-  if (out1 != nullptr) out1[c] += s1;
+  red[0][pl][cl] = s0; red[1][pl][cl] = s1;
+  __syncthreads();
+  if (pl == 0 && c < width) {
+    float a = 0.f, b = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) { a += red[0][j][cl]; b += red[1][j][cl]; }
+    out0[c] += a;
+    if (out1 != nullptr) out1[c] += b;
+  }
 }
 
 static inline int reduce_parts(int rows) { return std::max(1, std::min(64, (rows + 31) / 32)); }
@@ -187,7 +199,7 @@ static hipError_t colsum_launch(const T* dy, const T* x, const float* mean, cons
   const double bytes = (double)rows * width * sizeof(T) * (XHAT ? 2 : 1);
   klaunch(colsum_partial_kernel<T, XHAT>, grid, dim3(256), 0, s, (XHAT ? PK_COLSUM_XHAT : PK_COLSUM) + (int)sizeof(T), bytes, dy, x,
           mean, rstd, scratch, rows, width, rpp);
-  klaunch(colsum_final_kernel, dim3((width + 255) / 256), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * width * 4 * (XHAT ? 2 : 1),
+  klaunch(colsum_final_kernel, dim3((width + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * width * 4 * (XHAT ? 2 : 1),
           scratch, parts, width, out_sum, XHAT ? out_xhat : (float*)nullptr);
   return hipGetLastError();
 }
