@@ -19,7 +19,7 @@
 //   Reduction slot s of lane half hh in a 16-row sub-block corresponds to streamed row
 //   (s / 4) * 8 + hh * 4 + s % 4 on both operands.
 //
-// LDS tiles are [64 rows][D] with the 16-byte chunk index XOR-ed with (row & 7).
+// LDS tiles are [64 rows][D] with the 16-byte chunk index XOR-ed with a function of the row (TileIO::sw).
 #include "common.h"
 
 namespace kfkb {
@@ -30,6 +30,15 @@ constexpr float kLn2 = 0.6931471805599453f;
 template <int D>
 struct TileIO {
   static constexpr int CH = D / 8;            // 16-byte chunks per row
+  // Swizzle: the chunk index is XOR-ed with sw(row).  The LDS has 64 banks (256 bytes per clock).  A 16-byte
+  // fragment read serves 16 consecutive rows per clock and needs them on 16 different chunk slots of the
+  // 256-byte window; a transpose read serves 64 contiguous bytes of 4 consecutive rows per clock and needs
+  // those on 4 different 64-byte slots.  D = 64 (two rows per window): sw = row bit 1 -> chunk bit 2, row bits
+  // 3:2 -> chunk bits 1:0.  D = 128 (one row per window): sw = row bits 1:0 -> chunk bits 3:2, row bits 3:2 ->
+  // chunk bits 1:0.
+  static __device__ __forceinline__ int sw(int row) {
+    return D == 64 ? ((((row >> 1) & 1) << 2) | ((row >> 2) & 3)) : (((row & 3) << 2) | ((row >> 2) & 3));
+  }
   static constexpr int NL = D / 32;           // chunks per thread for a 64-row tile
   // rows row0 .. row0+63 of a [*, ld] matrix, clamped to row_max, columns col0 .. col0+D
   static __device__ __forceinline__ void load(bf16x8 (&r)[NL], const bf16_t* __restrict__ src, size_t ld, int row0,
@@ -46,19 +55,20 @@ struct TileIO {
 #pragma unroll
     for (int i = 0; i < NL; i++) {
       const int row = threadIdx.x / CH + (256 / CH) * i;
-      *reinterpret_cast<bf16x8*>(tile + (row * CH + (c ^ (row & 7))) * 8) = r[i];
+      *reinterpret_cast<bf16x8*>(tile + (row * CH + (c ^ sw(row))) * 8) = r[i];
     }
   }
   // 8 reduction-contiguous values of row `row`, chunk `chunk`
   static __device__ __forceinline__ bf16x8 frag(const bf16_t* tile, int row, int chunk) {
-    return *reinterpret_cast<const bf16x8*>(tile + (row * CH + (chunk ^ (row & 7))) * 8);
+    return *reinterpret_cast<const bf16x8*>(tile + (row * CH + (chunk ^ sw(row))) * 8);
   }
   // transpose read: this lane points at (row, col .. col+4) and (row + 8, col .. col+4)
   static __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* tile, int row, int col) {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const bf16_t* p = tile + (row * CH + ((col >> 3) ^ (row & 7))) * 8 + (col & 7);
+    const bf16_t* p = tile + (row * CH + ((col >> 3) ^ sw(row))) * 8 + (col & 7);
+    const bf16_t* p8 = tile + ((row + 8) * CH + ((col >> 3) ^ sw(row + 8))) * 8 + (col & 7);
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 8 * D));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p8);
     union { struct { s16x4 a, b; } s; bf16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
@@ -77,6 +87,10 @@ __device__ __forceinline__ f32x16 zero16() {
   for (int e = 0; e < 16; e++) z[e] = 0.f;
   return z;
 }
+// 2^x through the hardware instruction alone: arguments here are <= 0 (or -inf), results that would be
+// denormal flush to zero, which is what a softmax weight that small should be
+__device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp2f(x); }
+
 // streamed-row offset (inside a 32-row tile) of accumulator register r for lane half hh
 __device__ __forceinline__ int acc_row(int r, int hh) { return (r >> 2) * 8 + hh * 4 + (r & 3); }
 
@@ -137,35 +151,41 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
 #pragma unroll
         for (int ds = 0; ds < D / 16; ds++)
           st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt], 0, 0, 0);
+      // masking is needed only where the tile crosses the diagonal or the end of the sequence
+      if (j0 + 63 >= T || (causal && j0 + 63 > qw0)) {
+#pragma unroll
+        for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int j = j0 + jt * 32 + acc_row(r, hh);
+            if (j >= T || (causal && j > i)) st[jt][r] = -INFINITY;
+          }
+      }
       float mx = -INFINITY;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int j = j0 + jt * 32 + acc_row(r, hh);
-          float t = st[jt][r] * scale_log2;
-          if (j >= T || (causal && j > i)) t = -INFINITY;
-          st[jt][r] = t;
-          mx = fmaxf(mx, t);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        for (int r = 0; r < 16; r++) mx = fmaxf(mx, st[jt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;      // scale > 0: max commutes with it
       const float mnew = fmaxf(fmaxf(mrun, mx), -1e30f);
-      const float alpha = exp2f(mrun - mnew);
+      const float alpha = exp2_raw(mrun - mnew);
       float ps = 0.f;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-          const float p = exp2f(st[jt][r] - mnew);
+          const float p = exp2_raw(fmaf(st[jt][r], scale_log2, -mnew));
           st[jt][r] = p;
           ps += p;
         }
       lsum = lsum * alpha + ps;
       mrun = mnew;
+      if (__any(alpha != 1.0f)) {                    // the running maximum settles after a few tiles
 #pragma unroll
-      for (int t = 0; t < D / 32; t++)
+        for (int t = 0; t < D / 32; t++)
 #pragma unroll
-        for (int e = 0; e < 16; e++) oacc[t][e] *= alpha;
+          for (int e = 0; e < 16; e++) oacc[t][e] *= alpha;
+      }
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
@@ -262,13 +282,20 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
           st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt], 0, 0, 0);
           dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Vt, jt * 32 + l32, ds * 2 + hh), dof[ds], dp[jt], 0, 0, 0);
         }
+      if (j0 + 63 >= T || (causal && j0 + 63 > qw0)) {
+#pragma unroll
+        for (int jt = 0; jt < 2; jt++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int j = j0 + jt * 32 + acc_row(r, hh);
+            if (j >= T || (causal && j > i)) st[jt][r] = -INFINITY;
+          }
+      }
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-          const int j = j0 + jt * 32 + acc_row(r, hh);
-          float p = exp2f(st[jt][r] * scale_log2 - lse_i);
-          if (j >= T || (causal && j > i)) p = 0.f;
+          const float p = exp2_raw(fmaf(st[jt][r], scale_log2, -lse_i));
           st[jt][r] = p * (dp[jt][r] - dsum_i);
         }
 #pragma unroll
@@ -380,16 +407,29 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
           st[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Qt, it * 32 + l32, ds * 2 + hh), kf[ds], st[it], 0, 0, 0);
           dp[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Ot, it * 32 + l32, ds * 2 + hh), vf[ds], dp[it], 0, 0, 0);
         }
+      if (i0 + 63 >= T || jw0 + 31 >= T || (causal && jw0 + 31 > i0)) {
+#pragma unroll
+        for (int it = 0; it < 2; it++)
+#pragma unroll
+          for (int r = 0; r < 16; r++) {
+            const int i = i0 + it * 32 + acc_row(r, hh);
+            if (i >= T || j >= T || (causal && j > i)) st[it][r] = -INFINITY;
+          }
+      }
 #pragma unroll
       for (int it = 0; it < 2; it++)
 #pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const int il = it * 32 + acc_row(r, hh);
-          const int i = i0 + il;
-          float p = exp2f(st[it][r] * scale_log2 - Ls[cur * 64 + il]);
-          if (i >= T || j >= T || (causal && j > i)) p = 0.f;
-          st[it][r] = p;
-          dp[it][r] = p * (dp[it][r] - Ss[cur * 64 + il]);
+        for (int q = 0; q < 4; q++) {                // four consecutive query rows per register quad
+          const int il = it * 32 + q * 8 + hh * 4;
+          const float4 l4 = *reinterpret_cast<const float4*>(Ls + cur * 64 + il);
+          const float4 s4 = *reinterpret_cast<const float4*>(Ss + cur * 64 + il);
+          const float lv[4] = {l4.x, l4.y, l4.z, l4.w}, sv[4] = {s4.x, s4.y, s4.z, s4.w};
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            const float p = exp2_raw(fmaf(st[it][q * 4 + e], scale_log2, -lv[e]));
+            st[it][q * 4 + e] = p;
+            dp[it][q * 4 + e] = p * (dp[it][q * 4 + e] - sv[e]);
+          }
         }
 #pragma unroll
       for (int it = 0; it < 2; it++)

@@ -7,9 +7,9 @@
 //
 // One work-group = 256 threads = 2 x 2 waves computes a BM x BN tile in 64-deep slices.  Slices go
 // global -> registers -> LDS (two LDS stages, one barrier per slice).  NT tiles are stored
-// [row][64] with the 16-byte chunk index XOR-ed by (row & 7) so that both the 16-byte stores and
-// the 16-byte fragment reads are bank-conflict free.  TN tiles are stored as they lie in memory,
-// [reduction row][BM + 16], and fragments are fetched with the LDS transpose read
+// [row][64] with the 16-byte chunk index XOR-ed by ((row >> 1) & 7) so that the 16-byte fragment reads
+// are bank-conflict free.  TN tiles are stored as they lie in memory,
+// [reduction row][BM] (XOR-swizzled), and fragments are fetched with the LDS transpose read
 // (ds_read_b64_tr_b16), which hands every lane four reduction-consecutive values of its column.
 //
 // The MFMA is issued with its operands swapped (A operand <- B tile, B operand <- A tile): the
@@ -22,6 +22,7 @@
 // the tile order, and that order walks groups of four tile-rows column by column.
 #include "common.h"
 #include "../../include/kfkb.h"
+#include <cstdlib>
 
 namespace kfkb {
 
@@ -91,7 +92,9 @@ __device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, i
 // ------------------------------------------------------------------------------------------------
 // Shared pieces of the two pipelined kernels.
 //
-// Pipeline (per work-group, two LDS stages, ONE barrier per 64-deep slice):
+// Pipeline (per work-group, NS LDS stages, ONE barrier per 64-deep slice; slice j lives in stage j % NS and
+// is requested NS - 1 slices ahead: a 128 x 128 tile spends only ~0.2 us of MFMA time on a slice, far less
+// than a trip to L2 / HBM, so several slices have to be in flight):
 //   slices are fetched with direct global->LDS loads (global_load_lds_dwordx4: no registers, no LDS
 //   store instructions); a wave instruction fills 1 KiB of LDS linearly, so the swizzle is applied on
 //   the global side: the lane that owns LDS position p fetches the logical chunk that belongs there.
@@ -105,8 +108,13 @@ __device__ __forceinline__ void dma16(const bf16_t* g, bf16_t* lds_wave_base) {
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
 // s_waitcnt encodings (gfx9 layout: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
-__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
-__device__ __forceinline__ void wait_vm0_lgkm0() { __builtin_amdgcn_s_waitcnt(0x0070); }
+// wait until at most N vector-memory operations (here: direct loads into LDS) of this wave are outstanding;
+// LGKM0 additionally waits for all LDS reads
+template <int N, bool LGKM0>
+__device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | (LGKM0 ? 0 : 0x0F00));
+}
 
 template <int TM, int TN>
 __device__ __forceinline__ void mfma_step(f32x16 (&acc)[TM][TN], const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
@@ -137,9 +145,11 @@ __device__ __forceinline__ void interleave_hint() {
 }
 
 // ------------------------------------------------------------------------------------------------
-// NT kernel.  LDS tile [rows][64]: 8 chunks of 16 bytes per row, chunk index XOR (row & 7).
+// NT kernel.  LDS tile [rows][64]: 8 chunks of 16 bytes per row, chunk index XOR ((row >> 1) & 7): a 16-byte
+// fragment read serves 16 lanes (16 consecutive rows) per clock from 64 banks, and two rows fill one 256-byte
+// bank window, so the 16 rows have to land on 16 different chunk slots of it.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int NS>
 __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
                                                            const bf16_t* __restrict__ residual, bf16_t* __restrict__ C,
@@ -148,8 +158,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
   constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 accumulator tiles per wave
   constexpr int GA = BM / 32, GB = BN / 32;          // 8-row groups (1 KiB) each wave fetches per slice
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][BM][64]
-  bf16_t* Bs = As + 2 * BM * BK;                                      // [2][BN][64]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [NS][BM][64]
+  bf16_t* Bs = As + NS * BM * BK;                                     // [NS][BN][64]
 
   int tm, tn; bool valid;
   tile_of_block(tiles_m, tiles_n, tm, tn, valid);
@@ -158,7 +168,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
 
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ lrow;   // LDS position (lrow, lane & 7) holds logical chunk lchunk
+  // LDS position (row, lane & 7) holds logical chunk (lane & 7) ^ ((row >> 1) & 7); wave w fetches the 8-row groups
+  // i*4 + w, whose rows start at multiples of 8, so ((row >> 1) & 7) = 4 * (w & 1) + (lrow >> 1)
+  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (((wave & 1) << 2) | (lrow >> 1));
   const bf16_t* Ag[GA]; const bf16_t* Bg[GB];
 #pragma unroll
   for (int i = 0; i < GA; i++) Ag[i] = A + (size_t)min(m0 + (i * 4 + wave) * 8 + lrow, M - 1) * K + lchunk * 8;
@@ -175,12 +187,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
 #pragma unroll
     for (int i = 0; i < TM; i++) {
       const int r = wm0 + i * 32 + frow;
-      fa[i] = *reinterpret_cast<const bf16x8*>(As + ((st * BM + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
+      fa[i] = *reinterpret_cast<const bf16x8*>(As + ((st * BM + r) * 8 + ((ks * 2 + fhalf) ^ ((r >> 1) & 7))) * 8);
     }
 #pragma unroll
     for (int j = 0; j < TN; j++) {
       const int r = wn0 + j * 32 + frow;
-      fb[j] = *reinterpret_cast<const bf16x8*>(Bs + ((st * BN + r) * 8 + ((ks * 2 + fhalf) ^ (r & 7))) * 8);
+      fb[j] = *reinterpret_cast<const bf16x8*>(Bs + ((st * BN + r) * 8 + ((ks * 2 + fhalf) ^ ((r >> 1) & 7))) * 8);
     }
   };
 
@@ -193,15 +205,17 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
+  constexpr int LPS = GA + GB;                       // loads each wave issues per slice
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  issue(0, 0);
-  wait_vm0();
+#pragma unroll
+  for (int j = 0; j < NS - 1; j++)
+    if (j < nk) issue(j, j);
+  if (nk >= NS - 1) wait_vm<(NS - 2) * LPS, false>(); else wait_vm<0, false>();   // slice 0 has landed
   __syncthreads();
-  if (nk > 1) issue(1, 1);
+  if (NS - 1 < nk) issue(NS - 1, NS - 1);
   read_frags(0, 0, fa0, fb0);
-  // one slice; `more` = slice kt+2 exists (fetch it), `next` = slice kt+1 exists (start on its fragments)
-  auto slice = [&](int kt, bool more, bool next) {
-    const int cur = kt & 1;
+  // one slice; `more` = slice kt+NS exists (request it), `next` = slice kt+1 exists (start on its fragments)
+  auto slice = [&](int kt, int cur, bool more, bool next) {
     read_frags(cur, 1, fa1, fb1);
     mfma_step<TM, TN>(acc, fa0, fb0);
     interleave_hint<TM * TN, TM + TN, 0>();
@@ -211,18 +225,19 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
     read_frags(cur, 3, fa1, fb1);
     mfma_step<TM, TN>(acc, fa0, fb0);
     interleave_hint<TM * TN, TM + TN, 0>();
-    wait_vm0_lgkm0();                  // own loads of slice kt+1 have landed; last fragments of slice kt are in registers
+    // own loads of slice kt+1 have landed; the last fragments of slice kt are in registers
+    if (more) wait_vm<(NS - 2) * LPS, true>(); else wait_vm<0, true>();
     __syncthreads();
-    if (more) issue(kt + 2, cur);
-    if (next) read_frags(cur ^ 1, 0, fa0, fb0);
+    if (more) issue(kt + NS, cur);
+    if (next) read_frags(cur + 1 == NS ? 0 : cur + 1, 0, fa0, fb0);
     mfma_step<TM, TN>(acc, fa1, fb1);
     if (more) interleave_hint<TM * TN, TM + TN, GA + GB>();
     else if (next) interleave_hint<TM * TN, TM + TN, 0>();
   };
-  int kt = 0;
-  for (; kt + 2 < nk; kt++) slice(kt, true, true);
-  if (kt + 1 < nk) { slice(kt, false, true); kt++; }
-  slice(kt, false, false);
+  int kt = 0, cur = 0;
+  for (; kt + NS < nk; kt++) { slice(kt, cur, true, true); cur = cur + 1 == NS ? 0 : cur + 1; }
+  for (; kt + 1 < nk; kt++) { slice(kt, cur, false, true); cur = cur + 1 == NS ? 0 : cur + 1; }
+  slice(kt, cur, false, false);
 
 #pragma unroll
   for (int i = 0; i < TM; i++) {
@@ -239,8 +254,9 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
 
 // ------------------------------------------------------------------------------------------------
 // TN kernel, K % 64 == 0.  LDS tile [64 reduction rows][BM] as it lies in memory, the 16-byte chunk
-// index XOR 2 * (row & 3): the four rows a 16-lane transpose read touches land in four different
-// 32-byte slots of a 128-byte bank window.
+// index XOR 4 * (row & 3).  The LDS of gfx950 has 64 banks (256 bytes per clock): a transpose read serves
+// 32 lanes per clock, i.e. 64 contiguous bytes of each of four consecutive rows, and the XOR puts those four
+// rows into the four different 64-byte slots of the 256-byte bank window.
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ bf16x8 lds_tr_pair(const bf16_t* p, int second_offset) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -251,15 +267,15 @@ __device__ __forceinline__ bf16x8 lds_tr_pair(const bf16_t* p, int second_offset
   return u.v;
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int NS>
 __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                         bf16_t* __restrict__ C, float* __restrict__ Cacc, int tm, int tn, char* smem) {
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
   constexpr int RA = 64 / CA, RB = 64 / CB;          // tile rows one wave instruction (1 KiB) covers
   constexpr int GA = BM / 32, GB = BN / 32;          // wave instructions per wave per slice
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][64][BM]
-  bf16_t* Bs = As + 2 * BK * BM;                                      // [2][64][BN]
+  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [NS][64][BM]
+  bf16_t* Bs = As + NS * BK * BM;                                     // [NS][64][BN]
   const int m0 = tm * BM, n0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
@@ -269,12 +285,12 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
 #pragma unroll
   for (int i = 0; i < GA; i++) {
     const int row = (i * 4 + wave) * RA + lane / CA, pc = lane % CA;
-    Ag[i] = A + (size_t)row * M + m0 + (pc ^ (2 * (row & 3))) * 8;
+    Ag[i] = A + (size_t)row * M + m0 + (pc ^ (4 * (row & 3))) * 8;
   }
 #pragma unroll
   for (int i = 0; i < GB; i++) {
     const int row = (i * 4 + wave) * RB + lane / CB, pc = lane % CB;
-    Bg[i] = B + (size_t)row * N + n0 + (pc ^ (2 * (row & 3))) * 8;
+    Bg[i] = B + (size_t)row * N + n0 + (pc ^ (4 * (row & 3))) * 8;
   }
   auto issue = [&](int kt, int st) {
 #pragma unroll
@@ -288,7 +304,7 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
   const int tr_row = (g16 >> 1) * 8 + (j16 >> 2);
   const int tr_col = (g16 & 1) * 16 + (j16 & 3) * 4;
   auto read_frags = [&](int st, int ks, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
-    const int row = ks * 16 + tr_row, sw = 2 * (row & 3);
+    const int row = ks * 16 + tr_row, sw = 4 * (row & 3);
 #pragma unroll
     for (int i = 0; i < TM; i++) {
       const int col = wm0 + i * 32 + tr_col;
@@ -310,15 +326,17 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
 
   const int nk = K / BK;
+  constexpr int LPS = GA + GB;                       // loads each wave issues per slice
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-  issue(0, 0);
-  wait_vm0();
+#pragma unroll
+  for (int j = 0; j < NS - 1; j++)
+    if (j < nk) issue(j, j);
+  if (nk >= NS - 1) wait_vm<(NS - 2) * LPS, false>(); else wait_vm<0, false>();   // slice 0 has landed
   __syncthreads();
-  if (nk > 1) issue(1, 1);
+  if (NS - 1 < nk) issue(NS - 1, NS - 1);
   read_frags(0, 0, fa0, fb0);
-  // one slice; `more` = slice kt+2 exists (fetch it), `next` = slice kt+1 exists (start on its fragments)
-  auto slice = [&](int kt, bool more, bool next) {
-    const int cur = kt & 1;
+  // one slice; `more` = slice kt+NS exists (request it), `next` = slice kt+1 exists (start on its fragments)
+  auto slice = [&](int kt, int cur, bool more, bool next) {
     read_frags(cur, 1, fa1, fb1);
     mfma_step<TM, TN>(acc, fa0, fb0);
     interleave_hint<TM * TN, 2 * (TM + TN), 0>();
@@ -328,18 +346,19 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
     read_frags(cur, 3, fa1, fb1);
     mfma_step<TM, TN>(acc, fa0, fb0);
     interleave_hint<TM * TN, 2 * (TM + TN), 0>();
-    wait_vm0_lgkm0();                  // own loads of slice kt+1 have landed; last fragments of slice kt are in registers
+    // own loads of slice kt+1 have landed; the last fragments of slice kt are in registers
+    if (more) wait_vm<(NS - 2) * LPS, true>(); else wait_vm<0, true>();
     __syncthreads();
-    if (more) issue(kt + 2, cur);
-    if (next) read_frags(cur ^ 1, 0, fa0, fb0);
+    if (more) issue(kt + NS, cur);
+    if (next) read_frags(cur + 1 == NS ? 0 : cur + 1, 0, fa0, fb0);
     mfma_step<TM, TN>(acc, fa1, fb1);
     if (more) interleave_hint<TM * TN, 2 * (TM + TN), GA + GB>();
     else if (next) interleave_hint<TM * TN, 2 * (TM + TN), 0>();
   };
-  int kt = 0;
-  for (; kt + 2 < nk; kt++) slice(kt, true, true);
-  if (kt + 1 < nk) { slice(kt, false, true); kt++; }
-  slice(kt, false, false);
+  int kt = 0, cur = 0;
+  for (; kt + NS < nk; kt++) { slice(kt, cur, true, true); cur = cur + 1 == NS ? 0 : cur + 1; }
+  for (; kt + 1 < nk; kt++) { slice(kt, cur, false, true); cur = cur + 1 == NS ? 0 : cur + 1; }
+  slice(kt, cur, false, false);
 
   const int frow = lane & 31, fhalf = lane >> 5;
 #pragma unroll
@@ -353,7 +372,7 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
   }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, int NS>
 __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                            float* __restrict__ Cacc, int tiles_m, int tiles_n) {
@@ -361,7 +380,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
   int tm, tn; bool valid;
   tile_of_block(tiles_m, tiles_n, tm, tn, valid);
   if (!valid) return;
-  tn_tile<BM, BN, EPI>(M, N, K, A, B, C, Cacc, tm, tn, smem);
+  tn_tile<BM, BN, EPI, NS>(M, N, K, A, B, C, Cacc, tm, tn, smem);
 }
 
 // Several weight-gradient products that share the reduction length K (the token axis) in one launch:
@@ -369,7 +388,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
 struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const bf16_t* A; const bf16_t* B; float* Cacc; };
 struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 
-template <int BM, int BN>
+template <int BM, int BN, int NS>
 __global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int t = linear_of_block(grp.total_tiles);
@@ -380,12 +399,12 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp) 
   const TnProblem pr = grp.p[i];
   int tm, tn;
   tile_from_linear(t - pr.first_tile, pr.tiles_m, pr.tiles_n, tm, tn);
-  tn_tile<BM, BN, KFKB_EPI_ACCUM>(pr.M, pr.N, grp.K, pr.A, pr.B, nullptr, pr.Cacc, tm, tn, smem);
+  tn_tile<BM, BN, KFKB_EPI_ACCUM, NS>(pr.M, pr.N, grp.K, pr.A, pr.B, nullptr, pr.Cacc, tm, tn, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
 // TN kernel, register-staged variant: accepts a ragged reduction length K (zero-fills the tail).
-// Tiles are stored [reduction row][BM + 16].
+// Tiles are stored [reduction row][BM + 32].
 // ------------------------------------------------------------------------------------------------
 __device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* p, int row_stride) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -401,7 +420,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, 
                                                            const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                            float* __restrict__ Cacc, int tiles_m, int tiles_n) {
   constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int SA = BM + 16, SB = BN + 16;          // LDS row strides (elements): +32 bytes per row
+  constexpr int SA = BM + 32, SB = BN + 32;          // LDS row strides (elements): +64 bytes per row
   constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
   constexpr int LA = BM / 32, LB = BN / 32;          // chunks per thread per slice
   extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -518,12 +537,24 @@ const char* gemm_bf16_check(const GemmArgs& g) {
   return nullptr;
 }
 
-template <int BM, int BN, int EPI>
-static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
+// Pipeline depth of the 128 x 128 tiles (32 KiB of LDS per stage).  KFKB_STAGES_128 = 2, 3 or 4 overrides
+// the default for experiments.
+static int stages_128() {
+  static int v = 0;
+  if (v == 0) {
+    const char* e = getenv("KFKB_STAGES_128");
+    v = e ? atoi(e) : 4;
+    if (v < 2 || v > 4) v = 4;
+  }
+  return v;
+}
+
+template <int BM, int BN, int EPI, int NS>
+static hipError_t launch_nt_ns(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  const size_t smem = (size_t)2 * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI>;
+  const size_t smem = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, NS>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -535,12 +566,21 @@ static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
           (bf16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
 }
+template <int BM, int BN, int EPI>
+static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
+  if (BM == 256) return launch_nt_ns<BM, BN, EPI, 2>(g, s);
+  switch (stages_128()) {
+    case 2: return launch_nt_ns<BM, BN, EPI, 2>(g, s);
+    case 3: return launch_nt_ns<BM, BN, EPI, 3>(g, s);
+    default: return launch_nt_ns<BM, BN, EPI, (BM == 256 ? 2 : 4)>(g, s);
+  }
+}
 
 template <int BM, int BN, int EPI>
 static hipError_t launch_tn_staged(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  const size_t smem = (size_t)2 * BK * (BM + 16 + BN + 16) * sizeof(bf16_t);
+  const size_t smem = (size_t)2 * BK * (BM + 32 + BN + 32) * sizeof(bf16_t);
   auto kern = gemm_bf16_tn_staged_kernel<BM, BN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
@@ -553,13 +593,12 @@ static hipError_t launch_tn_staged(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int EPI>
-static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
-  if (g.K % BK != 0) return launch_tn_staged<BM, BN, EPI>(g, s);
+template <int BM, int BN, int EPI, int NS>
+static hipError_t launch_tn_ns(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  const size_t smem = (size_t)2 * BK * (BM + BN) * sizeof(bf16_t);
-  auto kern = gemm_bf16_tn_kernel<BM, BN, EPI>;
+  const size_t smem = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
+  auto kern = gemm_bf16_tn_kernel<BM, BN, EPI, NS>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -568,6 +607,33 @@ static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
   }
   klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
           (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, g.Cacc, tiles_m, tiles_n);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int EPI>
+static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
+  if (g.K % BK != 0) return launch_tn_staged<BM, BN, EPI>(g, s);
+  if (BM == 256) return launch_tn_ns<BM, BN, EPI, 2>(g, s);
+  switch (stages_128()) {
+    case 2: return launch_tn_ns<BM, BN, EPI, 2>(g, s);
+    case 3: return launch_tn_ns<BM, BN, EPI, 3>(g, s);
+    default: return launch_tn_ns<BM, BN, EPI, (BM == 256 ? 2 : 4)>(g, s);
+  }
+}
+
+template <int NS>
+static hipError_t launch_group_ns(const TnGroup& grp, double flops, hipStream_t s) {
+  constexpr int BM = 128, BN = 128;
+  const int grid = ((grp.total_tiles + 7) / 8) * 8;
+  const size_t smem = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
+  auto kern = gemm_bf16_tn_grouped_kernel<BM, BN, NS>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + 300, flops, grp);
   return hipGetLastError();
 }
 
@@ -595,17 +661,13 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
     grp.total_tiles += p.tiles_m * p.tiles_n;
     flops += 2.0 * g[i].M * g[i].N * g[i].K;
   }
-  const int grid = ((grp.total_tiles + 7) / 8) * 8;
-  const size_t smem = (size_t)2 * BK * (BM + BN) * sizeof(bf16_t);
-  auto kern = gemm_bf16_tn_grouped_kernel<BM, BN>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
+  static int ns = 0;
+  if (ns == 0) { const char* e = getenv("KFKB_STAGES_GROUP"); ns = e ? atoi(e) : 2; if (ns < 2 || ns > 4) ns = 2; }
+  switch (ns) {
+    case 3: return launch_group_ns<3>(grp, flops, s);
+    case 4: return launch_group_ns<4>(grp, flops, s);
+    default: return launch_group_ns<2>(grp, flops, s);
   }
-  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + 300, flops, grp);
-  return hipGetLastError();
 }
 
 // Large tiles when they still give every CU a tile; small tiles otherwise.

