@@ -7,7 +7,7 @@
 //               dq kernel   per 128 query rows, streams key tiles:   dQ = scale * dS K
 //               dkv kernel  per 128 key rows, streams query tiles:   dV = P^T dO,  dK = scale * dS^T Q
 //             both recompute P = exp(scale * Q K^T - lse) and dS = P o (dO V^T - dsum),
-//             dsum = rowsum(dO o O) coming from a small pre-pass.
+//             dsum = rowsum(dO o O), formed by the dq kernel (which runs first) and read by the dkv kernel.
 //
 // Register / lane plan (one wave owns 32 "own" rows and streams the other operand):
 //   the score tile is produced transposed with respect to the streamed rows, i.e. with the wave's own
@@ -109,7 +109,9 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  const int qb = gridDim.x - 1 - blockIdx.x;        // heaviest (latest) query blocks first
+  // Work per block grows with the query-block index (causal).  Consecutive block ids go to different XCDs, so
+  // the query block is rotated by the (sample, head) index: every XCD then sees every query-block index.
+  const int qb = (blockIdx.x + blockIdx.y) % gridDim.x;
   const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
@@ -223,8 +225,9 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
 // backward, dQ: own rows = queries, streamed rows = keys
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
-                                                               const float* __restrict__ lse, const float* __restrict__ dsum,
+__global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
+                                                               const bf16_t* __restrict__ d_o,
+                                                               const float* __restrict__ lse, float* __restrict__ dsum,
                                                                bf16_t* __restrict__ dqkv, int T, int H, int heads,
                                                                int causal, float scale) {
   using IO = TileIO<D>;
@@ -235,7 +238,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  const int qb = gridDim.x - 1 - blockIdx.x;
+  const int qb = (blockIdx.x + blockIdx.y) % gridDim.x;   // rotated: see the forward kernel
   const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
@@ -251,7 +254,17 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
     dof[ds] = *reinterpret_cast<const bf16x8*>(d_o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
   }
   const float lse_i = lse[((size_t)bi * heads + hd) * T + ic] * kLog2e;
-  const float dsum_i = dsum[((size_t)bi * heads + hd) * T + ic];
+  // dsum_i = sum_t dO[i,t] O[i,t]: this kernel owns the query rows, so it forms the sum (each lane half holds
+  // half of the row) and publishes it for the dK/dV kernel, which runs after this one
+  float dpart = 0.f;
+#pragma unroll
+  for (int ds = 0; ds < D / 16; ds++) {
+    const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
+#pragma unroll
+    for (int e = 0; e < 8; e++) dpart += (float)of[e] * (float)dof[ds][e];
+  }
+  const float dsum_i = dpart + __shfl_xor(dpart, 32, 64);
+  if (hh == 0 && i < T) dsum[((size_t)bi * heads + hd) * T + i] = dsum_i;
 
   const int nkv_all = (T + 63) / 64;
   const int nkv = causal ? min(nkv_all, (min(q0 + 127, T - 1)) / 64 + 1) : nkv_all;
@@ -346,7 +359,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  const int kb = blockIdx.x;                        // early key blocks see the most queries: they come first
+  const int kb = (blockIdx.x + blockIdx.y) % gridDim.x;   // rotated: see the forward kernel
   const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
@@ -468,7 +481,6 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
 }
 
 // ------------------------------------------------------------------------------------------------
-hipError_t launch_attn_dsum(int dt, const void* o, const void* d_o, float* dsum, int b, int T, int H, int heads, hipStream_t s);
 
 template <typename K>
 static hipError_t set_smem(K kern, size_t bytes, bool& done) {
@@ -492,8 +504,8 @@ static hipError_t fwd_d(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, 
 }
 
 template <int D>
-static hipError_t bwd_d(const bf16_t* qkv, const bf16_t* d_o, const float* lse, const float* dsum, bf16_t* dqkv, int b,
-                        int T, int H, int heads, int causal, hipStream_t s) {
+static hipError_t bwd_d(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse, float* dsum, bf16_t* dqkv,
+                        int b, int T, int H, int heads, int causal, hipStream_t s) {
   static bool attr1 = false, attr2 = false;
   const size_t smem1 = (size_t)4 * 64 * D * sizeof(bf16_t);
   const size_t smem2 = smem1 + 4 * 64 * sizeof(float);
@@ -504,10 +516,10 @@ static hipError_t bwd_d(const bf16_t* qkv, const bf16_t* d_o, const float* lse, 
   const float scale = 1.0f / sqrtf((float)D);
   const dim3 grid((T + 127) / 128, b * heads);
   const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
-  klaunch(attn_bwd_dkv_bf16_kernel<D>, grid, dim3(256), smem2, s, PK_ATTN_DKV + D / 128, 8.0 * pairs * D, qkv, d_o, lse, dsum, dqkv,
+  klaunch(attn_bwd_dq_bf16_kernel<D>, grid, dim3(256), smem1, s, PK_ATTN_DQ + D / 128, 6.0 * pairs * D, qkv, o, d_o, lse, dsum, dqkv,
           T, H, heads, causal, scale);
-  klaunch(attn_bwd_dq_bf16_kernel<D>, grid, dim3(256), smem1, s, PK_ATTN_DQ + D / 128, 6.0 * pairs * D, qkv, d_o, lse, dsum, dqkv, T,
-          H, heads, causal, scale);
+  klaunch(attn_bwd_dkv_bf16_kernel<D>, grid, dim3(256), smem2, s, PK_ATTN_DKV + D / 128, 8.0 * pairs * D, qkv, d_o, lse,
+          (const float*)dsum, dqkv, T, H, heads, causal, scale);
   return hipGetLastError();
 }
 
@@ -522,10 +534,8 @@ hipError_t launch_attention_bwd_bf16(const bf16_t* qkv, const bf16_t* o, const b
                                      float* dsum, bf16_t* dqkv, int b, int T, int H, int heads, int causal,
                                      hipStream_t s) {
   if (b <= 0 || T <= 0) return hipSuccess;
-  hipError_t e = launch_attn_dsum(DT_BF16, o, d_o, dsum, b, T, H, heads, s);
-  if (e != hipSuccess) return e;
-  return (H / heads == 64) ? bwd_d<64>(qkv, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s)
-                           : bwd_d<128>(qkv, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s);
+  return (H / heads == 64) ? bwd_d<64>(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s)
+                           : bwd_d<128>(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s);
 }
 
 }  // namespace kfkb

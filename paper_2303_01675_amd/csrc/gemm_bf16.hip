@@ -543,8 +543,8 @@ static int stages_128() {
   static int v = 0;
   if (v == 0) {
     const char* e = getenv("KFKB_STAGES_128");
-    v = e ? atoi(e) : 4;
-    if (v < 2 || v > 4) v = 4;
+    v = e ? atoi(e) : 2;
+    if (v < 2 || v > 4) v = 2;
   }
   return v;
 }
@@ -572,7 +572,7 @@ static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
   switch (stages_128()) {
     case 2: return launch_nt_ns<BM, BN, EPI, 2>(g, s);
     case 3: return launch_nt_ns<BM, BN, EPI, 3>(g, s);
-    default: return launch_nt_ns<BM, BN, EPI, (BM == 256 ? 2 : 4)>(g, s);
+    default: return launch_nt_ns<BM, BN, EPI, (BM == 256 ? 2 : 4)>(g, s);   // 4 stages
   }
 }
 
@@ -675,7 +675,9 @@ static bool use_big_tiles(int M, int N, bool m_must_divide) {
   if (N % 256 != 0) return false;
   if (m_must_divide && M % 256 != 0) return false;
   const long tiles = (long)((M + 255) / 256) * (N / 256);
-  return tiles >= 224;
+  static long min_tiles = -1;                 // KFKB_BIG_TILE_MIN overrides the threshold for experiments
+  if (min_tiles < 0) { const char* e = getenv("KFKB_BIG_TILE_MIN"); min_tiles = e ? atol(e) : 192; }
+  return tiles >= min_tiles;
 }
 
 template <int EPI>
