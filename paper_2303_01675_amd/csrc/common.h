@@ -110,6 +110,8 @@ hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mea
                          const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta,
                          float* scratch, int rows, int H, hipStream_t s);
 hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratch, int rows, int N, hipStream_t s);
+hipError_t launch_colsum_group(int dt, int n, const void* const* dy, float* const* out, const int* widths, float* scratch,
+                               int rows, hipStream_t s);   // up to 4 column sums over the same rows
 hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int cols, hipStream_t s);

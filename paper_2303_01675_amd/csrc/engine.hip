@@ -40,7 +40,10 @@ void prof_key_name(int key, char* out, size_t cap, int* bound) {
     snprintf(out, cap, "%s<%d>", cls == 0 ? "attn_fwd_bf16_kernel" : cls == 1 ? "attn_bwd_dq_bf16_kernel" : "attn_bwd_dkv_bf16_kernel", (key - PK_ATTN_FWD) % 100 ? 128 : 64);
   } else if (key >= PK_ATTN_DSUM && key < PK_LN_FWD) snprintf(out, cap, "attn_dsum_kernel");
   else if (key >= PK_LN_FWD && key < PK_LN_BWD_DX) snprintf(out, cap, "ln_fwd_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_FWD) / 4);
-  else if (key >= PK_LN_BWD_DX && key < PK_COLSUM) snprintf(out, cap, "ln_bwd_dx_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_BWD_DX) / 4);
+  else if (key >= PK_LN_BWD_DX && key < PK_LN_BWD_DX + 80) snprintf(out, cap, "ln_bwd_dx_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_BWD_DX) / 4);
+  else if (key >= PK_LN_BWD_DX + 80 && key < PK_COLSUM) snprintf(out, cap, "ln_bwd_fused_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_BWD_DX - 80) / 4);
+  else if (key == PK_COLSUM + 10 || key == PK_COLSUM + 12) snprintf(out, cap, "colsum_group_partial_kernel<%s>", key == PK_COLSUM + 12 ? "float" : "bf16");
+  else if (key == PK_COLSUM_FINAL + 1) snprintf(out, cap, "colsum_group_final_kernel");
   else if (key >= PK_COLSUM && key < PK_COLSUM_XHAT) snprintf(out, cap, "colsum_partial_kernel<%s,false>", key - PK_COLSUM == 4 ? "float" : "bf16");
   else if (key >= PK_COLSUM_XHAT && key < PK_COLSUM_FINAL) snprintf(out, cap, "colsum_partial_kernel<%s,true>", key - PK_COLSUM_XHAT == 4 ? "float" : "bf16");
   else if (key == PK_COLSUM_FINAL) snprintf(out, cap, "colsum_final_kernel");
@@ -209,7 +212,9 @@ int peak_live_for(const Stage& s, int k, int M) {
   return std::min((warmup_for(s, k, M) + 1) * k, M);
 }
 
-size_t red_floats(const Stage& s) { return (size_t)64 * 2 * std::max(s.F, 3 * s.H); }
+// column-sum partials: 64 parts x 2 slots x widest matrix, the four bias gradients side by side (F + 5H),
+// or 512 parts x 2 x H of the fused LayerNorm backward: 128 (F + 5H) floats covers all three
+size_t red_floats(const Stage& s) { return (size_t)128 * (s.F + 5 * (size_t)s.H); }
 
 struct Carve { size_t wt, stash, xs, dys, ys, dxs, tn, tmf, t3n, dsum, red, total; int n_stash, n_x, n_io; };
 
@@ -347,28 +352,30 @@ int compute_backward(int slot, const char* x_in, const char* dy_in, char* dx_out
     const char* x = (l == 0) ? x_in : view(s, slot, l - 1).y;
     char* dx = (l == 0) ? dx_out : s.t_n[2 + (l & 1)];
     // y = x1 + g W2 + b2
-    HIPCHK(launch_colsum_accum(s.dt, dy, gptr(s, l, s.po.b_2), s.red, s.m, s.H, s.sc));
     wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
     // u = c W1 + b1
-    HIPCHK(launch_colsum_accum(s.dt, du, gptr(s, l, s.po.b_1), s.red, s.m, s.F, s.sc));
     wgrad(1, s.H, s.F, v.c, du, gptr(s, l, s.po.w_1));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr));
     // c = LN2(x1), plus the residual path
     HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), s.red, s.m, s.H, s.sc));
     // x1 = x + o Wo + bo
-    HIPCHK(launch_colsum_accum(s.dt, dx1, gptr(s, l, s.po.b_o), s.red, s.m, s.H, s.sc));
     wgrad(3, s.H, s.H, v.o, dx1, gptr(s, l, s.po.w_o));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr));
     // o = attention(qkv)
     TRY(attention_bwd(s, v.qkv, v.o, d_o, v.lse, dqkv));
     // qkv = a Wqkv + bqkv
-    HIPCHK(launch_colsum_accum(s.dt, dqkv, gptr(s, l, s.po.b_qkv), s.red, s.m, 3 * s.H, s.sc));
     wgrad(0, s.H, 3 * s.H, v.a, dqkv, gptr(s, l, s.po.w_qkv));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
     // a = LN1(x), plus the residual path
     HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), s.red, s.m, s.H, s.sc));
     // du, dx1, dqkv and this block's dy are still intact here; the next block overwrites them
+    {
+      const void* srcs[4] = {dqkv, du, dy, dx1};
+      float* outs[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
+      const int widths[4] = {3 * s.H, s.F, s.H, s.H};
+      HIPCHK(launch_colsum_group(s.dt, 4, srcs, outs, widths, s.red, s.m, s.sc));
+    }
     if (s.dt == DT_BF16) {
       for (int i = 0; i < 4; i++) {
         const char* why = gemm_bf16_check(wg[i]);
@@ -896,7 +903,7 @@ int kfkb_op_colsum_accum(int dtype, const void* dy, float* out, float* scratch, 
   return 0;
 }
 
-size_t kfkb_op_reduce_scratch_floats(int width) { return width > 0 ? (size_t)64 * 2 * width : 0; }
+size_t kfkb_op_reduce_scratch_floats(int width) { return width > 0 ? (size_t)1024 * width : 0; }
 
 int kfkb_op_gelu_bwd(int dtype, const void* dg, const void* u, void* du, size_t n, void* stream) {
   CHECK_DT(dtype);

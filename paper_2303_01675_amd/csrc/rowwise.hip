@@ -111,6 +111,92 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
   }
 }
 
+// LayerNorm backward with the parameter-gradient partial sums folded in (rows short enough to keep the
+// per-lane column sums in registers: H <= 2048).  A block owns a run of rows, wave w takes every fourth of
+// them; a lane always holds the same columns, so it adds dy and dy * xhat of its rows into registers, the
+// four waves meet in LDS in fixed order and the block writes one partial row [2][H] for the finishing pass.
+template <typename T, int NCH>
+__global__ void __launch_bounds__(256) ln_bwd_fused_kernel(const T* __restrict__ dy, const T* __restrict__ x,
+                                                           const float* __restrict__ mean, const float* __restrict__ rstd,
+                                                           const T* __restrict__ gamma, const T* __restrict__ dres,
+                                                           T* __restrict__ dx, float* __restrict__ partial, int rows, int H,
+                                                           int rows_per_block) {
+  extern __shared__ float lnred[];                    // [2][4][H]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nchunks = H >> 3;
+  const int r0 = blockIdx.x * rows_per_block;
+  const int r1 = min(rows, r0 + rows_per_block);
+  float sb[NCH][8], sg[NCH][8], gm[NCH][8];
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+#pragma unroll
+    for (int e = 0; e < 8; e++) { sb[i][e] = 0.f; sg[i][e] = 0.f; gm[i][e] = 0.f; }
+    if (c < nchunks) Vec8<T>::load(gamma + c * 8, gm[i]);
+  }
+  for (int row = r0 + wave; row < r1; row += 4) {
+    const float mu = mean[row], rs = rstd[row];
+    const T* xr = x + (size_t)row * H;
+    const T* dyr = dy + (size_t)row * H;
+    float xh[NCH][8], g[NCH][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int i = 0; i < NCH; i++) {
+      const int c = lane + 64 * i;
+      if (c < nchunks) {
+        Vec8<T>::load(xr + c * 8, xh[i]);
+        Vec8<T>::load(dyr + c * 8, g[i]);
+#pragma unroll
+        for (int e = 0; e < 8; e++) {
+          xh[i][e] = (xh[i][e] - mu) * rs;
+          sb[i][e] += g[i][e];
+          sg[i][e] += g[i][e] * xh[i][e];
+          g[i][e] *= gm[i][e];
+          s1 += g[i][e];
+          s2 += g[i][e] * xh[i][e];
+        }
+      }
+    }
+    const float m1 = wave_sum(s1) / (float)H;
+    const float m2 = wave_sum(s2) / (float)H;
+    T* dxr = dx + (size_t)row * H;
+#pragma unroll
+    for (int i = 0; i < NCH; i++) {
+      const int c = lane + 64 * i;
+      if (c < nchunks) {
+        float o[8];
+#pragma unroll
+        for (int e = 0; e < 8; e++) o[e] = rs * (g[i][e] - m1 - xh[i][e] * m2);
+        if (dres != nullptr) {
+          float r[8];
+          Vec8<T>::load(dres + (size_t)row * H + c * 8, r);
+#pragma unroll
+          for (int e = 0; e < 8; e++) o[e] += r[e];
+        }
+        Vec8<T>::store(dxr + c * 8, o);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {
+    const int c = lane + 64 * i;
+    if (c < nchunks) {
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        lnred[(0 * 4 + wave) * H + c * 8 + e] = sb[i][e];
+        lnred[(1 * 4 + wave) * H + c * 8 + e] = sg[i][e];
+      }
+    }
+  }
+  __syncthreads();
+  float* p = partial + (size_t)blockIdx.x * 2 * H;
+  for (int c = threadIdx.x; c < 2 * H; c += 256) {
+    const int slot = c / H, col = c - slot * H;
+    p[c] = ((lnred[(slot * 4 + 0) * H + col] + lnred[(slot * 4 + 1) * H + col]) + lnred[(slot * 4 + 2) * H + col]) +
+           lnred[(slot * 4 + 3) * H + col];
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // Column sums in two deterministic passes.
 //   pass 1: block (colblock, part) sums rows [part*rpp, (part+1)*rpp) of 256 columns; a thread owns
@@ -172,7 +258,18 @@ __global__ void __launch_bounds__(256) colsum_final_kernel(const float* __restri
   const int c = blockIdx.x * 32 + cl;
   float s0 = 0.f, s1 = 0.f;
   if (c < width) {
-    for (int p = pl; p < parts; p += 8) {
+    // four loads in flight per accumulator, added in ascending part order
+    int p = pl;
+    for (; p + 24 < parts; p += 32) {
+      const float* q = partial + (size_t)p * 2 * width + c;
+      const float a0 = q[0], a1 = q[(size_t)16 * width], a2 = q[(size_t)32 * width], a3 = q[(size_t)48 * width];
+      s0 = (((s0 + a0) + a1) + a2) + a3;
+      if (out1 != nullptr) {
+        const float b0 = q[width], b1 = q[(size_t)17 * width], b2 = q[(size_t)33 * width], b3 = q[(size_t)49 * width];
+        s1 = (((s1 + b0) + b1) + b2) + b3;
+      }
+    }
+    for (; p < parts; p += 8) {
       s0 += partial[(size_t)p * 2 * width + c];
       if (out1 != nullptr) s1 += partial[(size_t)p * 2 * width + width + c];
     }
@@ -201,6 +298,92 @@ static hipError_t colsum_launch(const T* dy, const T* x, const float* mean, cons
           mean, rstd, scratch, rows, width, rpp);
   klaunch(colsum_final_kernel, dim3((width + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * width * 4 * (XHAT ? 2 : 1),
           scratch, parts, width, out_sum, XHAT ? out_xhat : (float*)nullptr);
+  return hipGetLastError();
+}
+
+// Up to four column sums over the same rows in one pair of launches (the four bias gradients of a block).
+struct ColsumProblem { const void* dy; float* out; int width, first_block, col_off; };
+struct ColsumGroup { int count, rows, rows_per_part, total_width; ColsumProblem p[4]; };
+
+template <typename T>
+__global__ void __launch_bounds__(256) colsum_group_partial_kernel(ColsumGroup g, float* __restrict__ partial) {
+  __shared__ float red[8][256 + 8];
+  int pi = 0;
+#pragma unroll
+  for (int q = 1; q < 4; q++) if (q < g.count && (int)blockIdx.x >= g.p[q].first_block) pi = q;
+  const ColsumProblem pr = g.p[pi];
+  const T* dy = (const T*)pr.dy;
+  const int cg = threadIdx.x & 31, rl = threadIdx.x >> 5;
+  const int cb = (blockIdx.x - pr.first_block) * 256;
+  const int col = cb + cg * 8;
+  const int part = blockIdx.y;
+  const int r0 = part * g.rows_per_part;
+  const int r1 = min(g.rows, r0 + g.rows_per_part);
+  float a[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) a[e] = 0.f;
+  if (col < pr.width) {
+    for (int r = r0 + rl; r < r1; r += 8) {
+      float d[8];
+      Vec8<T>::load(dy + (size_t)r * pr.width + col, d);
+#pragma unroll
+      for (int e = 0; e < 8; e++) a[e] += d[e];
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; e++) red[rl][cg * 8 + e] = a[e];
+  __syncthreads();
+  const int c = threadIdx.x;
+  if (cb + c < pr.width) {
+    float sa = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) sa += red[j][c];
+    partial[(size_t)part * g.total_width + pr.col_off + cb + c] = sa;
+  }
+}
+
+__global__ void __launch_bounds__(256) colsum_group_final_kernel(ColsumGroup g, const float* __restrict__ partial, int parts) {
+  __shared__ float red[8][32];
+  const int cl = threadIdx.x & 31, pl = threadIdx.x >> 5;
+  const int c = blockIdx.x * 32 + cl;
+  float s0 = 0.f;
+  if (c < g.total_width)
+    for (int p = pl; p < parts; p += 8) s0 += partial[(size_t)p * g.total_width + c];
+  red[pl][cl] = s0;
+  __syncthreads();
+  if (pl == 0 && c < g.total_width) {
+    float a = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; j++) a += red[j][cl];
+    int pi = 0;
+#pragma unroll
+    for (int q = 1; q < 4; q++) if (q < g.count && c >= g.p[q].col_off) pi = q;
+    g.p[pi].out[c - g.p[pi].col_off] += a;
+  }
+}
+
+hipError_t launch_colsum_group(int dt, int n, const void* const* dy, float* const* out, const int* widths, float* scratch,
+                               int rows, hipStream_t s) {
+  if (rows <= 0 || n <= 0) return hipSuccess;
+  if (n > 4) return hipErrorInvalidValue;
+  ColsumGroup g{};
+  g.count = n; g.rows = rows;
+  const int parts = reduce_parts(rows);
+  g.rows_per_part = (rows + parts - 1) / parts;
+  int blocks = 0;
+  double bytes = 0;
+  for (int i = 0; i < n; i++) {
+    g.p[i] = ColsumProblem{dy[i], out[i], widths[i], blocks, g.total_width};
+    blocks += (widths[i] + 255) / 256;
+    g.total_width += widths[i];
+    bytes += (double)rows * widths[i] * dt_bytes(dt);
+  }
+  if (dt == DT_BF16)
+    klaunch(colsum_group_partial_kernel<bf16_t>, dim3(blocks, parts), dim3(256), 0, s, PK_COLSUM + 10, bytes, g, scratch);
+  else
+    klaunch(colsum_group_partial_kernel<float>, dim3(blocks, parts), dim3(256), 0, s, PK_COLSUM + 12, bytes, g, scratch);
+  klaunch(colsum_group_final_kernel, dim3((g.total_width + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL + 1,
+          (double)parts * g.total_width * 4, g, (const float*)scratch, parts);
   return hipGetLastError();
 }
 
@@ -285,13 +468,31 @@ hipError_t launch_ln_fwd(int dt, const void* x, const void* gamma, const void* b
   return ln_fwd_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd, rows, H, eps, s);
 }
 
+template <typename T, int NCH>
+static hipError_t ln_bwd_fused_launch(const T* dy, const T* x, const float* mean, const float* rstd, const T* gamma,
+                                      const T* dres, T* dx, float* dgamma, float* dbeta, float* scratch, int rows, int H,
+                                      hipStream_t s) {
+  const int rpb = std::max(8, ((rows + 511) / 512 + 3) / 4 * 4);   // at most 512 partial rows
+  const int parts = (rows + rpb - 1) / rpb;
+  const double bytes = (dres ? 4.0 : 3.0) * rows * H * sizeof(T);
+  klaunch(ln_bwd_fused_kernel<T, NCH>, dim3(parts), dim3(256), (size_t)8 * H * sizeof(float), s,
+          PK_LN_BWD_DX + 80 + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, scratch, rows, H, rpb);
+  klaunch(colsum_final_kernel, dim3((H + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * H * 8, (const float*)scratch,
+          parts, H, dbeta, dgamma);
+  return hipGetLastError();
+}
+
 template <typename T>
 static hipError_t ln_bwd_t(const T* dy, const T* x, const float* mean, const float* rstd, const T* gamma,
                            const T* dres, T* dx, float* dgamma, float* dbeta, float* scratch, int rows, int H,
                            hipStream_t s) {
+  const int nch = nch_for(H);
+  if (nch == 1) return ln_bwd_fused_launch<T, 1>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
+  if (nch == 2) return ln_bwd_fused_launch<T, 2>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
+  if (nch == 4) return ln_bwd_fused_launch<T, 4>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
   const dim3 grid((rows + 3) / 4);
   const double bytes = (dres ? 4.0 : 3.0) * rows * H * sizeof(T);
-  KFKB_NCH_SWITCH(nch_for(H), klaunch(ln_bwd_dx_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_BWD_DX + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, rows, H));
+  KFKB_NCH_SWITCH(nch, klaunch(ln_bwd_dx_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_BWD_DX + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, rows, H));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return colsum_launch<T, true>(dy, x, mean, rstd, dbeta, dgamma, scratch, rows, H, s);
