@@ -20,9 +20,17 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 WORKLOADS = {
-    # name: L, H, heads, T, b, M, dtype, ks
-    "gpt2-medium-stage": dict(L=6, H=1024, heads=16, T=1024, b=4, M=16, dtype="bf16", ks=(1, 2, 4)),
-    "tiny-stage": dict(L=2, H=128, heads=4, T=64, b=2, M=4, dtype="f32", ks=(1, 2)),
+    # name: L, H, heads, T, b, M, dtype, ks, default delay model, activation limit (bytes, 0 = none)
+    "gpt2-medium-stage": dict(L=6, H=1024, heads=16, T=1024, b=4, M=16, dtype="bf16", ks=(1, 2, 4), delay="none", limit=0),
+    "tiny-stage": dict(L=2, H=128, heads=4, T=64, b=2, M=4, dtype="f32", ks=(1, 2), delay="none", limit=0),
+    # the larger configurations: timing only (weights are one seeded 4M-element draw tiled over every tensor,
+    # two seeded micro-batches reused cyclically); parity at these shapes is covered kernel by kernel in tests/
+    "gpt-1.3b-stage": dict(L=6, H=2048, heads=16, T=2048, b=2, M=32, dtype="bf16", ks=(1, 2, 4, 8), delay="lognormal",
+                           limit=0, tiled=True),
+    "wide-stage": dict(L=4, H=4096, heads=32, T=2048, b=1, M=32, dtype="bf16", ks=(1, 2, 4, 8, 0), delay="bimodal",
+                       limit=200e9, tiled=True),
+    "very-wide-stage": dict(L=2, H=8192, heads=64, T=4096, b=1, M=64, dtype="bf16", ks=(1, 2, 4, 8), delay="drift",
+                            limit=250e9, tiled=True),
 }
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 PEAK_HBM_GBS = 8000.0
@@ -36,8 +44,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2-medium-stage", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--delay", default="none", choices=["none", "lognormal"],
-                    help="per-transfer injected delay (lognormal: mean 2 ms, sigma 0.5)")
+    ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
+                    help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
+                         "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build drives one pipeline stage on ONE GPU; --gpus %d is not supported "
@@ -57,35 +66,65 @@ def main():
     w = WORKLOADS[args.workload]
     L, H, heads, T, b, M = w["L"], w["H"], w["heads"], w["T"], w["b"], w["M"]
     dt = kf.BF16 if w["dtype"] == "bf16" else kf.F32
+    delay_model = args.delay or w["delay"]
     t0 = time.time()
-    blocks = synth.stage_weights(L, H, 4 * H, w["dtype"])
-    st = kf.StageBuffers(blocks, dt, heads, T, b, M, max(w["ks"]))
+    if w.get("tiled"):
+        base = synth.normal(1234, 1 << 22, 0.0, 0.02)
+
+        def tensor(name, shp):
+            v = np.resize(base, int(np.prod(shp)))
+            return synth.round_to_bf16(v + 1.0 if name in ("ln1_g", "ln2_g") else v).reshape(shp)
+        one = {n: tensor(n, shp) for n, shp in synth.param_shapes(H, 4 * H).items()}
+        blocks = [one] * L
+    else:
+        blocks = synth.stage_weights(L, H, 4 * H, w["dtype"])
+    st = kf.StageBuffers(blocks, dt, heads, T, b, M, M if 0 in w["ks"] else max(w["ks"]))
+    distinct = 2 if w.get("tiled") else M
+    cache = {}
     for mb in range(M):
-        st.set_inputs_one(mb, synth.microbatch_inputs(mb, b, T, H, w["dtype"]),
-                          synth.microbatch_upstream_grads(mb, b, T, H, w["dtype"]))
+        src = mb % distinct
+        if src not in cache:
+            cache[src] = (synth.microbatch_inputs(src, b, T, H, w["dtype"]), synth.microbatch_upstream_grads(src, b, T, H, w["dtype"]))
+        st.set_inputs_one(mb, *cache[src])
+    del cache
+    if w.get("tiled"):
+        del blocks
     t_setup = time.time() - t0
     overlap = kf.stage_side_streams_overlap()
-    if args.delay == "lognormal":
-        d = [synth.delays_lognormal(M, 2.0, 0.5, seed=4242 + i) for i in range(4)]
+
+    def set_delays(step_index, n_steps):
+        """Delays of one iteration, the same for every k: drawn per (iteration, direction, micro-batch)."""
+        if delay_model == "none":
+            return
+        if delay_model == "lognormal":
+            d = [synth.delays_lognormal(M, 2.0, 0.5, seed=4242 + 4 * step_index + i) for i in range(4)]
+        elif delay_model == "bimodal":
+            d = [synth.delays_bimodal(M, 0.5, 10.0, 0.7, seed=4242 + 4 * step_index + i) for i in range(4)]
+        else:
+            d = [synth.delays_drift(M, step_index, n_steps, 20.0)] * 4
         kf.stage_set_delays(*d)
 
     from oracle import stage_math as osm        # only for the FLOP model and the CPU-baseline leg
     flops_iter = M * osm.stage_flops(L, b, T, H, causal=True)
     flops_iter_megatron = M * osm.stage_flops(L, b, T, H, causal=True, megatron=True)
 
-    def step(k):
+    limit = int(w["limit"])
+
+    def step(k, i=0):
+        set_delays(i, args.steps)
         kf.stage_zero_grads()
-        kf.run_kFkB(k, M, 0)
+        kf.run_kFkB(k, M, limit)
 
     per_k = {}
-    for k in w["ks"]:
+    for k_req in w["ks"]:
         for _ in range(args.warmup):
-            step(k)
+            step(k_req)
         kf.stage_sync()
+        k = kf.stage_last_k()                      # k_req = 0 asks for the largest k that fits the activation limit
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(args.steps):
-            step(k)
+        for i in range(args.steps):
+            step(k_req, i)
         kf.stage_sync()
         torch.cuda.synchronize()
         dt_s = time.perf_counter() - t0
@@ -96,11 +135,14 @@ def main():
     best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
 
     # per-kernel timing of the same steps at the best k: HIP start/stop events on the compute stream
+    kf.stage_set_delays(None, None, None, None)
+    delay_model_saved, delay_model = delay_model, "none"
     kf.kfkb_profile(True)
     for _ in range(args.steps):
         step(best_k)
     kf.stage_sync()
     kf.kfkb_profile(False)
+    delay_model = delay_model_saved
     stats = kf.kfkb_profile_report()
     tot_ms = sum(s["total_ms"] for s in stats) or 1.0
     kernels = []
@@ -120,7 +162,7 @@ def main():
         roofline["all_gemm_frac"] = roofline["all_gemm_tflops"] / PEAK_BF16_TFLOPS
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not w.get("tiled"):
         from oracle import stage_math as sm
         x = synth.microbatch_inputs(0, b, T, H, w["dtype"])
         dy = synth.microbatch_upstream_grads(0, b, T, H, w["dtype"])
@@ -145,9 +187,11 @@ def main():
         "metric": "stage fwd+bwd samples/sec (kFkB iteration, best k)", "value": best["samples_per_s"],
         "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": best["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": w["dtype"], "data": "synthetic",
+        "dtype": w["dtype"],
+        "data": "synthetic" + (" (one seeded draw tiled over the weights, 2 micro-batches reused)" if w.get("tiled") else ""),
         "config": {"workload": args.workload, "layers": L, "hidden": H, "heads": heads, "seq_len": T, "micro_batch": b,
-                   "num_microbatches": M, "global_batch": M * b, "k": best_k, "delay": args.delay,
+                   "num_microbatches": M, "global_batch": M * b, "k": best_k, "delay": delay_model,
+                   "activation_limit_bytes": limit,
                    "side_streams_overlap": bool(overlap)},
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
         "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,

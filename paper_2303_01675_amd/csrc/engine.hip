@@ -30,7 +30,7 @@ void prof_key_name(int key, char* out, size_t cap, int* bound) {
     const bool tn = key >= PK_GEMM_TN;
     const int r = key - (tn ? PK_GEMM_TN : PK_GEMM_NT);
     *bound = 0;
-    if (tn && r == 300) { snprintf(out, cap, "gemm_bf16_tn_grouped_kernel<128,128>"); return; }
+    if (tn && (r == 300 || r == 301)) { snprintf(out, cap, "gemm_bf16_tn_grouped_kernel<%d,%d>", r == 301 ? 256 : 128, r == 301 ? 256 : 128); return; }
     const bool staged = r >= 200;
     const int tile = (r % 200) >= 100 ? 256 : 128;
     snprintf(out, cap, "gemm_bf16_%s_kernel<%d,%d,%s>", tn ? (staged ? "tn_staged" : "tn") : "nt", tile, tile, epi[r % 100]);

@@ -22,6 +22,7 @@
 // the tile order, and that order walks groups of four tile-rows column by column.
 #include "common.h"
 #include "../../include/kfkb.h"
+#include <algorithm>
 #include <cstdlib>
 
 namespace kfkb {
@@ -621,9 +622,8 @@ static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
   }
 }
 
-template <int NS>
+template <int BM, int BN, int NS>
 static hipError_t launch_group_ns(const TnGroup& grp, double flops, hipStream_t s) {
-  constexpr int BM = 128, BN = 128;
   const int grid = ((grp.total_tiles + 7) / 8) * 8;
   const size_t smem = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
   auto kern = gemm_bf16_tn_grouped_kernel<BM, BN, NS>;
@@ -633,8 +633,16 @@ static hipError_t launch_group_ns(const TnGroup& grp, double flops, hipStream_t 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + 300, flops, grp);
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 301 : 300), flops, grp);
   return hipGetLastError();
+}
+
+// fewest 256 x 256 tiles a launch must have before they are preferred over 128 x 128 tiles
+// (KFKB_BIG_TILE_MIN overrides it for experiments)
+static long big_tile_min() {
+  static long v = -1;
+  if (v < 0) { const char* e = getenv("KFKB_BIG_TILE_MIN"); v = e ? atol(e) : 192; }
+  return v;
 }
 
 hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
@@ -650,24 +658,27 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
     }
     return hipSuccess;
   }
-  constexpr int BM = 128, BN = 128;
+  // 256 x 256 tiles when every problem divides into them and the group still gives every CU a tile
+  long big_tiles = 0;
+  bool big = true;
+  for (int i = 0; i < n; i++) {
+    big = big && g[i].M % 256 == 0 && g[i].N % 256 == 0;
+    big_tiles += (long)(g[i].M / 256) * (g[i].N / 256);
+  }
+  big = big && big_tiles >= big_tile_min();
+  const int BT = big ? 256 : 128;
   TnGroup grp{};
   grp.count = n; grp.K = g[0].K;
   double flops = 0;
   for (int i = 0; i < n; i++) {
     TnProblem& p = grp.p[i];
-    p.M = g[i].M; p.N = g[i].N; p.tiles_m = g[i].M / BM; p.tiles_n = g[i].N / BN; p.first_tile = grp.total_tiles;
+    p.M = g[i].M; p.N = g[i].N; p.tiles_m = g[i].M / BT; p.tiles_n = g[i].N / BT; p.first_tile = grp.total_tiles;
     p.A = (const bf16_t*)g[i].A; p.B = (const bf16_t*)g[i].B; p.Cacc = g[i].Cacc;
     grp.total_tiles += p.tiles_m * p.tiles_n;
     flops += 2.0 * g[i].M * g[i].N * g[i].K;
   }
-  static int ns = 0;
-  if (ns == 0) { const char* e = getenv("KFKB_STAGES_GROUP"); ns = e ? atoi(e) : 2; if (ns < 2 || ns > 4) ns = 2; }
-  switch (ns) {
-    case 3: return launch_group_ns<3>(grp, flops, s);
-    case 4: return launch_group_ns<4>(grp, flops, s);
-    default: return launch_group_ns<2>(grp, flops, s);
-  }
+  if (big) return launch_group_ns<256, 256, 2>(grp, flops, s);
+  return launch_group_ns<128, 128, 2>(grp, flops, s);
 }
 
 // Large tiles when they still give every CU a tile; small tiles otherwise.
@@ -675,9 +686,7 @@ static bool use_big_tiles(int M, int N, bool m_must_divide) {
   if (N % 256 != 0) return false;
   if (m_must_divide && M % 256 != 0) return false;
   const long tiles = (long)((M + 255) / 256) * (N / 256);
-  static long min_tiles = -1;                 // KFKB_BIG_TILE_MIN overrides the threshold for experiments
-  if (min_tiles < 0) { const char* e = getenv("KFKB_BIG_TILE_MIN"); min_tiles = e ? atol(e) : 192; }
-  return tiles >= min_tiles;
+  return tiles >= big_tile_min();
 }
 
 template <int EPI>
