@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gpt2-medium-stage", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, used to scale "
+                         "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -156,6 +159,17 @@ def main():
     peak = {"mfma": PEAK_BF16_TFLOPS, "hbm": PEAK_HBM_GBS, "alu": PEAK_F32_TFLOPS}[dom["bound"]]
     roofline = dict(bound=dom["bound"], kernel=dom["name"], achieved=dom["achieved"], peak=peak, unit=dom["unit"],
                     frac=dom["achieved"] / peak, traffic=None, avg_us=dom["avg_us"], share_of_kernel_time=dom["share"])
+    # HBM traffic of that kernel, where a rocprofv3 --pmc measurement of this workload is on file
+    try:
+        with open(os.path.join(ROOT, "profiles", "stage_%s_hbm_traffic.json" % args.workload.replace("-stage", "").replace("-", ""))) as f:
+            tj = json.load(f)
+        key = dom["name"].replace(" ", "")
+        hit = [v for k, v in tj["kernels"].items() if k.startswith(key.rstrip(">")) or key.startswith(k.rstrip(">"))]
+        if hit:
+            roofline["traffic"] = hit[0]["read_bytes"] + hit[0]["write_bytes"]
+            roofline["traffic_source"] = "profiles/stage_%s_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a 1 GiB copy)" % args.workload.replace("-stage", "").replace("-", "")
+    except (OSError, ValueError, KeyError):
+        pass
     gemm = [s for s in stats if s["name"].startswith("gemm_bf16")]
     if gemm:
         roofline["all_gemm_tflops"] = sum(s["work"] for s in gemm) / (sum(s["total_ms"] for s in gemm) * 1e-3) / 1e12
@@ -199,6 +213,11 @@ def main():
         "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
     }
     st.close()
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
+        c = torch.empty_like(a)
+        c.copy_(a)
+        torch.cuda.synchronize()
     print(json.dumps(out))
 
 

@@ -94,6 +94,23 @@ __device__ __forceinline__ float exp2_raw(float x) { return __builtin_amdgcn_exp
 // streamed-row offset (inside a 32-row tile) of accumulator register r for lane half hh
 __device__ __forceinline__ int acc_row(int r, int hh) { return (r >> 2) * 8 + hh * 4 + (r & 3); }
 
+// Block -> (row block, sample*head).  Work per block grows with the row-block index (causal), and consecutive
+// block ids are dealt round-robin to the 8 XCDs, each with its own L2.  All row blocks of one (sample, head)
+// are therefore given to ONE XCD (its K and V, or Q and dO, then stay in that L2), longest first, and every XCD
+// gets the same mix of short and long blocks.  Falls back to a rotation when sample*head does not divide by 8.
+__device__ __forceinline__ void block_to_work(int& rb, int& bh) {
+  const int gx = gridDim.x, gy = gridDim.y;
+  if (gy % 8 == 0) {
+    const int lin = blockIdx.y * gx + blockIdx.x;
+    const int xcd = lin & 7, n = lin >> 3;
+    bh = xcd + 8 * (n / gx);
+    rb = gx - 1 - n % gx;
+  } else {
+    bh = blockIdx.y;
+    rb = (blockIdx.x + blockIdx.y) % gx;
+  }
+}
+
 // ------------------------------------------------------------------------------------------------
 // forward
 // ------------------------------------------------------------------------------------------------
@@ -109,10 +126,9 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  // Work per block grows with the query-block index (causal).  Consecutive block ids go to different XCDs, so
-  // the query block is rotated by the (sample, head) index: every XCD then sees every query-block index.
-  const int qb = (blockIdx.x + blockIdx.y) % gridDim.x;
-  const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
+  int qb, bh;
+  block_to_work(qb, bh);
+  const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
   const int q0 = qb * 128, qw0 = q0 + wave * 32;
@@ -238,8 +254,9 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  const int qb = (blockIdx.x + blockIdx.y) % gridDim.x;   // rotated: see the forward kernel
-  const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
+  int qb, bh;
+  block_to_work(qb, bh);
+  const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
   const int q0 = qb * 128, qw0 = q0 + wave * 32;
@@ -359,8 +376,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  const int kb = (blockIdx.x + blockIdx.y) % gridDim.x;   // rotated: see the forward kernel
-  const int bi = blockIdx.y / heads, hd = blockIdx.y % heads;
+  int kb, bh;
+  block_to_work(kb, bh);
+  kb = gridDim.x - 1 - kb;                          // for keys the early blocks are the long ones
+  const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
   const bf16_t* dobase = d_o + (size_t)bi * T * H;
