@@ -152,7 +152,13 @@ int stage_last_k(void);
  * Measures three 1 ms delay kernels, one per stream; call while the stage is idle. */
 int stage_side_streams_overlap(void);
 int stage_zero_grads(void);               /* enqueues a fill of grad_accum on the compute stream */
-int stage_sync(void);                     /* waits for compute, send and receive streams */
+/* Weight-gradient stream (on by default): the weight and bias gradients of a block (the gradient-accumulation
+ * task nodes of paper section 2.4) are enqueued on a stream of their own and run beside the chain of input
+ * gradients of the following blocks and of the next op; the accumulation order, hence every result bit, is
+ * unchanged.  An op's end time in stage_get_order is the end of its chain (dX is complete then).  0 puts them
+ * back on the compute stream.  Call while no micro-batch is live.  Returns the previous setting. */
+int stage_set_wgrad_stream(int enable);
+int stage_sync(void);                     /* waits for compute, weight-gradient, send and receive streams */
 int stage_sync_timeout(double seconds);   /* same, polling; KFKB_E_TIMEOUT if not done in time */
 int stage_destroy(void);
 

@@ -8,6 +8,7 @@
 #include <chrono>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <thread>
@@ -178,11 +179,25 @@ struct Stage {
   char* wt = nullptr;                        // bf16 only: weight matrices stored [out, in]
   std::vector<char*> stash; std::vector<int> stash_free;
   Pool xs, dys, ys, dxs;
-  char* t_n[4] = {nullptr, nullptr, nullptr, nullptr}; char* t_mf = nullptr; char* t_3n = nullptr;
-  float* dsum = nullptr; float* red = nullptr;
+  // backward scratch: t_n0 (dc, d_o, da in turn); dx1, du, dqkv alternate between two buffers and the block input
+  // gradient rotates over three, so that the weight gradients of a block can still read them while the next
+  // block's chain runs
+  char* t_n0 = nullptr; char* t_dx1[2] = {nullptr, nullptr}; char* t_dxr[3] = {nullptr, nullptr, nullptr};
+  char* t_mf[2] = {nullptr, nullptr}; char* t_3n[2] = {nullptr, nullptr};
+  float* dsum = nullptr; float* red = nullptr; float* red_w = nullptr;
   size_t stash_block_bytes = 0, stash_bytes = 0;
   // streams and events
   hipStream_t sc = nullptr, ss = nullptr, sr = nullptr;
+  // weight-gradient stream: the weight and bias gradients of a block run here, beside the chain of input
+  // gradients on sc; gradient accumulation keeps its order because this stream is in order
+  hipStream_t sw = nullptr;
+  bool wgrad_overlap = true;
+  static constexpr int kRing = 8;
+  hipEvent_t ev_chain[kRing] = {}, ev_wdone[kRing] = {};   // per block of a backward pass, reused round-robin
+  uint64_t wseq = 0;                                       // blocks of backward passes issued so far
+  hipEvent_t last_wdone = nullptr;
+  std::vector<hipEvent_t> ev_w;                            // per micro-batch: all its weight gradients are done
+  std::vector<hipEvent_t> stash_release;                   // per activation slot: last reader on sw (or null)
   std::vector<hipEvent_t> ev_x, ev_dy, ev_f0, ev_f1, ev_b0, ev_b1, ev_ys, ev_dxs;
   hipEvent_t ev_epoch = nullptr, ev_run_end = nullptr;
   bool epoch_valid = false, run_timed = false;
@@ -231,11 +246,11 @@ Carve carve_for(const Stage& s, int k_max) {
   c.dys = off; off += (size_t)c.n_io * act;
   c.ys = off; off += (size_t)c.n_io * act;
   c.dxs = off; off += (size_t)c.n_io * act;
-  c.tn = off; off += 4 * act;
-  c.tmf = off; off += align_up((size_t)s.m * s.F * s.esz);
-  c.t3n = off; off += align_up(3 * s.n * s.esz);
+  c.tn = off; off += 6 * act;
+  c.tmf = off; off += 2 * align_up((size_t)s.m * s.F * s.esz);
+  c.t3n = off; off += 2 * align_up(3 * s.n * s.esz);
   c.dsum = off; off += align_up((size_t)s.b * s.heads * s.T * 4);
-  c.red = off; off += align_up(red_floats(s) * 4);
+  c.red = off; off += 2 * align_up(red_floats(s) * 4);
   c.total = off;
   return c;
 }
@@ -333,24 +348,29 @@ int compute_forward(int slot, const char* x_in, char* y_out) {
 }
 
 int compute_backward(int slot, const char* x_in, const char* dy_in, char* dx_out) {
-  const Stage& s = g;
+  Stage& s = g;
   const char* dy = dy_in;
-  char* du = s.t_mf;
-  char* dc = s.t_n[0];
-  char* dx1 = s.t_n[1];
-  char* d_o = s.t_n[0];          // dc is dead once dx1 exists
-  char* da = s.t_n[0];           // d_o is dead once dqkv exists
-  char* dqkv = s.t_3n;
-  // the four weight-gradient products of a block are issued together once their operands exist (all of
-  // them outlive the block's backward): one launch fills the chip where each alone would not
+  char* dc = s.t_n0;
+  char* d_o = s.t_n0;            // dc is dead once dx1 exists
+  char* da = s.t_n0;             // d_o is dead once dqkv exists
+  // the four weight-gradient products of a block are issued together once their operands exist: one launch
+  // fills the chip where each alone would not.  With the weight-gradient stream they, and the four bias
+  // gradients, run beside the next block's chain; the operands they read (du, dx1, dqkv, this block's dy)
+  // sit in buffers that the chain reuses only two blocks later, after waiting for them.
   GemmArgs wg[4];
   auto wgrad = [&](int i, int in, int out, const void* x, const void* dyv, float* acc) {
     wg[i] = GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, in, out, s.m, x, dyv, nullptr, nullptr, nullptr, nullptr, acc};
   };
   for (int l = s.L - 1; l >= 0; l--) {
+    const uint64_t seq = s.wseq++;
+    const int par = (int)(seq & 1), ring = (int)(seq % Stage::kRing);
+    char* du = s.t_mf[par];
+    char* dqkv = s.t_3n[par];
+    char* dx1 = s.t_dx1[par];
     StashView v = view(s, slot, l);
     const char* x = (l == 0) ? x_in : view(s, slot, l - 1).y;
-    char* dx = (l == 0) ? dx_out : s.t_n[2 + (l & 1)];
+    char* dx = (l == 0) ? dx_out : s.t_dxr[seq % 3];
+    if (s.wgrad_overlap && seq >= 2) HIPCHK(hipStreamWaitEvent(s.sc, s.ev_wdone[(seq - 2) % Stage::kRing], 0));
     // y = x1 + g W2 + b2
     wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
@@ -369,21 +389,31 @@ int compute_backward(int slot, const char* x_in, const char* dy_in, char* dx_out
     TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
     // a = LN1(x), plus the residual path
     HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), s.red, s.m, s.H, s.sc));
-    // du, dx1, dqkv and this block's dy are still intact here; the next block overwrites them
+    // bias and weight gradients of this block
+    hipStream_t sw = s.sc;
+    if (s.wgrad_overlap) {
+      HIPCHK(hipEventRecord(s.ev_chain[ring], s.sc));
+      HIPCHK(hipStreamWaitEvent(s.sw, s.ev_chain[ring], 0));
+      sw = s.sw;
+    }
     {
       const void* srcs[4] = {dqkv, du, dy, dx1};
       float* outs[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
       const int widths[4] = {3 * s.H, s.F, s.H, s.H};
-      HIPCHK(launch_colsum_group(s.dt, 4, srcs, outs, widths, s.red, s.m, s.sc));
+      HIPCHK(launch_colsum_group(s.dt, 4, srcs, outs, widths, s.red_w, s.m, sw));
     }
     if (s.dt == DT_BF16) {
       for (int i = 0; i < 4; i++) {
         const char* why = gemm_bf16_check(wg[i]);
         if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
       }
-      HIPCHK(launch_gemm_bf16_tn_group(wg, 4, s.sc));
+      HIPCHK(launch_gemm_bf16_tn_group(wg, 4, sw));
     } else {
-      for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], s.sc));
+      for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], sw));
+    }
+    if (s.wgrad_overlap) {
+      HIPCHK(hipEventRecord(s.ev_wdone[ring], s.sw));
+      s.last_wdone = s.ev_wdone[ring];
     }
     dy = dx;
   }
@@ -443,6 +473,10 @@ int do_forward(int mbi) {
   if (!g.epoch_valid) TRY(begin_log_epoch());
   HIPCHK(hipStreamWaitEvent(g.sc, g.ev_x[mbi], 0));
   if (g.ys.release[ybuf]) HIPCHK(hipStreamWaitEvent(g.sc, g.ys.release[ybuf], 0));
+  if (g.stash_release[st.stash]) {                   // weight gradients of the slot's last owner still read it
+    HIPCHK(hipStreamWaitEvent(g.sc, g.stash_release[st.stash], 0));
+    g.stash_release[st.stash] = nullptr;
+  }
   HIPCHK(hipEventRecord(g.ev_f0[mbi], g.sc));
   TRY(compute_forward(st.stash, g.xs.buf[st.x_slot], g.ys.buf[ybuf]));
   HIPCHK(hipEventRecord(g.ev_f1[mbi], g.sc));
@@ -473,6 +507,12 @@ int do_backward(int mbi) {
   HIPCHK(hipEventRecord(g.ev_b0[mbi], g.sc));
   TRY(compute_backward(st.stash, g.xs.buf[st.x_slot], g.dys.buf[st.dy_slot], g.dxs.buf[dxbuf]));
   HIPCHK(hipEventRecord(g.ev_b1[mbi], g.sc));
+  hipEvent_t ev_done = g.ev_b1[mbi];                 // after it nothing reads the micro-batch's activations or dY
+  if (g.wgrad_overlap) {
+    HIPCHK(hipEventRecord(g.ev_w[mbi], g.sw));
+    ev_done = g.ev_w[mbi];
+    g.stash_release[st.stash] = ev_done;
+  }
   g.log.push_back({KFKB_OP_B, mbi});
   const size_t bytes = g.n * g.esz;
   HIPCHK(hipStreamWaitEvent(g.ss, g.ev_b1[mbi], 0));
@@ -483,7 +523,7 @@ int do_backward(int mbi) {
   // early release: the micro-batch's activations and its input slots return to their pools
   g.stash_free.push_back(st.stash);
   g.xs.give(st.x_slot, g.ev_b1[mbi]);
-  g.dys.give(st.dy_slot, g.ev_b1[mbi]);
+  g.dys.give(st.dy_slot, ev_done);
   st.stash = st.x_slot = st.dy_slot = -1;
   st.bwd_done = true;
   return 0;
@@ -589,6 +629,10 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   HIPCHK(hipStreamCreateWithFlags(&g.sc, hipStreamNonBlocking));
   HIPCHK(hipStreamCreateWithFlags(&g.ss, hipStreamNonBlocking));
   HIPCHK(hipStreamCreateWithFlags(&g.sr, hipStreamNonBlocking));
+  HIPCHK(hipStreamCreateWithFlags(&g.sw, hipStreamNonBlocking));
+  for (int i = 0; i < Stage::kRing; i++) { HIPCHK(hipEventCreate(&g.ev_chain[i])); HIPCHK(hipEventCreate(&g.ev_wdone[i])); }
+  TRY(make_events(g.ev_w, g.Mmax));
+  { const char* e = getenv("KFKB_WGRAD_STREAM"); g.wgrad_overlap = !(e && e[0] == '0'); }
   TRY(make_events(g.ev_x, g.Mmax)); TRY(make_events(g.ev_dy, g.Mmax));
   TRY(make_events(g.ev_f0, g.Mmax)); TRY(make_events(g.ev_f1, g.Mmax));
   TRY(make_events(g.ev_b0, g.Mmax)); TRY(make_events(g.ev_b1, g.Mmax));
@@ -638,10 +682,17 @@ int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum, const
     for (int i = 0; i < cnt; i++) p.buf[i] = g.ws + off + (size_t)i * act;
   };
   fill_pool(g.xs, c.xs, c.n_x); fill_pool(g.dys, c.dys, c.n_io); fill_pool(g.ys, c.ys, c.n_io); fill_pool(g.dxs, c.dxs, c.n_io);
-  for (int i = 0; i < 4; i++) g.t_n[i] = g.ws + c.tn + (size_t)i * act;
-  g.t_mf = g.ws + c.tmf; g.t_3n = g.ws + c.t3n;
+  g.t_n0 = g.ws + c.tn;
+  for (int i = 0; i < 2; i++) g.t_dx1[i] = g.ws + c.tn + (size_t)(1 + i) * act;
+  for (int i = 0; i < 3; i++) g.t_dxr[i] = g.ws + c.tn + (size_t)(3 + i) * act;
+  for (int i = 0; i < 2; i++) {
+    g.t_mf[i] = g.ws + c.tmf + (size_t)i * align_up((size_t)g.m * g.F * g.esz);
+    g.t_3n[i] = g.ws + c.t3n + (size_t)i * align_up(3 * g.n * g.esz);
+  }
   g.dsum = reinterpret_cast<float*>(g.ws + c.dsum);
   g.red = reinterpret_cast<float*>(g.ws + c.red);
+  g.red_w = reinterpret_cast<float*>(g.ws + c.red + align_up(red_floats(g) * 4));
+  g.stash_release.assign(c.n_stash, nullptr);
   reset_iteration_state();
   g.epoch_valid = false; g.run_timed = false; g.log.clear();
   g.bound = true;
@@ -724,6 +775,7 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
   // the run ends when the last transfer has landed
   hipEvent_t tail_s = g.ev_dxs[order.back().mb];
   HIPCHK(hipStreamWaitEvent(g.sc, tail_s, 0));
+  if (g.wgrad_overlap) HIPCHK(hipStreamWaitEvent(g.sc, g.ev_w[order.back().mb], 0));
   HIPCHK(hipEventRecord(g.ev_run_end, g.sc));
   g.run_timed = true;
   return 0;
@@ -746,13 +798,25 @@ int stage_side_streams_overlap(void) {
 
 int stage_zero_grads(void) {
   if (!g.bound) return fail(KFKB_E_STATE, "stage_zero_grads before stage_bind");
+  if (g.last_wdone) HIPCHK(hipStreamWaitEvent(g.sc, g.last_wdone, 0));   // accumulation still in flight
   HIPCHK(launch_fill_zero(g.grad, (size_t)g.L * g.po.total, g.sc));
   return 0;
+}
+
+int stage_set_wgrad_stream(int enable) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_set_wgrad_stream before stage_init");
+  if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_wgrad_stream while micro-batches are live");
+  HIPCHK(hipStreamSynchronize(g.sc));
+  HIPCHK(hipStreamSynchronize(g.sw));
+  const int prev = g.wgrad_overlap ? 1 : 0;
+  g.wgrad_overlap = enable != 0;
+  return prev;
 }
 
 int stage_sync(void) {
   if (!g.inited) return fail(KFKB_E_STATE, "stage_sync before stage_init");
   HIPCHK(hipStreamSynchronize(g.sc));
+  HIPCHK(hipStreamSynchronize(g.sw));
   HIPCHK(hipStreamSynchronize(g.sr));
   HIPCHK(hipStreamSynchronize(g.ss));
   return 0;
@@ -763,7 +827,7 @@ int stage_sync_timeout(double seconds) {
   const auto t0 = std::chrono::steady_clock::now();
   for (;;) {
     bool done = true;
-    for (hipStream_t s : {g.sc, g.sr, g.ss}) {
+    for (hipStream_t s : {g.sc, g.sw, g.sr, g.ss}) {
       hipError_t e = hipStreamQuery(s);
       if (e == hipErrorNotReady) done = false;
       else if (e != hipSuccess) return fail(KFKB_E_HIP, "hipStreamQuery failed: %s", hipGetErrorString(e));
@@ -800,11 +864,12 @@ double stage_last_run_ms(void) {
 
 int stage_destroy(void) {
   if (!g.inited) return 0;
-  hipStreamSynchronize(g.sc); hipStreamSynchronize(g.sr); hipStreamSynchronize(g.ss);
-  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs})
+  hipStreamSynchronize(g.sc); hipStreamSynchronize(g.sw); hipStreamSynchronize(g.sr); hipStreamSynchronize(g.ss);
+  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w})
     for (auto e : *v) hipEventDestroy(e);
+  for (int i = 0; i < Stage::kRing; i++) { hipEventDestroy(g.ev_chain[i]); hipEventDestroy(g.ev_wdone[i]); }
   hipEventDestroy(g.ev_epoch); hipEventDestroy(g.ev_run_end);
-  hipStreamDestroy(g.sc); hipStreamDestroy(g.ss); hipStreamDestroy(g.sr);
+  hipStreamDestroy(g.sc); hipStreamDestroy(g.ss); hipStreamDestroy(g.sr); hipStreamDestroy(g.sw);
   g = Stage{};
   g_cfg_set = false;
   return 0;
