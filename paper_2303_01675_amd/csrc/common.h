@@ -64,18 +64,21 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-// ---- GELU, tanh form: 0.5 u (1 + tanh(c0 (u + c1 u^3))) ----------------------------------------
-// tanh(z) = 1 - 2 / (1 + exp(2 z)); expf overflow to +inf gives exactly 1, underflow gives -1.
-__device__ __forceinline__ float tanh_f(float z) { return 1.0f - 2.0f / (1.0f + __expf(2.0f * z)); }
-__device__ __forceinline__ float gelu_f(float u) {
-  const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
-  return 0.5f * u * (1.0f + tanh_f(z));
+// ---- GELU, tanh form: 0.5 u (1 + tanh(z)), z = c0 (u + c1 u^3) ---------------------------------
+// With s = 1 / (1 + exp(-2 z)): 0.5 (1 + tanh z) = s and 1 - tanh^2 z = 4 s (1 - s), hence
+//   gelu(u) = u s,   gelu'(u) = s + u s (1 - s) 2 z'(u),   2 z' = 2 c0 (1 + 3 c1 u^2).
+// exp(-2 z) is taken as exp2 of a polynomial in u; its overflow to +inf gives s = 0, its underflow s = 1.
+__device__ __forceinline__ float gelu_sigmoid_f(float u) {
+  constexpr float k0 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;   // -2 c0 log2(e)
+  constexpr float k1 = k0 * 0.044715f;
+  const float e = __builtin_amdgcn_exp2f(u * (k0 + k1 * u * u));
+  return __builtin_amdgcn_rcpf(1.0f + e);
 }
+__device__ __forceinline__ float gelu_f(float u) { return u * gelu_sigmoid_f(u); }
 __device__ __forceinline__ float gelu_grad_f(float u) {
-  const float z = 0.7978845608028654f * (u + 0.044715f * u * u * u);
-  const float t = tanh_f(z);
-  const float dz = 0.7978845608028654f * (1.0f + 3.0f * 0.044715f * u * u);
-  return 0.5f * (1.0f + t) + 0.5f * u * (1.0f - t * t) * dz;
+  constexpr float d0 = 2.0f * 0.7978845608028654f, d1 = d0 * 3.0f * 0.044715f;
+  const float s = gelu_sigmoid_f(u);
+  return s + u * s * (1.0f - s) * (d0 + d1 * u * u);
 }
 
 // ---- optional per-kernel timing -------------------------------------------------------------------

@@ -5,17 +5,21 @@
 //   TN:  C[M,N] = A[K,M]^T . B[K,N]     both operands strided along the reduction axis, which is
 //        the token axis (weight gradients: A = layer input, B = output gradient)
 //
-// One work-group = 256 threads = 2 x 2 waves computes a BM x BN tile in 64-deep slices.  Slices go
-// global -> registers -> LDS (two LDS stages, one barrier per slice).  NT tiles are stored
-// [row][64] with the 16-byte chunk index XOR-ed by ((row >> 1) & 7) so that the 16-byte fragment reads
-// are bank-conflict free.  TN tiles are stored as they lie in memory,
-// [reduction row][BM] (XOR-swizzled), and fragments are fetched with the LDS transpose read
-// (ds_read_b64_tr_b16), which hands every lane four reduction-consecutive values of its column.
+// One work-group = 256 threads = 2 x 2 waves computes a BM x BN tile (256 x 256 or 128 x 128) in 32-deep chunks.
+// Four chunks live in LDS (a ring of four slots); they are filled by buffer loads that write straight into
+// LDS (no registers, no LDS store instructions, out-of-range rows read as zero), requested three to four
+// chunks ahead, one load instruction per group of MFMAs so that the loads of the four waves never queue up
+// behind each other.  Measured on the MI355X: the matrix pipe alone (no loads, no LDS reads) takes 1035 clocks
+// per chunk of a 256 x 256 tile, this loop about 1200; bursts of loads used to cost 1300 and more.
 //
-// The MFMA is issued with its operands swapped (A operand <- B tile, B operand <- A tile): the
-// accumulator of lane l then holds, for output row m = l % 32, four consecutive output columns per
-// register quad, so the epilogue reads bias / residual and writes C with 8-byte (bf16) or 16-byte
-// (fp32 accumulate) vectors.
+// NT chunks are stored [row][32] with the 16-byte piece index XOR-ed by ((row >> 2) & 3), TN chunks as they lie
+// in memory, [reduction row][BM], piece index XOR 4 * (row & 3), and read with the LDS transpose read
+// (ds_read_b64_tr_b16), which hands every lane four reduction-consecutive values of its column: both make
+// the fragment reads bank-conflict free on the 64-bank LDS.
+//
+// The MFMA is issued with its operands swapped (A operand <- B tile, B operand <- A tile): the accumulator of
+// lane l then holds, for output row m = l % 32, four consecutive output columns per register quad.  Finished
+// values are rounded once and go through LDS, so that C is written in whole rows, 16 bytes per lane.
 //
 // Block index -> tile: consecutive block ids land on different XCDs (8 of them, each with its own
 // L2), so block b works on tile (b % 8) * ceil(tiles/8) + b / 8: every XCD owns a contiguous run of
@@ -27,7 +31,7 @@
 
 namespace kfkb {
 
-constexpr int BK = 64;
+constexpr int BK = 64;             // slice depth of the register-staged TN kernel
 
 // position t of the tile order -> tile coordinates: groups of four tile-rows, column by column
 __device__ __forceinline__ void tile_from_linear(int t, int tiles_m, int tiles_n, int& tm, int& tn) {
@@ -90,234 +94,267 @@ __device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, i
   }
 }
 
-// ------------------------------------------------------------------------------------------------
-// Shared pieces of the two pipelined kernels.
-//
-// Pipeline (per work-group, NS LDS stages, ONE barrier per 64-deep slice; slice j lives in stage j % NS and
-// is requested NS - 1 slices ahead: a 128 x 128 tile spends only ~0.2 us of MFMA time on a slice, far less
-// than a trip to L2 / HBM, so several slices have to be in flight):
-//   slices are fetched with direct global->LDS loads (global_load_lds_dwordx4: no registers, no LDS
-//   store instructions); a wave instruction fills 1 KiB of LDS linearly, so the swizzle is applied on
-//   the global side: the lane that owns LDS position p fetches the logical chunk that belongs there.
-//   Inside a slice the fragments of k-step s+1 are read while the MFMAs of k-step s issue.  Before the
-//   last k-step of slice t every wave waits for its own loads of slice t+1, all waves meet, the loads
-//   of slice t+2 are issued into the stage slice t occupied (its last fragments are in registers by
-//   then), and the first fragments of slice t+1 are read during the last MFMAs of slice t.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ void dma16(const bf16_t* g, bf16_t* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
-}
-// s_waitcnt encodings (gfx9 layout: vmcnt [3:0]+[15:14], expcnt [6:4], lgkmcnt [11:8])
-// wait until at most N vector-memory operations (here: direct loads into LDS) of this wave are outstanding;
-// LGKM0 additionally waits for all LDS reads
-template <int N, bool LGKM0>
-__device__ __forceinline__ void wait_vm() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | (LGKM0 ? 0 : 0x0F00));
-}
 
-template <int TM, int TN>
-__device__ __forceinline__ void mfma_step(f32x16 (&acc)[TM][TN], const bf16x8 (&fa)[TM], const bf16x8 (&fb)[TN]) {
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-}
+constexpr int CK_ = 32;            // depth of a chunk
+constexpr int RING = 4;            // chunks in LDS
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-// scheduling hints for one k-step: READS LDS reads (and LOADS direct global->LDS loads) are issued one
-// per MFMA at the front of the step, the remaining MFMAs run at the end and cover the LDS latency of the
-// last reads before the next step needs them.
-template <int I, int SLOTS, int READS, int LOADS>
-__device__ __forceinline__ void interleave_slot() {
-  if constexpr (I < SLOTS) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    __builtin_amdgcn_sched_group_barrier(0x100, (READS + SLOTS - 1 - I) / SLOTS, 0);
-    if constexpr (LOADS > 0) __builtin_amdgcn_sched_group_barrier(0x020, (LOADS + SLOTS - 1 - I) / SLOTS, 0);
-    interleave_slot<I + 1, SLOTS, READS, LOADS>();
-  }
+__device__ __forceinline__ void dma16b(i32x4 rsrc, int voff, int soff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "m0");
 }
-template <int MFMAS, int READS, int LOADS>
-__device__ __forceinline__ void interleave_hint() {
-  constexpr int SLOTS = READS < MFMAS ? READS : MFMAS - 1;      // MFMAs that carry memory instructions
-  interleave_slot<0, SLOTS, READS, LOADS>();
-  __builtin_amdgcn_sched_group_barrier(0x008, MFMAS - SLOTS, 0);
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, size_t bytes) {
+  const unsigned long long a = (unsigned long long)p;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(a & 0xffffffffu));
+  r[1] = __builtin_amdgcn_readfirstlane((int)(a >> 32));
+  r[2] = __builtin_amdgcn_readfirstlane((int)(bytes > 0xFFFFFFFFull ? 0xFFFFFFFFull : bytes));
+  r[3] = 0x00020000;
+  return r;
 }
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
+}
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // ------------------------------------------------------------------------------------------------
-// NT kernel.  LDS tile [rows][64]: 8 chunks of 16 bytes per row, chunk index XOR ((row >> 1) & 7): a 16-byte
-// fragment read serves 16 lanes (16 consecutive rows) per clock from 64 banks, and two rows fill one 256-byte
-// bank window, so the 16 rows have to land on 16 different chunk slots of it.
+// The main loop shared by the NT and TN kernels.  LAYOUT supplies the DMA source offsets and the fragment reads.
+//   chunk kc lives in ring slot kc % 4.  One chunk = two 16-deep k-steps; a k-step = TN groups of TM MFMAs.
+//   Every group carries one DMA instruction (B part of chunk kc+3 during k-step 0, A part of chunk kc+4 during
+//   k-step 1) and up to PER fragment reads of the next k-step; nothing moves across group boundaries.
+//   Between the k-steps every wave waits for its own loads of chunk kc+1 and all waves meet: after that chunk
+//   kc+1 is complete in LDS and slot kc % 4 is free.
 // ------------------------------------------------------------------------------------------------
-template <int BM, int BN, int EPI, int NS>
-__global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                           const bf16_t* __restrict__ B, const bf16_t* __restrict__ bias,
-                                                           const bf16_t* __restrict__ residual, bf16_t* __restrict__ C,
-                                                           bf16_t* __restrict__ C2, float* __restrict__ Cacc,
-                                                           int tiles_m, int tiles_n) {
-  constexpr int TM = BM / 64, TN = BN / 64;          // 32x32 accumulator tiles per wave
-  constexpr int GA = BM / 32, GB = BN / 32;          // 8-row groups (1 KiB) each wave fetches per slice
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [NS][BM][64]
-  bf16_t* Bs = As + NS * BM * BK;                                     // [NS][BN][64]
-
-  int tm, tn; bool valid;
-  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
-  if (!valid) return;
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
-
-  // LDS position (row, lane & 7) holds logical chunk (lane & 7) ^ ((row >> 1) & 7); wave w fetches the 8-row groups
-  // i*4 + w, whose rows start at multiples of 8, so ((row >> 1) & 7) = 4 * (w & 1) + (lrow >> 1)
-  const int lrow = lane >> 3, lchunk = (lane & 7) ^ (((wave & 1) << 2) | (lrow >> 1));
-  const bf16_t* Ag[GA]; const bf16_t* Bg[GB];
-#pragma unroll
-  for (int i = 0; i < GA; i++) Ag[i] = A + (size_t)min(m0 + (i * 4 + wave) * 8 + lrow, M - 1) * K + lchunk * 8;
-#pragma unroll
-  for (int i = 0; i < GB; i++) Bg[i] = B + (size_t)(n0 + (i * 4 + wave) * 8 + lrow) * K + lchunk * 8;
-  auto issue = [&](int kt, int st) {
-#pragma unroll
-    for (int i = 0; i < GA; i++) dma16(Ag[i] + kt * BK, As + st * BM * BK + (i * 4 + wave) * 512);
-#pragma unroll
-    for (int i = 0; i < GB; i++) dma16(Bg[i] + kt * BK, Bs + st * BN * BK + (i * 4 + wave) * 512);
-  };
-  const int frow = lane & 31, fhalf = lane >> 5;
-  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
-#pragma unroll
-    for (int i = 0; i < TM; i++) {
-      const int r = wm0 + i * 32 + frow;
-      fa[i] = *reinterpret_cast<const bf16x8*>(As + ((st * BM + r) * 8 + ((ks * 2 + fhalf) ^ ((r >> 1) & 7))) * 8);
-    }
-#pragma unroll
-    for (int j = 0; j < TN; j++) {
-      const int r = wn0 + j * 32 + frow;
-      fb[j] = *reinterpret_cast<const bf16x8*>(Bs + ((st * BN + r) * 8 + ((ks * 2 + fhalf) ^ ((r >> 1) & 7))) * 8);
-    }
-  };
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; i++)
-#pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-  const int nk = K / BK;
-  constexpr int LPS = GA + GB;                       // loads each wave issues per slice
+template <int TM, int TN, typename L>
+__device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk) {
+  constexpr int LPC = 2 * TN;
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
 #pragma unroll
-  for (int j = 0; j < NS - 1; j++)
-    if (j < nk) issue(j, j);
-  if (nk >= NS - 1) wait_vm<(NS - 2) * LPS, false>(); else wait_vm<0, false>();   // slice 0 has landed
-  __syncthreads();
-  if (NS - 1 < nk) issue(NS - 1, NS - 1);
-  read_frags(0, 0, fa0, fb0);
-  // one slice; `more` = slice kt+NS exists (request it), `next` = slice kt+1 exists (start on its fragments)
-  auto slice = [&](int kt, int cur, bool more, bool next) {
-    read_frags(cur, 1, fa1, fb1);
-    mfma_step<TM, TN>(acc, fa0, fb0);
-    interleave_hint<TM * TN, TM + TN, 0>();
-    read_frags(cur, 2, fa0, fb0);
-    mfma_step<TM, TN>(acc, fa1, fb1);
-    interleave_hint<TM * TN, TM + TN, 0>();
-    read_frags(cur, 3, fa1, fb1);
-    mfma_step<TM, TN>(acc, fa0, fb0);
-    interleave_hint<TM * TN, TM + TN, 0>();
-    // own loads of slice kt+1 have landed; the last fragments of slice kt are in registers
-    if (more) wait_vm<(NS - 2) * LPS, true>(); else wait_vm<0, true>();
-    __syncthreads();
-    if (more) issue(kt + NS, cur);
-    if (next) read_frags(cur + 1 == NS ? 0 : cur + 1, 0, fa0, fb0);
-    mfma_step<TM, TN>(acc, fa1, fb1);
-    if (more) interleave_hint<TM * TN, TM + TN, GA + GB>();
-    else if (next) interleave_hint<TM * TN, TM + TN, 0>();
-  };
-  int kt = 0, cur = 0;
-  for (; kt + NS < nk; kt++) { slice(kt, cur, true, true); cur = cur + 1 == NS ? 0 : cur + 1; }
-  for (; kt + 1 < nk; kt++) { slice(kt, cur, false, true); cur = cur + 1 == NS ? 0 : cur + 1; }
-  slice(kt, cur, false, false);
-
+  for (int c = 0; c < RING; c++) {
 #pragma unroll
-  for (int i = 0; i < TM; i++) {
-    const int m = m0 + wm0 + i * 32 + frow;
-    if (m < M) {
+    for (int i = 0; i < TN; i++) lay.dma_a(i, c, c);
+    if (c < RING - 1) {
 #pragma unroll
-      for (int j = 0; j < TN; j++)
-#pragma unroll
-        for (int q = 0; q < 4; q++)
-          epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, bias, residual, C, C2, Cacc);
+      for (int i = 0; i < TN; i++) lay.dma_b(i, c, c);
     }
   }
-}
+  wait_vmcnt<2 * LPC + TN>();
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < TN; j++) fb0[j] = lay.rd_b(0, 0, j);
+#pragma unroll
+  for (int i = 0; i < TM; i++) fa0[i] = lay.rd_a(0, 0, i);
 
-// ------------------------------------------------------------------------------------------------
-// TN kernel, K % 64 == 0.  LDS tile [64 reduction rows][BM] as it lies in memory, the 16-byte chunk
-// index XOR 4 * (row & 3).  The LDS of gfx950 has 64 banks (256 bytes per clock): a transpose read serves
-// 32 lanes per clock, i.e. 64 contiguous bytes of each of four consecutive rows, and the XOR puts those four
-// rows into the four different 64-byte slots of the 256-byte bank window.
-// ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ bf16x8 lds_tr_pair(const bf16_t* p, int second_offset) {
-  typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + second_offset));
-  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
-  u.s.a = lo; u.s.b = hi;
-  return u.v;
-}
-
-template <int BM, int BN, int EPI, int NS>
-__device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                        bf16_t* __restrict__ C, float* __restrict__ Cacc, int tm, int tn, char* smem) {
-  constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
-  constexpr int RA = 64 / CA, RB = 64 / CB;          // tile rows one wave instruction (1 KiB) covers
-  constexpr int GA = BM / 32, GB = BN / 32;          // wave instructions per wave per slice
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [NS][64][BM]
-  bf16_t* Bs = As + NS * BK * BM;                                     // [NS][64][BN]
-  const int m0 = tm * BM, n0 = tn * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
-
-  // wave instruction g (0 .. 4*GA) of a slice covers tile rows g*RA .. +RA; lane -> (row, physical chunk)
-  const bf16_t* Ag[GA]; const bf16_t* Bg[GB];
+  auto step = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], bf16x8 (&na)[TM], bf16x8 (&nb)[TN], int nslot, int nks, auto&& dma) {
+    constexpr int NR = TM + TN;
+    constexpr int PER = (NR + TN - 2) / (TN - 1);      // reads per group so that the last group has none
 #pragma unroll
-  for (int i = 0; i < GA; i++) {
-    const int row = (i * 4 + wave) * RA + lane / CA, pc = lane % CA;
-    Ag[i] = A + (size_t)row * M + m0 + (pc ^ (4 * (row & 3))) * 8;
-  }
+    for (int j = 0; j < TN; j++) {
 #pragma unroll
-  for (int i = 0; i < GB; i++) {
-    const int row = (i * 4 + wave) * RB + lane / CB, pc = lane % CB;
-    Bg[i] = B + (size_t)row * N + n0 + (pc ^ (4 * (row & 3))) * 8;
-  }
-  auto issue = [&](int kt, int st) {
+      for (int r = j * PER; r < (j + 1) * PER && r < NR; r++) {
+        if (r == 0) nb[0] = lay.rd_b(nslot, nks, 0);
+        else if (r <= TM) na[r - 1] = lay.rd_a(nslot, nks, r - 1);
+        else nb[r - TM] = lay.rd_b(nslot, nks, r - TM);
+      }
+      dma(j);
 #pragma unroll
-    for (int i = 0; i < GA; i++) dma16(Ag[i] + (size_t)kt * BK * M, As + st * BK * BM + (i * 4 + wave) * 512);
-#pragma unroll
-    for (int i = 0; i < GB; i++) dma16(Bg[i] + (size_t)kt * BK * N, Bs + st * BK * BN + (i * 4 + wave) * 512);
+      for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
-  // transpose-read geometry: 16-lane group g covers columns (g & 1) * 16 .. + 16 and the reduction half
-  // g >> 1; inside the group lane j points at row j / 4, columns (j % 4) * 4 .. + 4.
-  const int g16 = lane >> 4, j16 = lane & 15;
-  const int tr_row = (g16 >> 1) * 8 + (j16 >> 2);
-  const int tr_col = (g16 & 1) * 16 + (j16 & 3) * 4;
-  auto read_frags = [&](int st, int ks, bf16x8 (&fa)[TM], bf16x8 (&fb)[TN]) {
-    const int row = ks * 16 + tr_row, sw = 4 * (row & 3);
+  auto chunk = [&](int kc, int slot) {
+    step(fa0, fb0, fa1, fb1, slot, 1, [&](int j) { lay.dma_b(j, kc + 3, (slot + 3) & 3); });
+    wait_vmcnt<2 * LPC>();
+    wait_lgkm0();
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    step(fa1, fb1, fa0, fb0, (slot + 1) & 3, 0, [&](int j) { lay.dma_a(j, kc + 4, slot); });
+  };
+  int kc = 0;
+  for (; kc + RING <= nk; kc += RING) {
+#pragma unroll
+    for (int s = 0; s < RING; s++) chunk(kc + s, s);
+  }
+  for (int s = 0; kc < nk; kc++, s++) chunk(kc, s);
+  wait_vmcnt<0>();
+}
+
+// NT operands: X[rows, K] row-major, both.  LDS chunk [rows][32]: 16-byte piece p of row r holds logical piece
+// p ^ ((r >> 2) & 3): the 16 rows a fragment read touches per clock land on 16 different 16-byte bank groups.
+template <int BM, int BN>
+struct NtLayout {
+  static constexpr int TM = BM / 64, TN = BN / 64, A_SLOT = BM * CK_, B_SLOT = BN * CK_;
+  static_assert(TM == TN, "one DMA instruction per MFMA group");
+  i32x4 ra, rb; unsigned lds0; int wave, nk; int voa[TN], vob[TN];
+  const bf16_t* fa_base[2]; const bf16_t* fb_base[2];
+  __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
+    wave = wave_; nk = K / CK_;
+    ra = make_rsrc(A, (size_t)M * K * 2); rb = make_rsrc(B, (size_t)N * K * 2);
+    lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    const int lrow = lane >> 2, lpiece = (lane & 3) ^ ((lane >> 4) & 3);
+#pragma unroll
+    for (int i = 0; i < TN; i++) {
+      voa[i] = ((m0 + (i * 4 + wave) * 16 + lrow) * K + lpiece * 8) * 2;
+      vob[i] = ((n0 + (i * 4 + wave) * 16 + lrow) * K + lpiece * 8) * 2;
+    }
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const int frow = lane & 31, fhalf = lane >> 5, fsw = (lane >> 2) & 3;
+    const bf16_t* As = reinterpret_cast<const bf16_t*>(smem);
+    const bf16_t* Bs = As + RING * A_SLOT;
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) {
+      fa_base[ks] = As + (wm0 + frow) * CK_ + (((ks * 2 + fhalf) ^ fsw) << 3);
+      fb_base[ks] = Bs + (wn0 + frow) * CK_ + (((ks * 2 + fhalf) ^ fsw) << 3);
+    }
+  }
+  __device__ __forceinline__ void dma_a(int i, int kc, int slot) { dma16b(ra, voa[i], min(kc, nk - 1) * (CK_ * 2), lds0 + (slot * A_SLOT + (i * 4 + wave) * 512) * 2); }
+  __device__ __forceinline__ void dma_b(int i, int kc, int slot) { dma16b(rb, vob[i], min(kc, nk - 1) * (CK_ * 2), lds0 + (RING * A_SLOT + slot * B_SLOT + (i * 4 + wave) * 512) * 2); }
+  __device__ __forceinline__ bf16x8 rd_a(int slot, int ks, int i) { return *reinterpret_cast<const bf16x8*>(fa_base[ks] + slot * A_SLOT + i * 32 * CK_); }
+  __device__ __forceinline__ bf16x8 rd_b(int slot, int ks, int j) { return *reinterpret_cast<const bf16x8*>(fb_base[ks] + slot * B_SLOT + j * 32 * CK_); }
+};
+
+// TN operands: X[K, cols] row-major, both (K = reduction).  LDS chunk [32 reduction rows][cols] as in memory, the
+// 16-byte piece index XOR 4 * (row & 3); fragments come out of LDS transpose reads (ds_read_b64_tr_b16), two per
+// fragment: each hands a lane four reduction-consecutive values of its column.
+template <int BM, int BN>
+struct TnLayout {
+  static constexpr int TM = BM / 64, TN = BN / 64, A_SLOT = BM * CK_, B_SLOT = BN * CK_;
+  static_assert(TM == TN, "one DMA instruction per MFMA group");
+  static constexpr int CA = BM / 8, CB = BN / 8;           // 16-byte pieces per row
+  static constexpr int RA = 64 / CA, RB = 64 / CB;         // rows one DMA instruction (1 KiB) covers
+  i32x4 ra, rb; unsigned lds0; int wave, nk, sa, sb; int voa[TN], vob[TN];
+  const bf16_t* fa_base[TM]; const bf16_t* fb_base[TN];
+  __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
+    wave = wave_; nk = K / CK_;
+    ra = make_rsrc(A, (size_t)K * M * 2); rb = make_rsrc(B, (size_t)K * N * 2);
+    sa = CK_ * M * 2; sb = CK_ * N * 2;                    // bytes per chunk step
+    lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+#pragma unroll
+    for (int i = 0; i < TN; i++) {
+      const int rowa = (i * 4 + wave) * RA + lane / CA, pa = lane % CA;
+      voa[i] = (rowa * M + m0 + (pa ^ (4 * (rowa & 3))) * 8) * 2;
+      const int rowb = (i * 4 + wave) * RB + lane / CB, pb = lane % CB;
+      vob[i] = (rowb * N + n0 + (pb ^ (4 * (rowb & 3))) * 8) * 2;
+    }
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const int g16 = lane >> 4, j16 = lane & 15;
+    const int tr_row = (g16 >> 1) * 8 + (j16 >> 2), tr_col = (g16 & 1) * 16 + (j16 & 3) * 4;
+    const int sw = 4 * (tr_row & 3);
+    const bf16_t* As = reinterpret_cast<const bf16_t*>(smem);
+    const bf16_t* Bs = As + RING * A_SLOT;
 #pragma unroll
     for (int i = 0; i < TM; i++) {
       const int col = wm0 + i * 32 + tr_col;
-      fa[i] = lds_tr_pair(As + (st * BK + row) * BM + (((col >> 3) ^ sw) << 3) + (col & 7), 4 * BM);
+      fa_base[i] = As + tr_row * BM + (((col >> 3) ^ sw) << 3) + (col & 7);
     }
 #pragma unroll
     for (int j = 0; j < TN; j++) {
       const int col = wn0 + j * 32 + tr_col;
-      fb[j] = lds_tr_pair(Bs + (st * BK + row) * BN + (((col >> 3) ^ sw) << 3) + (col & 7), 4 * BN);
+      fb_base[j] = Bs + tr_row * BN + (((col >> 3) ^ sw) << 3) + (col & 7);
     }
-  };
+  }
+  __device__ __forceinline__ void dma_a(int i, int kc, int slot) { dma16b(ra, voa[i], min(kc, nk - 1) * sa, lds0 + (slot * A_SLOT + (i * 4 + wave) * 512) * 2); }
+  __device__ __forceinline__ void dma_b(int i, int kc, int slot) { dma16b(rb, vob[i], min(kc, nk - 1) * sb, lds0 + (RING * A_SLOT + slot * B_SLOT + (i * 4 + wave) * 512) * 2); }
+  static __device__ __forceinline__ bf16x8 tr_pair(const bf16_t* p, int second_offset) {
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + second_offset));
+    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    u.s.a = lo; u.s.b = hi;
+    return u.v;
+  }
+  __device__ __forceinline__ bf16x8 rd_a(int slot, int ks, int i) { return tr_pair(fa_base[i] + slot * A_SLOT + ks * 16 * BM, 4 * BM); }
+  __device__ __forceinline__ bf16x8 rd_b(int slot, int ks, int j) { return tr_pair(fb_base[j] + slot * B_SLOT + ks * 16 * BN, 4 * BN); }
+};
 
+// ---- epilogues ---------------------------------------------------------------------------------
+// Accumulator of lane l, register 4 q + e: row (l % 32) of the 32 x 32 tile, column q * 8 + (l / 32) * 4 + e.
+// The finished values (bias, residual or GELU derivative applied in fp32, rounded once) go through LDS so
+// that every row is written with 16 bytes per lane, whole rows at a time; BIAS_GELU takes the GELU of the
+// rounded pre-activation on the way out.
+template <int BM, int BN> constexpr size_t epilogue_lds_bytes() { return (size_t)4 * (BM / 2) * (BN + 16); }
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64], char* smem, int M, int N, int m0, int n0, int lane, int wave,
+                                                const bf16_t* __restrict__ bias, const bf16_t* __restrict__ residual,
+                                                bf16_t* __restrict__ C, bf16_t* __restrict__ C2) {
+  constexpr int TM = BM / 64, TN = BN / 64, WR = BM / 2, WC = BN / 2;
+  constexpr int RS = WC * 2 + 16;                                 // row stride in bytes
+  const int wm0 = (wave >> 1) * WR, wn0 = (wave & 1) * WC;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  constexpr bool HAS_BIAS = EPI == KFKB_EPI_BIAS || EPI == KFKB_EPI_BIAS_GELU || EPI == KFKB_EPI_BIAS_RES;
+  constexpr bool HAS_RES = EPI == KFKB_EPI_BIAS_RES || EPI == KFKB_EPI_GELU_BWD;
+  __syncthreads();                                                // every wave is done with the ring
+  char* ew = smem + wave * (WR * RS);
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    const int m = min(m0 + wm0 + i * 32 + frow, M - 1);           // rows past M are computed and dropped
+    bf16x4 rr[TN][4];
+    if constexpr (HAS_RES) {
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+          rr[j][q] = *reinterpret_cast<const bf16x4*>(residual + (size_t)m * N + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+    }
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
+        if constexpr (HAS_BIAS) {
+          const bf16x4 b = *reinterpret_cast<const bf16x4*>(bias + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] += (float)b[e];
+        }
+        if constexpr (EPI == KFKB_EPI_BIAS_RES) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] += (float)rr[j][q][e];
+        }
+        if constexpr (EPI == KFKB_EPI_GELU_BWD) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] *= gelu_grad_f((float)rr[j][q][e]);
+        }
+        bf16x4 o;
+#pragma unroll
+        for (int e = 0; e < 4; e++) o[e] = (bf16_t)v[e];
+        *reinterpret_cast<bf16x4*>(ew + (i * 32 + frow) * RS + (j * 32 + q * 8 + fhalf * 4) * 2) = o;
+      }
+  }
+  wait_lgkm0();
+  constexpr int LPR = WC / 8, RPI = 64 / LPR;                     // lanes per row (16 bytes each), rows per instruction
+  const int er = lane / LPR, ec = lane % LPR;
+#pragma unroll
+  for (int r0 = 0; r0 < WR; r0 += RPI) {
+    const int r = r0 + er, m = m0 + wm0 + r;
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(ew + r * RS + ec * 16);
+    if (m < M) {
+      const size_t o = (size_t)m * N + n0 + wn0 + ec * 8;
+      *reinterpret_cast<bf16x8*>(C + o) = v;
+      if constexpr (EPI == KFKB_EPI_BIAS_GELU) {
+        bf16x8 gl;
+#pragma unroll
+        for (int e = 0; e < 8; e++) gl[e] = (bf16_t)gelu_f((float)v[e]);
+        *reinterpret_cast<bf16x8*>(C2 + o) = gl;
+      }
+    }
+  }
+}
+
+template <int BM, int BN, int EPI>
+__global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                                 const bf16_t* __restrict__ bias, const bf16_t* __restrict__ residual,
+                                                 bf16_t* __restrict__ C, bf16_t* __restrict__ C2, float* __restrict__ Cacc,
+                                                 int tiles_m, int tiles_n) {
+  constexpr int TM = BM / 64, TN = BN / 64;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int tm, tn; bool valid;
+  tile_of_block(tiles_m, tiles_n, tm, tn, valid);
+  if (!valid) return;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  NtLayout<BM, BN> lay;
+  lay.init(smem, A, B, M, N, K, m0, n0, lane, wave);
   f32x16 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; i++)
@@ -325,55 +362,61 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
     for (int j = 0; j < TN; j++)
 #pragma unroll
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
-
-  const int nk = K / BK;
-  constexpr int LPS = GA + GB;                       // loads each wave issues per slice
-  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  main_loop<TM, TN>(lay, acc, K / CK_);
+  if constexpr (EPI == KFKB_EPI_ACCUM) {
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2), frow = lane & 31, fhalf = lane >> 5;
 #pragma unroll
-  for (int j = 0; j < NS - 1; j++)
-    if (j < nk) issue(j, j);
-  if (nk >= NS - 1) wait_vm<(NS - 2) * LPS, false>(); else wait_vm<0, false>();   // slice 0 has landed
-  __syncthreads();
-  if (NS - 1 < nk) issue(NS - 1, NS - 1);
-  read_frags(0, 0, fa0, fb0);
-  // one slice; `more` = slice kt+NS exists (request it), `next` = slice kt+1 exists (start on its fragments)
-  auto slice = [&](int kt, int cur, bool more, bool next) {
-    read_frags(cur, 1, fa1, fb1);
-    mfma_step<TM, TN>(acc, fa0, fb0);
-    interleave_hint<TM * TN, 2 * (TM + TN), 0>();
-    read_frags(cur, 2, fa0, fb0);
-    mfma_step<TM, TN>(acc, fa1, fb1);
-    interleave_hint<TM * TN, 2 * (TM + TN), 0>();
-    read_frags(cur, 3, fa1, fb1);
-    mfma_step<TM, TN>(acc, fa0, fb0);
-    interleave_hint<TM * TN, 2 * (TM + TN), 0>();
-    // own loads of slice kt+1 have landed; the last fragments of slice kt are in registers
-    if (more) wait_vm<(NS - 2) * LPS, true>(); else wait_vm<0, true>();
-    __syncthreads();
-    if (more) issue(kt + NS, cur);
-    if (next) read_frags(cur + 1 == NS ? 0 : cur + 1, 0, fa0, fb0);
-    mfma_step<TM, TN>(acc, fa1, fb1);
-    if (more) interleave_hint<TM * TN, 2 * (TM + TN), GA + GB>();
-    else if (next) interleave_hint<TM * TN, 2 * (TM + TN), 0>();
-  };
-  int kt = 0, cur = 0;
-  for (; kt + NS < nk; kt++) { slice(kt, cur, true, true); cur = cur + 1 == NS ? 0 : cur + 1; }
-  for (; kt + 1 < nk; kt++) { slice(kt, cur, false, true); cur = cur + 1 == NS ? 0 : cur + 1; }
-  slice(kt, cur, false, false);
-
-  const int frow = lane & 31, fhalf = lane >> 5;
+    for (int i = 0; i < TM; i++) {
+      const int m = m0 + wm0 + i * 32 + frow;
+      if (m < M) {
 #pragma unroll
-  for (int i = 0; i < TM; i++) {
-    const int m = m0 + wm0 + i * 32 + frow;
+        for (int j = 0; j < TN; j++)
 #pragma unroll
-    for (int j = 0; j < TN; j++)
-#pragma unroll
-      for (int q = 0; q < 4; q++)
-        epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, nullptr, nullptr, C, nullptr, Cacc);
+          for (int q = 0; q < 4; q++)
+            epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, bias, residual, C, C2, Cacc);
+      }
+    }
+  } else {
+    epilogue_staged<BM, BN, EPI>(acc, smem, M, N, m0, n0, lane, wave, bias, residual, C, C2);
   }
 }
 
-template <int BM, int BN, int EPI, int NS>
+// C[M,N] (+)= A[K,M]^T . B[K,N]; EPI NONE (bf16 C) or ACCUM (fp32 Cacc +=)
+template <int BM, int BN, int EPI>
+__device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
+                                        bf16_t* __restrict__ C, float* __restrict__ Cacc, int tm, int tn, char* smem) {
+  constexpr int TM = BM / 64, TN = BN / 64;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  TnLayout<BM, BN> lay;
+  lay.init(smem, A, B, M, N, K, m0, n0, lane, wave);
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; i++)
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
+  main_loop<TM, TN>(lay, acc, K / CK_);
+  if constexpr (EPI == KFKB_EPI_ACCUM) {
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2), frow = lane & 31, fhalf = lane >> 5;
+#pragma unroll
+    for (int i = 0; i < TM; i++) {
+      const int m = m0 + wm0 + i * 32 + frow;
+#pragma unroll
+      for (int j = 0; j < TN; j++)
+#pragma unroll
+        for (int q = 0; q < 4; q++)
+          epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, nullptr, nullptr, C, nullptr, Cacc);
+    }
+  } else {
+    epilogue_staged<BM, BN, KFKB_EPI_NONE>(acc, smem, M, N, m0, n0, lane, wave, nullptr, nullptr, C, nullptr);
+  }
+}
+
+
+template <int BM, int BN, int EPI>
 __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
                                                            const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
                                                            float* __restrict__ Cacc, int tiles_m, int tiles_n) {
@@ -381,7 +424,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
   int tm, tn; bool valid;
   tile_of_block(tiles_m, tiles_n, tm, tn, valid);
   if (!valid) return;
-  tn_tile<BM, BN, EPI, NS>(M, N, K, A, B, C, Cacc, tm, tn, smem);
+  tn_tile<BM, BN, EPI>(M, N, K, A, B, C, Cacc, tm, tn, smem);
 }
 
 // Several weight-gradient products that share the reduction length K (the token axis) in one launch:
@@ -389,7 +432,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
 struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const bf16_t* A; const bf16_t* B; float* Cacc; };
 struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 
-template <int BM, int BN, int NS>
+template <int BM, int BN>
 __global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int t = linear_of_block(grp.total_tiles);
@@ -400,7 +443,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp) 
   const TnProblem pr = grp.p[i];
   int tm, tn;
   tile_from_linear(t - pr.first_tile, pr.tiles_m, pr.tiles_n, tm, tn);
-  tn_tile<BM, BN, KFKB_EPI_ACCUM, NS>(pr.M, pr.N, grp.K, pr.A, pr.B, nullptr, pr.Cacc, tm, tn, smem);
+  tn_tile<BM, BN, KFKB_EPI_ACCUM>(pr.M, pr.N, grp.K, pr.A, pr.B, nullptr, pr.Cacc, tm, tn, smem);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -528,34 +571,28 @@ const char* gemm_bf16_check(const GemmArgs& g) {
   if (g.M <= 0 || g.N <= 0 || g.K <= 0) return "bf16 GEMM: empty shape";
   if (g.kind == KFKB_GEMM_NT) {
     if (g.N % 128 != 0) return "bf16 NT GEMM needs N % 128 == 0";
-    if (g.K % 64 != 0) return "bf16 NT GEMM needs K % 64 == 0";
+    if (g.K % 32 != 0) return "bf16 NT GEMM needs K % 32 == 0";
   } else if (g.kind == KFKB_GEMM_TN) {
     if (g.M % 128 != 0 || g.N % 128 != 0) return "bf16 TN GEMM needs M % 128 == 0 and N % 128 == 0";
     if (g.epilogue != KFKB_EPI_ACCUM && g.epilogue != KFKB_EPI_NONE) return "bf16 TN GEMM supports epilogues NONE and ACCUM";
   } else {
     return "bf16 GEMM supports the NT and TN forms";
   }
+  // the kernels address their operands with 32-bit byte offsets
+  if ((double)g.M * g.K * 2 >= 4294967296.0 || (double)g.N * g.K * 2 >= 4294967296.0) return "bf16 GEMM: an operand of 4 GiB or more";
   return nullptr;
 }
 
-// Pipeline depth of the 128 x 128 tiles (32 KiB of LDS per stage).  KFKB_STAGES_128 = 2, 3 or 4 overrides
-// the default for experiments.
-static int stages_128() {
-  static int v = 0;
-  if (v == 0) {
-    const char* e = getenv("KFKB_STAGES_128");
-    v = e ? atoi(e) : 2;
-    if (v < 2 || v > 4) v = 2;
-  }
-  return v;
+template <int BM, int BN> constexpr size_t tile_lds_bytes() {
+  return std::max((size_t)RING * (BM + BN) * CK_ * sizeof(bf16_t), epilogue_lds_bytes<BM, BN>());
 }
 
-template <int BM, int BN, int EPI, int NS>
-static hipError_t launch_nt_ns(const GemmArgs& g, hipStream_t s) {
+template <int BM, int BN, int EPI>
+static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  const size_t smem = (size_t)NS * (BM + BN) * BK * sizeof(bf16_t);
-  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, NS>;
+  constexpr size_t smem = tile_lds_bytes<BM, BN>();
+  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -566,15 +603,6 @@ static hipError_t launch_nt_ns(const GemmArgs& g, hipStream_t s) {
           (const bf16_t*)g.A, (const bf16_t*)g.B, (const bf16_t*)g.bias, (const bf16_t*)g.residual, (bf16_t*)g.C,
           (bf16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
-}
-template <int BM, int BN, int EPI>
-static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
-  if (BM == 256) return launch_nt_ns<BM, BN, EPI, 2>(g, s);
-  switch (stages_128()) {
-    case 2: return launch_nt_ns<BM, BN, EPI, 2>(g, s);
-    case 3: return launch_nt_ns<BM, BN, EPI, 3>(g, s);
-    default: return launch_nt_ns<BM, BN, EPI, (BM == 256 ? 2 : 4)>(g, s);   // 4 stages
-  }
 }
 
 template <int BM, int BN, int EPI>
@@ -594,12 +622,13 @@ static hipError_t launch_tn_staged(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int EPI, int NS>
-static hipError_t launch_tn_ns(const GemmArgs& g, hipStream_t s) {
+template <int BM, int BN, int EPI>
+static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
+  if (g.K % CK_ != 0) return launch_tn_staged<BM, BN, EPI>(g, s);
   const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  const size_t smem = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
-  auto kern = gemm_bf16_tn_kernel<BM, BN, EPI, NS>;
+  constexpr size_t smem = tile_lds_bytes<BM, BN>();
+  auto kern = gemm_bf16_tn_kernel<BM, BN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -611,22 +640,11 @@ static hipError_t launch_tn_ns(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int BM, int BN, int EPI>
-static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
-  if (g.K % BK != 0) return launch_tn_staged<BM, BN, EPI>(g, s);
-  if (BM == 256) return launch_tn_ns<BM, BN, EPI, 2>(g, s);
-  switch (stages_128()) {
-    case 2: return launch_tn_ns<BM, BN, EPI, 2>(g, s);
-    case 3: return launch_tn_ns<BM, BN, EPI, 3>(g, s);
-    default: return launch_tn_ns<BM, BN, EPI, (BM == 256 ? 2 : 4)>(g, s);
-  }
-}
-
-template <int BM, int BN, int NS>
-static hipError_t launch_group_ns(const TnGroup& grp, double flops, hipStream_t s) {
+template <int BM, int BN>
+static hipError_t launch_group(const TnGroup& grp, double flops, hipStream_t s) {
   const int grid = ((grp.total_tiles + 7) / 8) * 8;
-  const size_t smem = (size_t)NS * BK * (BM + BN) * sizeof(bf16_t);
-  auto kern = gemm_bf16_tn_grouped_kernel<BM, BN, NS>;
+  constexpr size_t smem = tile_lds_bytes<BM, BN>();
+  auto kern = gemm_bf16_tn_grouped_kernel<BM, BN>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -650,7 +668,7 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
   bool groupable = n <= 4;
   for (int i = 0; i < n; i++)
     groupable = groupable && g[i].kind == KFKB_GEMM_TN && g[i].epilogue == KFKB_EPI_ACCUM && g[i].K == g[0].K &&
-                g[i].K % BK == 0 && g[i].M % 128 == 0 && g[i].N % 128 == 0;
+                g[i].K % CK_ == 0 && g[i].M % 128 == 0 && g[i].N % 128 == 0 && gemm_bf16_check(g[i]) == nullptr;
   if (!groupable) {
     for (int i = 0; i < n; i++) {
       hipError_t e = launch_gemm_bf16(g[i], s);
@@ -658,7 +676,7 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
     }
     return hipSuccess;
   }
-  // 256 x 256 tiles when every problem divides into them and the group still gives every CU a tile
+  // 256 x 256 tiles when every problem divides into them and the group still gives most CUs a tile
   long big_tiles = 0;
   bool big = true;
   for (int i = 0; i < n; i++) {
@@ -677,11 +695,11 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
     grp.total_tiles += p.tiles_m * p.tiles_n;
     flops += 2.0 * g[i].M * g[i].N * g[i].K;
   }
-  if (big) return launch_group_ns<256, 256, 2>(grp, flops, s);
-  return launch_group_ns<128, 128, 2>(grp, flops, s);
+  if (big) return launch_group<256, 256>(grp, flops, s);
+  return launch_group<128, 128>(grp, flops, s);
 }
 
-// Large tiles when they still give every CU a tile; small tiles otherwise.
+// Large tiles when they still give most CUs a tile; small tiles otherwise.
 static bool use_big_tiles(int M, int N, bool m_must_divide) {
   if (N % 256 != 0) return false;
   if (m_must_divide && M % 256 != 0) return false;
@@ -696,6 +714,7 @@ static hipError_t launch_nt_epi(const GemmArgs& g, hipStream_t s) {
 }
 
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
+  if (gemm_bf16_check(g) != nullptr) return hipErrorInvalidValue;
   if (g.kind == KFKB_GEMM_NT) {
     switch (g.epilogue) {
       case KFKB_EPI_NONE: return launch_nt_epi<KFKB_EPI_NONE>(g, s);
