@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--wgrad-stream", type=int, default=1, choices=[0, 1],
                     help="1 (the library's default): weight and bias gradients run on a stream of their own beside the "
                          "input-gradient chain; 0: everything on the compute stream")
+    ap.add_argument("--lanes", type=int, default=2, choices=[1, 2],
+                    help="compute lanes (the library's default is 2): ops in flight at once, within the plan's peak of live "
+                         "micro-batches")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -98,6 +101,7 @@ def main():
     t_setup = time.time() - t0
     overlap = kf.stage_side_streams_overlap()
     kf.stage_set_wgrad_stream(args.wgrad_stream)
+    kf.stage_set_compute_lanes(args.lanes)
 
     def set_delays(step_index, n_steps):
         """Delays of one iteration, the same for every k: drawn per (iteration, direction, micro-batch)."""
@@ -142,10 +146,11 @@ def main():
     best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
 
     # per-kernel timing of the same steps at the best k: HIP start/stop events on the stream of each launch.
-    # Kernels that share the chip stretch each other's durations, so this pass runs with the weight-gradient
-    # stream folded back into the compute stream: every duration below is that of a kernel running alone.
+    # Kernels that share the chip stretch each other's durations, so this pass runs on one lane with the W steps
+    # behind their chains: every duration below is that of a kernel running alone.
     kf.stage_sync()
     kf.stage_set_wgrad_stream(0)
+    kf.stage_set_compute_lanes(1)
     kf.stage_set_delays(None, None, None, None)
     delay_model_saved, delay_model = delay_model, "none"
     kf.kfkb_profile(True)
@@ -154,6 +159,7 @@ def main():
     kf.stage_sync()
     kf.kfkb_profile(False)
     kf.stage_set_wgrad_stream(args.wgrad_stream)
+    kf.stage_set_compute_lanes(args.lanes)
     delay_model = delay_model_saved
     stats = kf.kfkb_profile_report()
     tot_ms = sum(s["total_ms"] for s in stats) or 1.0
@@ -215,7 +221,7 @@ def main():
         "config": {"workload": args.workload, "layers": L, "hidden": H, "heads": heads, "seq_len": T, "micro_batch": b,
                    "num_microbatches": M, "global_batch": M * b, "k": best_k, "delay": delay_model,
                    "activation_limit_bytes": limit,
-                   "side_streams_overlap": bool(overlap), "wgrad_stream": bool(args.wgrad_stream)},
+                   "side_streams_overlap": bool(overlap), "wgrad_stream": bool(args.wgrad_stream), "compute_lanes": args.lanes},
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
         "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,
         "per_k": {str(k): v for k, v in per_k.items()},

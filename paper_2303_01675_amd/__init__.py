@@ -4,5 +4,7 @@ All arithmetic runs in the HIP kernels behind the C boundary declared in include
 this package only marshals arguments (PyTorch supplies device memory).  Importing it
 does not load the library; the first call does, and fails loudly if it was not built.
 """
+import os
+
 from .binding import *          # noqa: F401,F403
 from .binding import __all__    # noqa: F401

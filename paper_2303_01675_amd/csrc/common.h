@@ -112,6 +112,8 @@ hipError_t launch_ln_fwd(int dt, const void* x, const void* gamma, const void* b
 hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mean, const float* rstd,
                          const void* gamma, const void* dres, void* dx, float* dgamma, float* dbeta,
                          float* scratch, int rows, int H, hipStream_t s);
+// dgamma == nullptr: dx and the partial sums only; launch_ln_bwd_final adds them into dgamma / dbeta later
+hipError_t launch_ln_bwd_final(const float* scratch, int rows, int H, float* dgamma, float* dbeta, hipStream_t s);
 hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratch, int rows, int N, hipStream_t s);
 hipError_t launch_colsum_group(int dt, int n, const void* const* dy, float* const* out, const int* widths, float* scratch,
                                int rows, hipStream_t s);   // up to 4 column sums over the same rows

@@ -151,7 +151,7 @@ struct BlockParams {          // element offsets inside one block's parameter ru
 
 struct MbState {
   int x_slot = -1, dy_slot = -1, stash = -1, y_buf = -1, dx_buf = -1;
-  bool x_issued = false, dy_issued = false, fwd_done = false, bwd_done = false;
+  bool x_issued = false, dy_issued = false, fwd_begun = false, fwd_done = false, bwd_begun = false, bwd_done = false;
 };
 
 struct Pool {                 // device buffers handed round between transfers and compute
@@ -179,25 +179,40 @@ struct Stage {
   char* wt = nullptr;                        // bf16 only: weight matrices stored [out, in]
   std::vector<char*> stash; std::vector<int> stash_free;
   Pool xs, dys, ys, dxs;
-  // backward scratch: t_n0 (dc, d_o, da in turn); dx1, du, dqkv alternate between two buffers and the block input
-  // gradient rotates over three, so that the weight gradients of a block can still read them while the next
-  // block's chain runs
-  char* t_n0 = nullptr; char* t_dx1[2] = {nullptr, nullptr}; char* t_dxr[3] = {nullptr, nullptr, nullptr};
-  char* t_mf[2] = {nullptr, nullptr}; char* t_3n[2] = {nullptr, nullptr};
-  float* dsum = nullptr; float* red = nullptr; float* red_w = nullptr;
   size_t stash_block_bytes = 0, stash_bytes = 0;
-  // streams and events
-  hipStream_t sc = nullptr, ss = nullptr, sr = nullptr;
-  // weight-gradient stream: the weight and bias gradients of a block run here, beside the chain of input
-  // gradients on sc; gradient accumulation keeps its order because this stream is in order
-  hipStream_t sw = nullptr;
-  bool wgrad_overlap = true;
+  // Compute lanes.  Ops are admitted in schedule order; up to `lanes` of them are in flight, each on its lane's
+  // stream, and their blocks are enqueued in turn, so that independent micro-batches fill each other's idle
+  // phases (launch gaps, memory-bound epilogues and row kernels, partly filled last rounds of tiles).
+  // The weight and bias gradients of a block (its "W step") go to the OTHER lane's stream when
+  // wgrad_overlap is set, and run beside the op's own chain of input gradients.
+  // Per-lane backward scratch: t_n0 (dc, d_o, da in turn); dx1, du, dqkv and the LayerNorm partial sums alternate
+  // between two buffers and the block input gradient rotates over three, so that the W step of a block can still
+  // read them while the next block's chain runs (the chain waits for it two blocks later).
   static constexpr int kRing = 8;
-  hipEvent_t ev_chain[kRing] = {}, ev_wdone[kRing] = {};   // per block of a backward pass, reused round-robin
-  uint64_t wseq = 0;                                       // blocks of backward passes issued so far
-  hipEvent_t last_wdone = nullptr;
-  std::vector<hipEvent_t> ev_w;                            // per micro-batch: all its weight gradients are done
-  std::vector<hipEvent_t> stash_release;                   // per activation slot: last reader on sw (or null)
+  struct Lane {
+    hipStream_t s = nullptr;
+    char* t_n0 = nullptr; char* t_dx1[2] = {nullptr, nullptr}; char* t_dxr[3] = {nullptr, nullptr, nullptr};
+    char* t_mf[2] = {nullptr, nullptr}; char* t_3n[2] = {nullptr, nullptr};
+    float* dsum = nullptr; float* red_ln[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}}; float* red_w[2] = {nullptr, nullptr};
+    hipEvent_t ev_chain[kRing] = {}, ev_wdone[kRing] = {};   // per block of a backward pass, reused round-robin
+    bool w_elsewhere[kRing] = {};                            // that block's W step ran on the other lane's stream
+    uint64_t seq = 0;                                        // blocks of backward passes issued on this lane
+    hipEvent_t ev_tail = nullptr;
+  };
+  Lane lane[2];
+  int lanes = 2;
+  bool wgrad_overlap = true;
+  // W steps get a stream of their own when the process has hardware queues to spare (GPU_MAX_HW_QUEUES >= 5:
+  // two lanes, this one, send, receive); otherwise they borrow the other lane's stream while that lane is idle
+  hipStream_t sw = nullptr;
+  hipEvent_t ev_sw_tail = nullptr;
+  hipStream_t ss = nullptr, sr = nullptr;
+  std::vector<hipEvent_t> ev_g;                            // per block: last accumulation into its gradients
+  std::vector<char> ev_g_set;
+  hipEvent_t ev_zero = nullptr;
+  hipEvent_t last_done = nullptr;                          // end of the most recent backward op, W steps included
+  std::vector<hipEvent_t> ev_w;                            // per micro-batch: its last W step is done
+  std::vector<hipEvent_t> stash_release;                   // per activation slot: last reader (or null)
   std::vector<hipEvent_t> ev_x, ev_dy, ev_f0, ev_f1, ev_b0, ev_b1, ev_ys, ev_dxs;
   hipEvent_t ev_epoch = nullptr, ev_run_end = nullptr;
   bool epoch_valid = false, run_timed = false;
@@ -227,11 +242,27 @@ int peak_live_for(const Stage& s, int k, int M) {
   return std::min((warmup_for(s, k, M) + 1) * k, M);
 }
 
-// column-sum partials: 64 parts x 2 slots x widest matrix, the four bias gradients side by side (F + 5H),
-// or 512 parts x 2 x H of the fused LayerNorm backward: 128 (F + 5H) floats covers all three
-size_t red_floats(const Stage& s) { return (size_t)128 * (s.F + 5 * (size_t)s.H); }
+// scratch of the column reductions, in floats: bias gradients of a block side by side (64 parts x 2 slots x
+// (F + 5 H)); LayerNorm parameter gradients (at most 512 parts x 2 slots x H), kept for the deferred finishing pass
+size_t red_w_floats(const Stage& s) { return (size_t)128 * (s.F + 5 * (size_t)s.H); }
+size_t red_ln_floats(const Stage& s) { return (size_t)1024 * s.H; }
 
-struct Carve { size_t wt, stash, xs, dys, ys, dxs, tn, tmf, t3n, dsum, red, total; int n_stash, n_x, n_io; };
+struct LaneCarve { size_t tn, tmf, t3n, dsum, red_ln, red_w, total; };
+LaneCarve lane_carve(const Stage& s) {
+  LaneCarve c{};
+  const size_t act = align_up(s.n * s.esz);
+  size_t off = 0;
+  c.tn = off; off += 6 * act;
+  c.tmf = off; off += 2 * align_up((size_t)s.m * s.F * s.esz);
+  c.t3n = off; off += 2 * align_up(3 * s.n * s.esz);
+  c.dsum = off; off += align_up((size_t)s.b * s.heads * s.T * 4);
+  c.red_ln = off; off += 4 * align_up(red_ln_floats(s) * 4);
+  c.red_w = off; off += 2 * align_up(red_w_floats(s) * 4);
+  c.total = off;
+  return c;
+}
+
+struct Carve { size_t wt, stash, xs, dys, ys, dxs, lanes, total; int n_stash, n_x, n_io; };
 
 Carve carve_for(const Stage& s, int k_max) {
   Carve c{};
@@ -246,11 +277,7 @@ Carve carve_for(const Stage& s, int k_max) {
   c.dys = off; off += (size_t)c.n_io * act;
   c.ys = off; off += (size_t)c.n_io * act;
   c.dxs = off; off += (size_t)c.n_io * act;
-  c.tn = off; off += 6 * act;
-  c.tmf = off; off += 2 * align_up((size_t)s.m * s.F * s.esz);
-  c.t3n = off; off += 2 * align_up(3 * s.n * s.esz);
-  c.dsum = off; off += align_up((size_t)s.b * s.heads * s.T * 4);
-  c.red = off; off += 2 * align_up(red_floats(s) * 4);
+  c.lanes = off; off += 2 * lane_carve(s).total;
   c.total = off;
   return c;
 }
@@ -280,143 +307,162 @@ WtView wt_view(const Stage& s, int l) {
   return WtView{p, p + 3 * H * H * 2, p + 4 * H * H * 2, p + (4 * H * H + H * F) * 2};
 }
 
-int gemm(const Stage& s, int kind, int epi, int M, int N, int K, const void* A, const void* B, const void* bias,
+int gemm(const Stage& s, hipStream_t st, int kind, int epi, int M, int N, int K, const void* A, const void* B, const void* bias,
          const void* res, void* C, void* C2, float* Cacc) {
   GemmArgs a{kind, epi, M, N, K, A, B, bias, res, C, C2, Cacc};
   if (s.dt == DT_BF16) {
     const char* why = gemm_bf16_check(a);
     if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
-    HIPCHK(launch_gemm_bf16(a, s.sc));
+    HIPCHK(launch_gemm_bf16(a, st));
   } else {
-    HIPCHK(launch_gemm_f32(a, s.sc));
+    HIPCHK(launch_gemm_f32(a, st));
   }
   return 0;
 }
 
 // forward linear map y = x W + b (+ epilogue): fp32 reads W [in,out] as given, bf16 reads the [out,in] copy
-int linear_fwd(const Stage& s, int epi, int in, int out, const void* x, const void* W, const void* Wt, const void* bias,
+int linear_fwd(const Stage& s, hipStream_t st, int epi, int in, int out, const void* x, const void* W, const void* Wt, const void* bias,
                const void* res, void* y, void* y2) {
-  if (s.dt == DT_BF16) return gemm(s, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr);
-  return gemm(s, KFKB_GEMM_NN, epi, s.m, out, in, x, W, bias, res, y, y2, nullptr);
+  if (s.dt == DT_BF16) return gemm(s, st, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr);
+  return gemm(s, st, KFKB_GEMM_NN, epi, s.m, out, in, x, W, bias, res, y, y2, nullptr);
 }
 
 int refresh_weights() {
   if (g.dt != DT_BF16) return 0;
+  hipStream_t st = g.lane[0].s;
   for (int l = 0; l < g.L; l++) {
     WtView w = wt_view(g, l);
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_qkv), (void*)w.qkv, g.H, 3 * g.H, g.sc));
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_o), (void*)w.o, g.H, g.H, g.sc));
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_1), (void*)w.w1, g.H, g.F, g.sc));
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_2), (void*)w.w2, g.F, g.H, g.sc));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_qkv), (void*)w.qkv, g.H, 3 * g.H, st));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_o), (void*)w.o, g.H, g.H, st));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_1), (void*)w.w1, g.H, g.F, st));
+    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_2), (void*)w.w2, g.F, g.H, st));
   }
   return 0;
 }
 
-int attention_fwd(const Stage& s, const void* qkv, void* o, float* lse) {
-  if (s.dt == DT_BF16) HIPCHK(launch_attention_fwd_bf16((const bf16_t*)qkv, (bf16_t*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
-  else HIPCHK(launch_attention_fwd_f32((const float*)qkv, (float*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+int attention_fwd(const Stage& s, hipStream_t st, const void* qkv, void* o, float* lse) {
+  if (s.dt == DT_BF16) HIPCHK(launch_attention_fwd_bf16((const bf16_t*)qkv, (bf16_t*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
+  else HIPCHK(launch_attention_fwd_f32((const float*)qkv, (float*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   return 0;
 }
-int attention_bwd(const Stage& s, const void* qkv, const void* o, const void* d_o, const float* lse, void* dqkv) {
+int attention_bwd(const Stage& s, hipStream_t st, const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum, void* dqkv) {
   if (s.dt == DT_BF16)
-    HIPCHK(launch_attention_bwd_bf16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, s.dsum, (bf16_t*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+    HIPCHK(launch_attention_bwd_bf16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, dsum, (bf16_t*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   else
-    HIPCHK(launch_attention_bwd_f32((const float*)qkv, (const float*)o, (const float*)d_o, lse, s.dsum, (float*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, s.sc));
+    HIPCHK(launch_attention_bwd_f32((const float*)qkv, (const float*)o, (const float*)d_o, lse, dsum, (float*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   return 0;
 }
 
 #define TRY(expr) do { int rc_ = (expr); if (rc_ != 0) return rc_; } while (0)
 
-// ---- the stage computation: forward and backward of all blocks for one micro-batch -----------
-int compute_forward(int slot, const char* x_in, char* y_out) {
+// ---- the stage computation, one block at a time ------------------------------------------------
+// An op in flight: forward (blocks 0 .. L-1) or backward (blocks L-1 .. 0) of one micro-batch on one lane.
+struct ActiveOp {
+  int op = 0, mb = 0, lane = 0, next = 0, left = 0;
+  bool other_busy = false;        // the other lane has an op in flight (set by whoever enqueues the blocks)
+  hipStream_t w_stream = nullptr; // where W steps of this op went, if not to the op's own stream
+  int out_buf = -1;               // Y buffer (forward) or dX buffer (backward)
+  const char* cur = nullptr;      // forward: input of the next block; backward: output gradient of the next block
+};
+
+int forward_block(ActiveOp& a) {
   const Stage& s = g;
-  const char* x = x_in;
-  for (int l = 0; l < s.L; l++) {
-    StashView v = view(s, slot, l);
-    WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{nullptr, nullptr, nullptr, nullptr};
-    char* y = (l == s.L - 1) ? y_out : v.y;
-    HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, s.sc));
-    TRY(linear_fwd(s, KFKB_EPI_BIAS, s.H, 3 * s.H, v.a, wptr(s, l, s.po.w_qkv), w.qkv, wptr(s, l, s.po.b_qkv), nullptr, v.qkv, nullptr));
-    TRY(attention_fwd(s, v.qkv, v.o, v.lse));
-    TRY(linear_fwd(s, KFKB_EPI_BIAS_RES, s.H, s.H, v.o, wptr(s, l, s.po.w_o), w.o, wptr(s, l, s.po.b_o), x, v.x1, nullptr));
-    HIPCHK(launch_ln_fwd(s.dt, v.x1, wptr(s, l, s.po.ln2_g), wptr(s, l, s.po.ln2_b), v.c, v.mean2, v.rstd2, s.m, s.H, s.cfg.ln_eps, s.sc));
-    TRY(linear_fwd(s, KFKB_EPI_BIAS_GELU, s.H, s.F, v.c, wptr(s, l, s.po.w_1), w.w1, wptr(s, l, s.po.b_1), nullptr, v.u, v.gact));
-    TRY(linear_fwd(s, KFKB_EPI_BIAS_RES, s.F, s.H, v.gact, wptr(s, l, s.po.w_2), w.w2, wptr(s, l, s.po.b_2), v.x1, y, nullptr));
-    x = y;
-  }
+  const MbState& st = s.mb[a.mb];
+  hipStream_t q = s.lane[a.lane].s;
+  const int l = a.next;
+  StashView v = view(s, st.stash, l);
+  WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{nullptr, nullptr, nullptr, nullptr};
+  const char* x = a.cur;
+  char* y = (l == s.L - 1) ? s.ys.buf[a.out_buf] : v.y;
+  HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, q));
+  TRY(linear_fwd(s, q, KFKB_EPI_BIAS, s.H, 3 * s.H, v.a, wptr(s, l, s.po.w_qkv), w.qkv, wptr(s, l, s.po.b_qkv), nullptr, v.qkv, nullptr));
+  TRY(attention_fwd(s, q, v.qkv, v.o, v.lse));
+  TRY(linear_fwd(s, q, KFKB_EPI_BIAS_RES, s.H, s.H, v.o, wptr(s, l, s.po.w_o), w.o, wptr(s, l, s.po.b_o), x, v.x1, nullptr));
+  HIPCHK(launch_ln_fwd(s.dt, v.x1, wptr(s, l, s.po.ln2_g), wptr(s, l, s.po.ln2_b), v.c, v.mean2, v.rstd2, s.m, s.H, s.cfg.ln_eps, q));
+  TRY(linear_fwd(s, q, KFKB_EPI_BIAS_GELU, s.H, s.F, v.c, wptr(s, l, s.po.w_1), w.w1, wptr(s, l, s.po.b_1), nullptr, v.u, v.gact));
+  TRY(linear_fwd(s, q, KFKB_EPI_BIAS_RES, s.F, s.H, v.gact, wptr(s, l, s.po.w_2), w.w2, wptr(s, l, s.po.b_2), v.x1, y, nullptr));
+  a.cur = y;
+  a.next++; a.left--;
   return 0;
 }
 
-int compute_backward(int slot, const char* x_in, const char* dy_in, char* dx_out) {
+int backward_block(ActiveOp& a) {
   Stage& s = g;
-  const char* dy = dy_in;
-  char* dc = s.t_n0;
-  char* d_o = s.t_n0;            // dc is dead once dx1 exists
-  char* da = s.t_n0;             // d_o is dead once dqkv exists
-  // the four weight-gradient products of a block are issued together once their operands exist: one launch
-  // fills the chip where each alone would not.  With the weight-gradient stream they, and the four bias
-  // gradients, run beside the next block's chain; the operands they read (du, dx1, dqkv, this block's dy)
-  // sit in buffers that the chain reuses only two blocks later, after waiting for them.
+  const MbState& st = s.mb[a.mb];
+  Stage::Lane& ln = s.lane[a.lane];
+  hipStream_t q = ln.s;
+  const int l = a.next;
+  const uint64_t seq = ln.seq++;
+  const int par = (int)(seq & 1), ring = (int)(seq % Stage::kRing);
+  char* du = ln.t_mf[par];
+  char* dqkv = ln.t_3n[par];
+  char* dx1 = ln.t_dx1[par];
+  char* dc = ln.t_n0;
+  char* d_o = ln.t_n0;           // dc is dead once dx1 exists
+  char* da = ln.t_n0;            // d_o is dead once dqkv exists
+  const char* dy = a.cur;
+  StashView v = view(s, st.stash, l);
+  const char* x = (l == 0) ? s.xs.buf[st.x_slot] : view(s, st.stash, l - 1).y;
+  char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : ln.t_dxr[seq % 3];
+  // where the W step of this block goes: the other lane's stream, beside this chain, when that lane has nothing
+  // of its own to do; behind the chain otherwise (the other lane's op then fills the chip beside it)
+  hipStream_t qw = !s.wgrad_overlap ? q : s.sw != nullptr ? s.sw : !a.other_busy ? s.lane[1 - a.lane].s : q;
+  // the buffers about to be overwritten were last read by the W step of two blocks ago
+  if (seq >= 2 && ln.w_elsewhere[(seq - 2) % Stage::kRing]) HIPCHK(hipStreamWaitEvent(q, ln.ev_wdone[(seq - 2) % Stage::kRing], 0));
+  // the four weight-gradient products of a block are issued together: one launch fills the chip where each
+  // alone would not
   GemmArgs wg[4];
-  auto wgrad = [&](int i, int in, int out, const void* x, const void* dyv, float* acc) {
-    wg[i] = GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, in, out, s.m, x, dyv, nullptr, nullptr, nullptr, nullptr, acc};
+  auto wgrad = [&](int i, int in, int out, const void* xin, const void* dyv, float* acc) {
+    wg[i] = GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, in, out, s.m, xin, dyv, nullptr, nullptr, nullptr, nullptr, acc};
   };
-  for (int l = s.L - 1; l >= 0; l--) {
-    const uint64_t seq = s.wseq++;
-    const int par = (int)(seq & 1), ring = (int)(seq % Stage::kRing);
-    char* du = s.t_mf[par];
-    char* dqkv = s.t_3n[par];
-    char* dx1 = s.t_dx1[par];
-    StashView v = view(s, slot, l);
-    const char* x = (l == 0) ? x_in : view(s, slot, l - 1).y;
-    char* dx = (l == 0) ? dx_out : s.t_dxr[seq % 3];
-    if (s.wgrad_overlap && seq >= 2) HIPCHK(hipStreamWaitEvent(s.sc, s.ev_wdone[(seq - 2) % Stage::kRing], 0));
-    // y = x1 + g W2 + b2
-    wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
-    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
-    // u = c W1 + b1
-    wgrad(1, s.H, s.F, v.c, du, gptr(s, l, s.po.w_1));
-    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr));
-    // c = LN2(x1), plus the residual path
-    HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), s.red, s.m, s.H, s.sc));
-    // x1 = x + o Wo + bo
-    wgrad(3, s.H, s.H, v.o, dx1, gptr(s, l, s.po.w_o));
-    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr));
-    // o = attention(qkv)
-    TRY(attention_bwd(s, v.qkv, v.o, d_o, v.lse, dqkv));
-    // qkv = a Wqkv + bqkv
-    wgrad(0, s.H, 3 * s.H, v.a, dqkv, gptr(s, l, s.po.w_qkv));
-    TRY(gemm(s, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
-    // a = LN1(x), plus the residual path
-    HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), s.red, s.m, s.H, s.sc));
-    // bias and weight gradients of this block
-    hipStream_t sw = s.sc;
-    if (s.wgrad_overlap) {
-      HIPCHK(hipEventRecord(s.ev_chain[ring], s.sc));
-      HIPCHK(hipStreamWaitEvent(s.sw, s.ev_chain[ring], 0));
-      sw = s.sw;
-    }
-    {
-      const void* srcs[4] = {dqkv, du, dy, dx1};
-      float* outs[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
-      const int widths[4] = {3 * s.H, s.F, s.H, s.H};
-      HIPCHK(launch_colsum_group(s.dt, 4, srcs, outs, widths, s.red_w, s.m, sw));
-    }
-    if (s.dt == DT_BF16) {
-      for (int i = 0; i < 4; i++) {
-        const char* why = gemm_bf16_check(wg[i]);
-        if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
-      }
-      HIPCHK(launch_gemm_bf16_tn_group(wg, 4, sw));
-    } else {
-      for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], sw));
-    }
-    if (s.wgrad_overlap) {
-      HIPCHK(hipEventRecord(s.ev_wdone[ring], s.sw));
-      s.last_wdone = s.ev_wdone[ring];
-    }
-    dy = dx;
+  // y = x1 + g W2 + b2
+  wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
+  // u = c W1 + b1
+  wgrad(1, s.H, s.F, v.c, du, gptr(s, l, s.po.w_1));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr));
+  // c = LN2(x1), plus the residual path; the parameter gradients are finished in the W step
+  HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, nullptr, nullptr, ln.red_ln[par][1], s.m, s.H, q));
+  // x1 = x + o Wo + bo
+  wgrad(3, s.H, s.H, v.o, dx1, gptr(s, l, s.po.w_o));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr));
+  // o = attention(qkv)
+  TRY(attention_bwd(s, q, v.qkv, v.o, d_o, v.lse, ln.dsum, dqkv));
+  // qkv = a Wqkv + bqkv
+  wgrad(0, s.H, 3 * s.H, v.a, dqkv, gptr(s, l, s.po.w_qkv));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
+  // a = LN1(x), plus the residual path
+  HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, nullptr, nullptr, ln.red_ln[par][0], s.m, s.H, q));
+
+  // ---- W step: every accumulation into the gradients of block l, in micro-batch order -----------------
+  if (qw != q) {
+    HIPCHK(hipEventRecord(ln.ev_chain[ring], q));
+    HIPCHK(hipStreamWaitEvent(qw, ln.ev_chain[ring], 0));
   }
+  if (s.ev_g_set[l]) HIPCHK(hipStreamWaitEvent(qw, s.ev_g[l], 0));     // the previous micro-batch's W step of this block
+  HIPCHK(launch_ln_bwd_final(ln.red_ln[par][1], s.m, s.H, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), qw));
+  HIPCHK(launch_ln_bwd_final(ln.red_ln[par][0], s.m, s.H, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), qw));
+  {
+    const void* srcs[4] = {dqkv, du, dy, dx1};
+    float* outs[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
+    const int widths[4] = {3 * s.H, s.F, s.H, s.H};
+    HIPCHK(launch_colsum_group(s.dt, 4, srcs, outs, widths, ln.red_w[par], s.m, qw));
+  }
+  if (s.dt == DT_BF16) {
+    for (int i = 0; i < 4; i++) {
+      const char* why = gemm_bf16_check(wg[i]);
+      if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
+    }
+    HIPCHK(launch_gemm_bf16_tn_group(wg, 4, qw));
+  } else {
+    for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], qw));
+  }
+  HIPCHK(hipEventRecord(s.ev_g[l], qw));
+  s.ev_g_set[l] = 1;
+  ln.w_elsewhere[ring] = qw != q;
+  if (qw != q) { HIPCHK(hipEventRecord(ln.ev_wdone[ring], qw)); a.w_stream = qw; }
+  a.cur = dx;
+  a.next--; a.left--;
   return 0;
 }
 
@@ -450,82 +496,140 @@ int issue_recv(int op, int mbi) {
 }
 
 int begin_log_epoch() {
-  HIPCHK(hipEventRecord(g.ev_epoch, g.sc));
+  HIPCHK(hipEventRecord(g.ev_epoch, g.lane[0].s));
+  HIPCHK(hipStreamWaitEvent(g.lane[1].s, g.ev_epoch, 0));
   g.epoch_valid = true;
   g.log.clear();
   return 0;
 }
 
-int do_forward(int mbi) {
+// Admission of F(mb) on a lane: takes the micro-batch's activation slot and output buffer, orders the lane's
+// stream after the arrival of X_mb and after the last readers of what it is about to overwrite.
+// Returns 0 admitted, 1 no slot free yet (only when wait_ok), < 0 error.
+int begin_forward(int mbi, int lane, bool wait_ok, ActiveOp& a) {
   MbState& st = g.mb[mbi];
   if (st.fwd_done && !st.bwd_done) return fail(KFKB_E_STATE, "forward of micro-batch %d while it is live", mbi);
-  if (st.fwd_done) return fail(KFKB_E_STATE, "forward of micro-batch %d issued twice in this iteration", mbi);
+  if (st.fwd_done || st.fwd_begun) return fail(KFKB_E_STATE, "forward of micro-batch %d issued twice in this iteration", mbi);
+  if (g.stash_free.empty() || g.ys.free_list.empty()) {
+    if (wait_ok) return 1;
+    if (g.stash_free.empty()) return fail(KFKB_E_STATE, "no free activation slot for micro-batch %d (peak live = %d)", mbi, g.n_stash);
+    return fail(KFKB_E_STATE, "no free output buffer for micro-batch %d", mbi);
+  }
   if (!st.x_issued) {
     int rc = issue_recv(KFKB_OP_F, mbi);
     if (rc < 0) return rc;
-    if (rc == 1) return fail(KFKB_E_STATE, "no free input slot for micro-batch %d", mbi);
+    if (rc == 1) return wait_ok ? 1 : fail(KFKB_E_STATE, "no free input slot for micro-batch %d", mbi);
   }
-  if (g.stash_free.empty()) return fail(KFKB_E_STATE, "no free activation slot for micro-batch %d (peak live = %d)", mbi, g.n_stash);
   const int ybuf = g.ys.take();
-  if (ybuf < 0) return fail(KFKB_E_STATE, "no free output buffer for micro-batch %d", mbi);
   st.stash = g.stash_free.back(); g.stash_free.pop_back();
   st.y_buf = ybuf;
+  st.fwd_begun = true;
   if (!g.epoch_valid) TRY(begin_log_epoch());
-  HIPCHK(hipStreamWaitEvent(g.sc, g.ev_x[mbi], 0));
-  if (g.ys.release[ybuf]) HIPCHK(hipStreamWaitEvent(g.sc, g.ys.release[ybuf], 0));
-  if (g.stash_release[st.stash]) {                   // weight gradients of the slot's last owner still read it
-    HIPCHK(hipStreamWaitEvent(g.sc, g.stash_release[st.stash], 0));
+  hipStream_t q = g.lane[lane].s;
+  HIPCHK(hipStreamWaitEvent(q, g.ev_x[mbi], 0));
+  if (g.ys.release[ybuf]) HIPCHK(hipStreamWaitEvent(q, g.ys.release[ybuf], 0));
+  if (g.stash_release[st.stash]) {                   // the slot's last owner may still be read on another stream
+    HIPCHK(hipStreamWaitEvent(q, g.stash_release[st.stash], 0));
     g.stash_release[st.stash] = nullptr;
   }
-  HIPCHK(hipEventRecord(g.ev_f0[mbi], g.sc));
-  TRY(compute_forward(st.stash, g.xs.buf[st.x_slot], g.ys.buf[ybuf]));
-  HIPCHK(hipEventRecord(g.ev_f1[mbi], g.sc));
+  HIPCHK(hipEventRecord(g.ev_f0[mbi], q));
   g.log.push_back({KFKB_OP_F, mbi});
+  a = ActiveOp{};
+  a.op = KFKB_OP_F; a.mb = mbi; a.lane = lane; a.next = 0; a.left = g.L; a.out_buf = ybuf; a.cur = g.xs.buf[st.x_slot];
+  return 0;
+}
+
+int end_forward(ActiveOp& a) {
+  const int mbi = a.mb;
+  MbState& st = g.mb[mbi];
+  hipStream_t q = g.lane[a.lane].s;
+  HIPCHK(hipEventRecord(g.ev_f1[mbi], q));
   // send Y_mb as soon as the forward has delivered it
   const size_t bytes = g.n * g.esz;
   HIPCHK(hipStreamWaitEvent(g.ss, g.ev_f1[mbi], 0));
   HIPCHK(launch_delay(g.dl_y[mbi], g.ss));
-  HIPCHK(hipMemcpyAsync(g.h_out + (size_t)mbi * bytes, g.ys.buf[ybuf], bytes, hipMemcpyDeviceToHost, g.ss));
+  HIPCHK(hipMemcpyAsync(g.h_out + (size_t)mbi * bytes, g.ys.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
   HIPCHK(hipEventRecord(g.ev_ys[mbi], g.ss));
-  g.ys.give(ybuf, g.ev_ys[mbi]);
+  g.ys.give(a.out_buf, g.ev_ys[mbi]);
   st.fwd_done = true;
   return 0;
 }
 
-int do_backward(int mbi) {
+int begin_backward(int mbi, int lane, bool wait_ok, ActiveOp& a) {
   MbState& st = g.mb[mbi];
-  if (!st.fwd_done || st.bwd_done) return fail(KFKB_E_STATE, "backward of micro-batch %d without a live forward", mbi);
+  if (st.bwd_done || st.bwd_begun) return fail(KFKB_E_STATE, "backward of micro-batch %d without a live forward", mbi);
+  if (!st.fwd_done) {
+    if (wait_ok && st.fwd_begun) return 1;            // its forward is still being enqueued
+    return fail(KFKB_E_STATE, "backward of micro-batch %d without a live forward", mbi);
+  }
+  if (g.dxs.free_list.empty()) return wait_ok ? 1 : fail(KFKB_E_STATE, "no free input-gradient buffer for micro-batch %d", mbi);
   if (!st.dy_issued) {
     int rc = issue_recv(KFKB_OP_B, mbi);
     if (rc < 0) return rc;
-    if (rc == 1) return fail(KFKB_E_STATE, "no free gradient slot for micro-batch %d", mbi);
+    if (rc == 1) return wait_ok ? 1 : fail(KFKB_E_STATE, "no free gradient slot for micro-batch %d", mbi);
   }
   const int dxbuf = g.dxs.take();
-  if (dxbuf < 0) return fail(KFKB_E_STATE, "no free input-gradient buffer for micro-batch %d", mbi);
-  HIPCHK(hipStreamWaitEvent(g.sc, g.ev_dy[mbi], 0));
-  if (g.dxs.release[dxbuf]) HIPCHK(hipStreamWaitEvent(g.sc, g.dxs.release[dxbuf], 0));
-  HIPCHK(hipEventRecord(g.ev_b0[mbi], g.sc));
-  TRY(compute_backward(st.stash, g.xs.buf[st.x_slot], g.dys.buf[st.dy_slot], g.dxs.buf[dxbuf]));
-  HIPCHK(hipEventRecord(g.ev_b1[mbi], g.sc));
-  hipEvent_t ev_done = g.ev_b1[mbi];                 // after it nothing reads the micro-batch's activations or dY
-  if (g.wgrad_overlap) {
-    HIPCHK(hipEventRecord(g.ev_w[mbi], g.sw));
-    ev_done = g.ev_w[mbi];
-    g.stash_release[st.stash] = ev_done;
-  }
+  st.bwd_begun = true;
+  hipStream_t q = g.lane[lane].s;
+  HIPCHK(hipStreamWaitEvent(q, g.ev_dy[mbi], 0));
+  HIPCHK(hipStreamWaitEvent(q, g.ev_f1[mbi], 0));    // the forward may have run on the other lane
+  if (g.dxs.release[dxbuf]) HIPCHK(hipStreamWaitEvent(q, g.dxs.release[dxbuf], 0));
+  HIPCHK(hipEventRecord(g.ev_b0[mbi], q));
   g.log.push_back({KFKB_OP_B, mbi});
+  a = ActiveOp{};
+  a.op = KFKB_OP_B; a.mb = mbi; a.lane = lane; a.next = g.L - 1; a.left = g.L; a.out_buf = dxbuf; a.cur = g.dys.buf[st.dy_slot];
+  return 0;
+}
+
+int end_backward(ActiveOp& a) {
+  const int mbi = a.mb;
+  MbState& st = g.mb[mbi];
+  hipStream_t q = g.lane[a.lane].s;
+  HIPCHK(hipEventRecord(g.ev_b1[mbi], q));           // dX_mb is complete
+  // after ev_done nothing reads the micro-batch's activations or dY any more
+  hipEvent_t ev_done = g.ev_b1[mbi];
+  if (a.w_stream != nullptr) {
+    hipStream_t qw = a.w_stream;
+    HIPCHK(hipStreamWaitEvent(qw, g.ev_b1[mbi], 0));
+    HIPCHK(hipEventRecord(g.ev_w[mbi], qw));
+    ev_done = g.ev_w[mbi];
+  }
   const size_t bytes = g.n * g.esz;
   HIPCHK(hipStreamWaitEvent(g.ss, g.ev_b1[mbi], 0));
   HIPCHK(launch_delay(g.dl_dx[mbi], g.ss));
-  HIPCHK(hipMemcpyAsync(g.h_ingrad + (size_t)mbi * bytes, g.dxs.buf[dxbuf], bytes, hipMemcpyDeviceToHost, g.ss));
+  HIPCHK(hipMemcpyAsync(g.h_ingrad + (size_t)mbi * bytes, g.dxs.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
   HIPCHK(hipEventRecord(g.ev_dxs[mbi], g.ss));
-  g.dxs.give(dxbuf, g.ev_dxs[mbi]);
+  g.dxs.give(a.out_buf, g.ev_dxs[mbi]);
   // early release: the micro-batch's activations and its input slots return to their pools
+  g.stash_release[st.stash] = ev_done;
   g.stash_free.push_back(st.stash);
-  g.xs.give(st.x_slot, g.ev_b1[mbi]);
+  g.xs.give(st.x_slot, ev_done);
   g.dys.give(st.dy_slot, ev_done);
   st.stash = st.x_slot = st.dy_slot = -1;
   st.bwd_done = true;
+  g.last_done = ev_done;
+  return 0;
+}
+
+// one op from start to end on lane 0 (the single-op entry points)
+int run_single(int op, int mbi) {
+  ActiveOp a;
+  TRY(op == KFKB_OP_F ? begin_forward(mbi, 0, false, a) : begin_backward(mbi, 0, false, a));
+  while (a.left > 0) TRY(op == KFKB_OP_F ? forward_block(a) : backward_block(a));
+  return op == KFKB_OP_F ? end_forward(a) : end_backward(a);
+}
+
+// orders stream q after everything enqueued so far on the other compute streams
+int join_compute_streams(hipStream_t q) {
+  for (int i = 0; i < 2; i++) {
+    if (g.lane[i].s == q) continue;
+    HIPCHK(hipEventRecord(g.lane[i].ev_tail, g.lane[i].s));
+    HIPCHK(hipStreamWaitEvent(q, g.lane[i].ev_tail, 0));
+  }
+  if (g.sw != nullptr) {
+    HIPCHK(hipEventRecord(g.ev_sw_tail, g.sw));
+    HIPCHK(hipStreamWaitEvent(q, g.ev_sw_tail, 0));
+  }
   return 0;
 }
 
@@ -540,6 +644,55 @@ void reset_iteration_state() {
   g.xs.reset(); g.dys.reset(); g.ys.reset(); g.dxs.reset();
   g.stash_free.clear();
   for (int i = g.n_stash - 1; i >= 0; i--) g.stash_free.push_back(i);
+}
+
+// The four streams of the stage, chosen once per process.  HIP multiplexes streams onto a few hardware queues
+// (four per process by default) and two streams on one queue run one after the other, so eight streams are
+// created and four that demonstrably run side by side are kept: pairs of 200 us delay kernels are timed.
+// Order of the result: lane 0, send, receive, lane 1 (if fewer than four independent streams exist, the later
+// entries share).  The streams live until the process ends.
+hipStream_t g_stream_pick[4] = {nullptr, nullptr, nullptr, nullptr};
+bool g_streams_picked = false;
+
+int pick_streams() {
+  if (g_streams_picked) return 0;
+  constexpr int P = 8;
+  hipStream_t pool[P];
+  for (int i = 0; i < P; i++) HIPCHK(hipStreamCreateWithFlags(&pool[i], hipStreamNonBlocking));
+  for (int rep = 0; rep < 2; rep++) {
+    for (int i = 0; i < P; i++) HIPCHK(launch_delay(2000, pool[i]));
+    for (int i = 0; i < P; i++) HIPCHK(hipStreamSynchronize(pool[i]));
+  }
+  bool together[P][P] = {};
+  for (int i = 0; i < P; i++)
+    for (int j = i + 1; j < P; j++) {
+      const auto t0 = std::chrono::steady_clock::now();
+      HIPCHK(launch_delay(200000, pool[i]));
+      HIPCHK(launch_delay(200000, pool[j]));
+      HIPCHK(hipStreamSynchronize(pool[i]));
+      HIPCHK(hipStreamSynchronize(pool[j]));
+      const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+      together[i][j] = together[j][i] = us < 330.0;
+    }
+  int chosen[4], n = 0;
+  for (int i = 0; i < P && n < 4; i++) {
+    bool ok = true;
+    for (int c = 0; c < n; c++) ok = ok && together[chosen[c]][i];
+    if (ok) chosen[n++] = i;
+  }
+  for (int i = 0; n < 4 && i < P; i++) {              // not enough independent ones: take what is left
+    bool used = false;
+    for (int c = 0; c < n; c++) used = used || chosen[c] == i;
+    if (!used) chosen[n++] = i;
+  }
+  for (int c = 0; c < 4; c++) g_stream_pick[c] = pool[chosen[c]];
+  for (int i = 0; i < P; i++) {
+    bool used = false;
+    for (int c = 0; c < 4; c++) used = used || chosen[c] == i;
+    if (!used) hipStreamDestroy(pool[i]);
+  }
+  g_streams_picked = true;
+  return 0;
 }
 
 int make_events(std::vector<hipEvent_t>& v, int n) {
@@ -626,13 +779,20 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   s.mb.assign(s.Mmax, MbState{});
   s.dl_x.assign(s.Mmax, 0); s.dl_dy.assign(s.Mmax, 0); s.dl_y.assign(s.Mmax, 0); s.dl_dx.assign(s.Mmax, 0);
   g = s;
-  HIPCHK(hipStreamCreateWithFlags(&g.sc, hipStreamNonBlocking));
-  HIPCHK(hipStreamCreateWithFlags(&g.ss, hipStreamNonBlocking));
-  HIPCHK(hipStreamCreateWithFlags(&g.sr, hipStreamNonBlocking));
-  HIPCHK(hipStreamCreateWithFlags(&g.sw, hipStreamNonBlocking));
-  for (int i = 0; i < Stage::kRing; i++) { HIPCHK(hipEventCreate(&g.ev_chain[i])); HIPCHK(hipEventCreate(&g.ev_wdone[i])); }
+  TRY(pick_streams());
+  g.lane[0].s = g_stream_pick[0]; g.ss = g_stream_pick[1]; g.sr = g_stream_pick[2]; g.lane[1].s = g_stream_pick[3];
+  for (auto& ln : g.lane) {
+    for (int i = 0; i < Stage::kRing; i++) { HIPCHK(hipEventCreate(&ln.ev_chain[i])); HIPCHK(hipEventCreate(&ln.ev_wdone[i])); }
+    HIPCHK(hipEventCreate(&ln.ev_tail));
+  }
   TRY(make_events(g.ev_w, g.Mmax));
+  TRY(make_events(g.ev_g, g.L));
+  g.ev_g_set.assign(g.L, 0);
+  HIPCHK(hipEventCreate(&g.ev_zero));
   { const char* e = getenv("KFKB_WGRAD_STREAM"); g.wgrad_overlap = !(e && e[0] == '0'); }
+  { const char* e = getenv("KFKB_LANES"); g.lanes = (e && e[0] == '1') ? 1 : 2; }
+  { const char* e = getenv("GPU_MAX_HW_QUEUES"); if (e && atoi(e) >= 5) HIPCHK(hipStreamCreateWithFlags(&g.sw, hipStreamNonBlocking)); }
+  HIPCHK(hipEventCreate(&g.ev_sw_tail));
   TRY(make_events(g.ev_x, g.Mmax)); TRY(make_events(g.ev_dy, g.Mmax));
   TRY(make_events(g.ev_f0, g.Mmax)); TRY(make_events(g.ev_f1, g.Mmax));
   TRY(make_events(g.ev_b0, g.Mmax)); TRY(make_events(g.ev_b1, g.Mmax));
@@ -682,22 +842,27 @@ int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum, const
     for (int i = 0; i < cnt; i++) p.buf[i] = g.ws + off + (size_t)i * act;
   };
   fill_pool(g.xs, c.xs, c.n_x); fill_pool(g.dys, c.dys, c.n_io); fill_pool(g.ys, c.ys, c.n_io); fill_pool(g.dxs, c.dxs, c.n_io);
-  g.t_n0 = g.ws + c.tn;
-  for (int i = 0; i < 2; i++) g.t_dx1[i] = g.ws + c.tn + (size_t)(1 + i) * act;
-  for (int i = 0; i < 3; i++) g.t_dxr[i] = g.ws + c.tn + (size_t)(3 + i) * act;
+  const LaneCarve lc = lane_carve(g);
   for (int i = 0; i < 2; i++) {
-    g.t_mf[i] = g.ws + c.tmf + (size_t)i * align_up((size_t)g.m * g.F * g.esz);
-    g.t_3n[i] = g.ws + c.t3n + (size_t)i * align_up(3 * g.n * g.esz);
+    Stage::Lane& ln = g.lane[i];
+    char* base = g.ws + c.lanes + (size_t)i * lc.total;
+    ln.t_n0 = base + lc.tn;
+    for (int j = 0; j < 2; j++) ln.t_dx1[j] = base + lc.tn + (size_t)(1 + j) * act;
+    for (int j = 0; j < 3; j++) ln.t_dxr[j] = base + lc.tn + (size_t)(3 + j) * act;
+    for (int j = 0; j < 2; j++) {
+      ln.t_mf[j] = base + lc.tmf + (size_t)j * align_up((size_t)g.m * g.F * g.esz);
+      ln.t_3n[j] = base + lc.t3n + (size_t)j * align_up(3 * g.n * g.esz);
+    }
+    ln.dsum = reinterpret_cast<float*>(base + lc.dsum);
+    for (int j = 0; j < 4; j++) ln.red_ln[j >> 1][j & 1] = reinterpret_cast<float*>(base + lc.red_ln + (size_t)j * align_up(red_ln_floats(g) * 4));
+    for (int j = 0; j < 2; j++) ln.red_w[j] = reinterpret_cast<float*>(base + lc.red_w + (size_t)j * align_up(red_w_floats(g) * 4));
   }
-  g.dsum = reinterpret_cast<float*>(g.ws + c.dsum);
-  g.red = reinterpret_cast<float*>(g.ws + c.red);
-  g.red_w = reinterpret_cast<float*>(g.ws + c.red + align_up(red_floats(g) * 4));
   g.stash_release.assign(c.n_stash, nullptr);
   reset_iteration_state();
   g.epoch_valid = false; g.run_timed = false; g.log.clear();
   g.bound = true;
   TRY(refresh_weights());
-  HIPCHK(hipStreamSynchronize(g.sc));
+  HIPCHK(hipStreamSynchronize(g.lane[0].s));
   return 0;
 }
 
@@ -721,14 +886,14 @@ int stage_forward(int mb) {
   if (mb < 0 || mb >= g.Mmax) return fail(KFKB_E_ARG, "stage_forward: micro-batch %d outside [0, %d)", mb, g.Mmax);
   if (g.mb[mb].fwd_done && g.mb[mb].bwd_done) g.mb[mb] = MbState{};     // a finished micro-batch may run again
   g.run_timed = false;
-  return do_forward(mb);
+  return run_single(KFKB_OP_F, mb);
 }
 
 int stage_backward(int mb) {
   if (!g.bound) return fail(KFKB_E_STATE, "stage_backward before stage_bind");
   if (mb < 0 || mb >= g.Mmax) return fail(KFKB_E_ARG, "stage_backward: micro-batch %d outside [0, %d)", mb, g.Mmax);
   g.run_timed = false;
-  return do_backward(mb);
+  return run_single(KFKB_OP_B, mb);
 }
 
 int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
@@ -762,21 +927,46 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
   TRY(begin_log_epoch());
   HIPCHK(hipStreamWaitEvent(g.ss, g.ev_epoch, 0));
   HIPCHK(hipStreamWaitEvent(g.sr, g.ev_epoch, 0));
-  size_t rp = 0;
-  for (const auto& op : order) {
+  // Ops are admitted in schedule order, as many as there are lanes at a time and only while an activation
+  // slot is free (the plan's peak of live micro-batches is never exceeded: k = 1 on the last stage runs one op
+  // at a time); the blocks of the ops in flight are enqueued in turn.
+  size_t rp = 0, next = 0;
+  std::vector<ActiveOp> act;
+  while (next < order.size() || !act.empty()) {
     while (rp < plan.size()) {                        // receives run ahead as far as slots and the echo allow
       const int rc = issue_recv(plan[rp].op, plan[rp].mb);
       if (rc < 0) return rc;
       if (rc == 1) break;
       rp++;
     }
-    if (op.op == KFKB_OP_F) TRY(do_forward(op.mb)); else TRY(do_backward(op.mb));
+    while (next < order.size() && (int)act.size() < g.lanes) {
+      int lane = 0;
+      for (const auto& a : act) if (a.lane == lane) lane = 1 - lane;
+      ActiveOp a;
+      const bool wait_ok = !act.empty();
+      const int rc = order[next].op == KFKB_OP_F ? begin_forward(order[next].mb, lane, wait_ok, a) : begin_backward(order[next].mb, lane, wait_ok, a);
+      if (rc < 0) return rc;
+      if (rc == 1) break;                             // needs something an op in flight still holds
+      act.push_back(a);
+      next++;
+    }
+    for (size_t i = 0; i < act.size();) {
+      ActiveOp& a = act[i];
+      a.other_busy = act.size() > 1;
+      TRY(a.op == KFKB_OP_F ? forward_block(a) : backward_block(a));
+      if (a.left == 0) {
+        TRY(a.op == KFKB_OP_F ? end_forward(a) : end_backward(a));
+        act.erase(act.begin() + i);
+      } else {
+        i++;
+      }
+    }
   }
-  // the run ends when the last transfer has landed
-  hipEvent_t tail_s = g.ev_dxs[order.back().mb];
-  HIPCHK(hipStreamWaitEvent(g.sc, tail_s, 0));
-  if (g.wgrad_overlap) HIPCHK(hipStreamWaitEvent(g.sc, g.ev_w[order.back().mb], 0));
-  HIPCHK(hipEventRecord(g.ev_run_end, g.sc));
+  // the run ends when the last transfer has landed and both lanes have drained
+  hipStream_t q0 = g.lane[0].s;
+  HIPCHK(hipStreamWaitEvent(q0, g.ev_dxs[order.back().mb], 0));
+  TRY(join_compute_streams(q0));
+  HIPCHK(hipEventRecord(g.ev_run_end, q0));
   g.run_timed = true;
   return 0;
 }
@@ -785,11 +975,11 @@ int stage_last_k(void) { return g.last_k; }
 
 int stage_side_streams_overlap(void) {
   if (!g.inited) return fail(KFKB_E_STATE, "stage_side_streams_overlap before stage_init");
-  HIPCHK(hipStreamSynchronize(g.sc)); HIPCHK(hipStreamSynchronize(g.ss)); HIPCHK(hipStreamSynchronize(g.sr));
+  for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.ss, g.sr}) HIPCHK(hipStreamSynchronize(q));
   for (int rep = 0; rep < 2; rep++) {                 // first round warms the launch path up
     const auto t0 = std::chrono::steady_clock::now();
-    for (hipStream_t s : {g.sc, g.ss, g.sr}) HIPCHK(launch_delay(rep == 0 ? 1000 : 1000000, s));
-    for (hipStream_t s : {g.sc, g.ss, g.sr}) HIPCHK(hipStreamSynchronize(s));
+    for (hipStream_t s : {g.lane[0].s, g.ss, g.sr}) HIPCHK(launch_delay(rep == 0 ? 1000 : 1000000, s));
+    for (hipStream_t s : {g.lane[0].s, g.ss, g.sr}) HIPCHK(hipStreamSynchronize(s));
     const double ms = std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
     if (rep == 1) return ms < 1.8 ? 1 : 0;
   }
@@ -798,25 +988,41 @@ int stage_side_streams_overlap(void) {
 
 int stage_zero_grads(void) {
   if (!g.bound) return fail(KFKB_E_STATE, "stage_zero_grads before stage_bind");
-  if (g.last_wdone) HIPCHK(hipStreamWaitEvent(g.sc, g.last_wdone, 0));   // accumulation still in flight
-  HIPCHK(launch_fill_zero(g.grad, (size_t)g.L * g.po.total, g.sc));
+  hipStream_t q0 = g.lane[0].s;
+  TRY(join_compute_streams(q0));                                        // accumulation may still be in flight there
+  HIPCHK(launch_fill_zero(g.grad, (size_t)g.L * g.po.total, q0));
+  HIPCHK(hipEventRecord(g.ev_zero, q0));
+  HIPCHK(hipStreamWaitEvent(g.lane[1].s, g.ev_zero, 0));
+  if (g.sw != nullptr) HIPCHK(hipStreamWaitEvent(g.sw, g.ev_zero, 0));
+  std::fill(g.ev_g_set.begin(), g.ev_g_set.end(), 0);
   return 0;
 }
 
 int stage_set_wgrad_stream(int enable) {
   if (!g.inited) return fail(KFKB_E_STATE, "stage_set_wgrad_stream before stage_init");
   if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_wgrad_stream while micro-batches are live");
-  HIPCHK(hipStreamSynchronize(g.sc));
-  HIPCHK(hipStreamSynchronize(g.sw));
+  for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
+  if (g.sw != nullptr) HIPCHK(hipStreamSynchronize(g.sw));
   const int prev = g.wgrad_overlap ? 1 : 0;
   g.wgrad_overlap = enable != 0;
   return prev;
 }
 
+int stage_set_compute_lanes(int lanes) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_set_compute_lanes before stage_init");
+  if (lanes != 1 && lanes != 2) return fail(KFKB_E_ARG, "stage_set_compute_lanes: 1 or 2 lanes (got %d)", lanes);
+  if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_compute_lanes while micro-batches are live");
+  for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
+  if (g.sw != nullptr) HIPCHK(hipStreamSynchronize(g.sw));
+  const int prev = g.lanes;
+  g.lanes = lanes;
+  return prev;
+}
+
 int stage_sync(void) {
   if (!g.inited) return fail(KFKB_E_STATE, "stage_sync before stage_init");
-  HIPCHK(hipStreamSynchronize(g.sc));
-  HIPCHK(hipStreamSynchronize(g.sw));
+  for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
+  if (g.sw != nullptr) HIPCHK(hipStreamSynchronize(g.sw));
   HIPCHK(hipStreamSynchronize(g.sr));
   HIPCHK(hipStreamSynchronize(g.ss));
   return 0;
@@ -827,7 +1033,8 @@ int stage_sync_timeout(double seconds) {
   const auto t0 = std::chrono::steady_clock::now();
   for (;;) {
     bool done = true;
-    for (hipStream_t s : {g.sc, g.sw, g.sr, g.ss}) {
+    for (hipStream_t s : {g.lane[0].s, g.lane[1].s, g.sw, g.sr, g.ss}) {
+      if (s == nullptr) continue;
       hipError_t e = hipStreamQuery(s);
       if (e == hipErrorNotReady) done = false;
       else if (e != hipSuccess) return fail(KFKB_E_HIP, "hipStreamQuery failed: %s", hipGetErrorString(e));
@@ -864,12 +1071,16 @@ double stage_last_run_ms(void) {
 
 int stage_destroy(void) {
   if (!g.inited) return 0;
-  hipStreamSynchronize(g.sc); hipStreamSynchronize(g.sw); hipStreamSynchronize(g.sr); hipStreamSynchronize(g.ss);
-  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w})
+  for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) hipStreamSynchronize(q);
+  if (g.sw != nullptr) { hipStreamSynchronize(g.sw); hipStreamDestroy(g.sw); }
+  hipEventDestroy(g.ev_sw_tail);
+  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w, &g.ev_g})
     for (auto e : *v) hipEventDestroy(e);
-  for (int i = 0; i < Stage::kRing; i++) { hipEventDestroy(g.ev_chain[i]); hipEventDestroy(g.ev_wdone[i]); }
-  hipEventDestroy(g.ev_epoch); hipEventDestroy(g.ev_run_end);
-  hipStreamDestroy(g.sc); hipStreamDestroy(g.ss); hipStreamDestroy(g.sr); hipStreamDestroy(g.sw);
+  for (auto& ln : g.lane) {
+    for (int i = 0; i < Stage::kRing; i++) { hipEventDestroy(ln.ev_chain[i]); hipEventDestroy(ln.ev_wdone[i]); }
+    hipEventDestroy(ln.ev_tail);
+  }
+  hipEventDestroy(g.ev_epoch); hipEventDestroy(g.ev_run_end); hipEventDestroy(g.ev_zero);
   g = Stage{};
   g_cfg_set = false;
   return 0;

@@ -287,6 +287,7 @@ __global__ void __launch_bounds__(256) colsum_final_kernel(const float* __restri
 
 static inline int reduce_parts(int rows) { return std::max(1, std::min(64, (rows + 31) / 32)); }
 
+// out_sum == nullptr: only the partial sums are written (the finishing pass is issued separately)
 template <typename T, bool XHAT>
 static hipError_t colsum_launch(const T* dy, const T* x, const float* mean, const float* rstd, float* out_sum,
                                 float* out_xhat, float* scratch, int rows, int width, hipStream_t s) {
@@ -296,8 +297,9 @@ static hipError_t colsum_launch(const T* dy, const T* x, const float* mean, cons
   const double bytes = (double)rows * width * sizeof(T) * (XHAT ? 2 : 1);
   klaunch(colsum_partial_kernel<T, XHAT>, grid, dim3(256), 0, s, (XHAT ? PK_COLSUM_XHAT : PK_COLSUM) + (int)sizeof(T), bytes, dy, x,
           mean, rstd, scratch, rows, width, rpp);
-  klaunch(colsum_final_kernel, dim3((width + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * width * 4 * (XHAT ? 2 : 1),
-          scratch, parts, width, out_sum, XHAT ? out_xhat : (float*)nullptr);
+  if (out_sum != nullptr)
+    klaunch(colsum_final_kernel, dim3((width + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * width * 4 * (XHAT ? 2 : 1),
+            scratch, parts, width, out_sum, XHAT ? out_xhat : (float*)nullptr);
   return hipGetLastError();
 }
 
@@ -477,8 +479,9 @@ static hipError_t ln_bwd_fused_launch(const T* dy, const T* x, const float* mean
   const double bytes = (dres ? 4.0 : 3.0) * rows * H * sizeof(T);
   klaunch(ln_bwd_fused_kernel<T, NCH>, dim3(parts), dim3(256), (size_t)8 * H * sizeof(float), s,
           PK_LN_BWD_DX + 80 + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, scratch, rows, H, rpb);
-  klaunch(colsum_final_kernel, dim3((H + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * H * 8, (const float*)scratch,
-          parts, H, dbeta, dgamma);
+  if (dgamma != nullptr)
+    klaunch(colsum_final_kernel, dim3((H + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * H * 8, (const float*)scratch,
+            parts, H, dbeta, dgamma);
   return hipGetLastError();
 }
 
@@ -495,7 +498,7 @@ static hipError_t ln_bwd_t(const T* dy, const T* x, const float* mean, const flo
   KFKB_NCH_SWITCH(nch, klaunch(ln_bwd_dx_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_BWD_DX + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, rows, H));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  return colsum_launch<T, true>(dy, x, mean, rstd, dbeta, dgamma, scratch, rows, H, s);
+  return colsum_launch<T, true>(dy, x, mean, rstd, dgamma != nullptr ? dbeta : (float*)nullptr, dgamma, scratch, rows, H, s);
 }
 
 hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mean, const float* rstd,
@@ -507,6 +510,22 @@ hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mea
                             (bf16_t*)dx, dgamma, dbeta, scratch, rows, H, s);
   return ln_bwd_t<float>((const float*)dy, (const float*)x, mean, rstd, (const float*)gamma, (const float*)dres,
                          (float*)dx, dgamma, dbeta, scratch, rows, H, s);
+}
+
+// The finishing pass of launch_ln_bwd called with dgamma == nullptr: adds the partial sums it left in `scratch`
+// into dgamma / dbeta.  rows and H must be those of that call (they fix the number of partial rows).
+hipError_t launch_ln_bwd_final(const float* scratch, int rows, int H, float* dgamma, float* dbeta, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  int parts;
+  if (nch_for(H) <= 4) {
+    const int rpb = std::max(8, ((rows + 511) / 512 + 3) / 4 * 4);
+    parts = (rows + rpb - 1) / rpb;
+  } else {
+    parts = reduce_parts(rows);
+  }
+  klaunch(colsum_final_kernel, dim3((H + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * H * 8, scratch, parts, H,
+          dbeta, dgamma);
+  return hipGetLastError();
 }
 
 hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratch, int rows, int N, hipStream_t s) {

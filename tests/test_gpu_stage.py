@@ -167,6 +167,7 @@ def test_delays_change_timing_not_results():
     dt, L, H, heads, T, b, M = kf.F32, 1, 64, 2, 32, 1, 8
     st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=4)
     overlap = kf.stage_side_streams_overlap()           # 0 if some other stream of the process shares a queue
+    kf.stage_set_compute_lanes(1)                       # the oracle's timing model has one compute resource
     _run(st, 1, M)
     _run(st, 1, M)
     ref = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
@@ -199,3 +200,37 @@ def test_delays_change_timing_not_results():
     kf.stage_set_delays(None, None, None, None)
     assert kf.stage_sync_timeout(5.0) == 0
     st.close()
+
+
+@pytest.mark.parametrize("dt", [kf.F32, kf.BF16])
+def test_lanes_and_w_step_placement_change_timing_not_results(dt):
+    """One or two compute lanes, W steps beside or behind their chain: the same bits and the same issue
+    order for every combination, for several k and with a warm-up depth above zero (more live micro-batches,
+    hence more ops in flight)."""
+    L, H, heads, T, b, M = (3, 128, 2, 64, 2, 8)
+    if dt == kf.BF16:
+        T = 128
+    for S, s in ((1, 0), (3, 0)):
+        st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=4, S=S, s=s)
+        ref = None
+        for lanes in (1, 2):
+            for w_beside in (0, 1):
+                kf.stage_set_compute_lanes(lanes)
+                kf.stage_set_wgrad_stream(w_beside)
+                for k in (1, 2, 4):
+                    G, Y, dX, order = _run(st, k, M)
+                    assert order == sch.kfkb_order(k, M, min(S - 1 - s, (M + k - 1) // k))
+                    got = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+                    if ref is None:
+                        ref = got
+                        _check_against_oracle(dt, st, blocks, xs, dys, heads, 1, G, Y, dX, order, k,
+                                              w=min(S - 1 - s, (M + k - 1) // k))
+                    for a, b_ in zip(ref, got):
+                        assert torch.equal(a, b_), (lanes, w_beside, k)
+                    log = kf.stage_get_order()
+                    assert all(t1 >= t0 for _, _, t0, t1 in log)
+                    if lanes == 1:                              # one lane: ops follow one another
+                        assert all(log[i + 1][2] >= log[i][3] - 1e-3 for i in range(len(log) - 1))
+        kf.stage_set_compute_lanes(2)
+        kf.stage_set_wgrad_stream(1)
+        st.close()
