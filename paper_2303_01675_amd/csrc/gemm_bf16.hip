@@ -121,7 +121,10 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 // The main loop shared by the NT and TN kernels.  LAYOUT supplies the DMA source offsets and the fragment reads.
 //   chunk kc lives in ring slot kc % 4.  One chunk = two 16-deep k-steps; a k-step = TN groups of TM MFMAs.
 //   Every group carries one DMA instruction (B part of chunk kc+3 during k-step 0, A part of chunk kc+4 during
-//   k-step 1) and up to PER fragment reads of the next k-step; nothing moves across group boundaries.
+//   k-step 1) and up to PER fragment reads of the next k-step.  A load that writes LDS keeps its wave from
+//   issuing anything else for about 32 clocks (measured: one wave alone moves 31 bytes per clock), which is the
+//   time one MFMA occupies the matrix pipe: in the 256 x 256 tiles every MFMA is therefore followed by exactly one
+//   memory instruction, pinned there, and the pipe never waits for the issue port.
 //   Between the k-steps every wave waits for its own loads of chunk kc+1 and all waves meet: after that chunk
 //   kc+1 is complete in LDS and slot kc % 4 is free.
 // ------------------------------------------------------------------------------------------------
@@ -148,18 +151,32 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
   auto step = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], bf16x8 (&na)[TM], bf16x8 (&nb)[TN], int nslot, int nks, auto&& dma) {
     constexpr int NR = TM + TN;
     constexpr int PER = (NR + TN - 2) / (TN - 1);      // reads per group so that the last group has none
+    auto rd = [&](int r) {
+      if (r == 0) nb[0] = lay.rd_b(nslot, nks, 0);
+      else if (r <= TM) na[r - 1] = lay.rd_a(nslot, nks, r - 1);
+      else nb[r - TM] = lay.rd_b(nslot, nks, r - TM);
+    };
 #pragma unroll
     for (int j = 0; j < TN; j++) {
+      if constexpr (PER + 1 <= TM) {
+        // MFMA i is followed by exactly one memory instruction (the DMA after the first, fragment reads after
+        // the next ones): each issues while that MFMA occupies the matrix pipe
 #pragma unroll
-      for (int r = j * PER; r < (j + 1) * PER && r < NR; r++) {
-        if (r == 0) nb[0] = lay.rd_b(nslot, nks, 0);
-        else if (r <= TM) na[r - 1] = lay.rd_a(nslot, nks, r - 1);
-        else nb[r - TM] = lay.rd_b(nslot, nks, r - TM);
+        for (int i = 0; i < TM; i++) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+          if (i == 0) dma(j);
+          else { const int r = j * PER + (i - 1); if (i - 1 < PER && r < NR) rd(r); }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+#pragma unroll
+        for (int r = j * PER; r < (j + 1) * PER && r < NR; r++) rd(r);
+        dma(j);
+#pragma unroll
+        for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
-      dma(j);
-#pragma unroll
-      for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-      __builtin_amdgcn_sched_barrier(0);
     }
   };
   auto chunk = [&](int kc, int slot) {
