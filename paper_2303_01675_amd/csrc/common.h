@@ -120,6 +120,8 @@ hipError_t launch_colsum_group(int dt, int n, const void* const* dy, float* cons
 hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int cols, hipStream_t s);
+// bf16 weight operand B[N][K] of an NT GEMM -> chunk-major [K/32][N][32]; transposed: src holds B^T as [K][N]
+hipError_t launch_tile_weights(const void* src, void* dst, int N, int K, bool transposed, hipStream_t s);
 hipError_t launch_delay(int64_t ns, hipStream_t s);
 
 struct GemmArgs {
@@ -127,6 +129,7 @@ struct GemmArgs {
   const void *A, *B, *bias, *residual;
   void *C, *C2;
   float* Cacc;
+  bool b_tiled = false;      // NT only: B is stored chunk-major, [K/32][N][32] (see launch_tile_weights)
 };
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);   // NT and TN only

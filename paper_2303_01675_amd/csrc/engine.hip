@@ -271,7 +271,7 @@ Carve carve_for(const Stage& s, int k_max) {
   const size_t act = align_up(s.n * s.esz);
   size_t off = 0;
   c.wt = off;
-  if (s.dt == DT_BF16) off += align_up((size_t)s.L * ((size_t)4 * s.H * s.H + 2 * (size_t)s.H * s.F) * 2);
+  if (s.dt == DT_BF16) off += align_up((size_t)2 * s.L * ((size_t)4 * s.H * s.H + 2 * (size_t)s.H * s.F) * 2);
   c.stash = off; off += (size_t)c.n_stash * s.L * stash_block_bytes_of(s);
   c.xs = off; off += (size_t)c.n_x * act;
   c.dys = off; off += (size_t)c.n_io * act;
@@ -298,18 +298,22 @@ StashView view(const Stage& s, int slot, int l) {
   return v;
 }
 
-// re-laid-out weight matrices of block l (bf16): [out, in]
-struct WtView { const char *qkv, *o, *w1, *w2; };
+// chunk-major copies of the weight matrices of block l (bf16), as the B operand of the NT GEMMs:
+// forward products read W^T (B[N = out][K = in]), input-gradient products read W (B[N = in][K = out])
+struct WtView { const char *qkv, *o, *w1, *w2, *qkv_d, *o_d, *w1_d, *w2_d; };
 WtView wt_view(const Stage& s, int l) {
   const size_t H = s.H, F = s.F;
   const size_t per = (3 * H * H + H * H + 2 * H * F) * 2;
-  const char* p = s.wt + (size_t)l * per;
-  return WtView{p, p + 3 * H * H * 2, p + 4 * H * H * 2, p + (4 * H * H + H * F) * 2};
+  const char* p = s.wt + (size_t)l * 2 * per;
+  const char* d = p + per;
+  return WtView{p, p + 3 * H * H * 2, p + 4 * H * H * 2, p + (4 * H * H + H * F) * 2,
+                d, d + 3 * H * H * 2, d + 4 * H * H * 2, d + (4 * H * H + H * F) * 2};
 }
 
 int gemm(const Stage& s, hipStream_t st, int kind, int epi, int M, int N, int K, const void* A, const void* B, const void* bias,
-         const void* res, void* C, void* C2, float* Cacc) {
+         const void* res, void* C, void* C2, float* Cacc, bool b_tiled = false) {
   GemmArgs a{kind, epi, M, N, K, A, B, bias, res, C, C2, Cacc};
+  a.b_tiled = b_tiled;
   if (s.dt == DT_BF16) {
     const char* why = gemm_bf16_check(a);
     if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
@@ -323,7 +327,7 @@ int gemm(const Stage& s, hipStream_t st, int kind, int epi, int M, int N, int K,
 // forward linear map y = x W + b (+ epilogue): fp32 reads W [in,out] as given, bf16 reads the [out,in] copy
 int linear_fwd(const Stage& s, hipStream_t st, int epi, int in, int out, const void* x, const void* W, const void* Wt, const void* bias,
                const void* res, void* y, void* y2) {
-  if (s.dt == DT_BF16) return gemm(s, st, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr);
+  if (s.dt == DT_BF16) return gemm(s, st, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr, true);
   return gemm(s, st, KFKB_GEMM_NN, epi, s.m, out, in, x, W, bias, res, y, y2, nullptr);
 }
 
@@ -332,10 +336,15 @@ int refresh_weights() {
   hipStream_t st = g.lane[0].s;
   for (int l = 0; l < g.L; l++) {
     WtView w = wt_view(g, l);
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_qkv), (void*)w.qkv, g.H, 3 * g.H, st));
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_o), (void*)w.o, g.H, g.H, st));
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_1), (void*)w.w1, g.H, g.F, st));
-    HIPCHK(launch_transpose(DT_BF16, wptr(g, l, g.po.w_2), (void*)w.w2, g.F, g.H, st));
+    // W is stored [in, out]: forward B = W^T has N = out, K = in; input-gradient B = W has N = in, K = out
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_qkv), (void*)w.qkv, 3 * g.H, g.H, true, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_o), (void*)w.o, g.H, g.H, true, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_1), (void*)w.w1, g.F, g.H, true, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_2), (void*)w.w2, g.H, g.F, true, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_qkv), (void*)w.qkv_d, g.H, 3 * g.H, false, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_o), (void*)w.o_d, g.H, g.H, false, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_1), (void*)w.w1_d, g.H, g.F, false, st));
+    HIPCHK(launch_tile_weights(wptr(g, l, g.po.w_2), (void*)w.w2_d, g.F, g.H, false, st));
   }
   return 0;
 }
@@ -371,7 +380,7 @@ int forward_block(ActiveOp& a) {
   hipStream_t q = s.lane[a.lane].s;
   const int l = a.next;
   StashView v = view(s, st.stash, l);
-  WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{nullptr, nullptr, nullptr, nullptr};
+  WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{};
   const char* x = a.cur;
   char* y = (l == s.L - 1) ? s.ys.buf[a.out_buf] : v.y;
   HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, q));
@@ -402,6 +411,8 @@ int backward_block(ActiveOp& a) {
   char* da = ln.t_n0;            // d_o is dead once dqkv exists
   const char* dy = a.cur;
   StashView v = view(s, st.stash, l);
+  const bool bt = s.dt == DT_BF16;                      // bf16 input-gradient products read the chunk-major copies
+  WtView w = bt ? wt_view(s, l) : WtView{};
   const char* x = (l == 0) ? s.xs.buf[st.x_slot] : view(s, st.stash, l - 1).y;
   char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : ln.t_dxr[seq % 3];
   // where the W step of this block goes: the other lane's stream, beside this chain, when that lane has nothing
@@ -417,20 +428,20 @@ int backward_block(ActiveOp& a) {
   };
   // y = x1 + g W2 + b2
   wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
-  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, bt ? w.w2_d : wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr, bt));
   // u = c W1 + b1
   wgrad(1, s.H, s.F, v.c, du, gptr(s, l, s.po.w_1));
-  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, bt ? w.w1_d : wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr, bt));
   // c = LN2(x1), plus the residual path; the parameter gradients are finished in the W step
   HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, nullptr, nullptr, ln.red_ln[par][1], s.m, s.H, q));
   // x1 = x + o Wo + bo
   wgrad(3, s.H, s.H, v.o, dx1, gptr(s, l, s.po.w_o));
-  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, bt ? w.o_d : wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr, bt));
   // o = attention(qkv)
   TRY(attention_bwd(s, q, v.qkv, v.o, d_o, v.lse, ln.dsum, dqkv));
   // qkv = a Wqkv + bqkv
   wgrad(0, s.H, 3 * s.H, v.a, dqkv, gptr(s, l, s.po.w_qkv));
-  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr));
+  TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, bt ? w.qkv_d : wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr, bt));
   // a = LN1(x), plus the residual path
   HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, nullptr, nullptr, ln.red_ln[par][0], s.m, s.H, q));
 

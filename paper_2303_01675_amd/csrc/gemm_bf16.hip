@@ -198,21 +198,23 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
 
 // NT operands: X[rows, K] row-major, both.  LDS chunk [rows][32]: 16-byte piece p of row r holds logical piece
 // p ^ ((r >> 2) & 3): the 16 rows a fragment read touches per clock land on 16 different 16-byte bank groups.
-template <int BM, int BN>
+// BT: the B operand is stored chunk-major, [K/32][N][32] (the stage's weight copies): a chunk of B rows is then one
+// contiguous run, where row-major rows give every load half a cache line per row and make L2 serve each line twice.
+template <int BM, int BN, bool BT>
 struct NtLayout {
   static constexpr int TM = BM / 64, TN = BN / 64, A_SLOT = BM * CK_, B_SLOT = BN * CK_;
   static_assert(TM == TN, "one DMA instruction per MFMA group");
-  i32x4 ra, rb; unsigned lds0; int wave, nk; int voa[TN], vob[TN];
+  i32x4 ra, rb; unsigned lds0; int wave, nk, sb; int voa[TN], vob[TN];
   const bf16_t* fa_base[2]; const bf16_t* fb_base[2];
   __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
-    wave = wave_; nk = K / CK_;
+    wave = wave_; nk = K / CK_; sb = BT ? N * CK_ * 2 : CK_ * 2;      // bytes from one chunk of B to the next
     ra = make_rsrc(A, (size_t)M * K * 2); rb = make_rsrc(B, (size_t)N * K * 2);
     lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
     const int lrow = lane >> 2, lpiece = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
     for (int i = 0; i < TN; i++) {
       voa[i] = ((m0 + (i * 4 + wave) * 16 + lrow) * K + lpiece * 8) * 2;
-      vob[i] = ((n0 + (i * 4 + wave) * 16 + lrow) * K + lpiece * 8) * 2;
+      vob[i] = ((n0 + (i * 4 + wave) * 16 + lrow) * (BT ? CK_ : K) + lpiece * 8) * 2;
     }
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
     const int frow = lane & 31, fhalf = lane >> 5, fsw = (lane >> 2) & 3;
@@ -225,7 +227,7 @@ struct NtLayout {
     }
   }
   __device__ __forceinline__ void dma_a(int i, int kc, int slot) { dma16b(ra, voa[i], min(kc, nk - 1) * (CK_ * 2), lds0 + (slot * A_SLOT + (i * 4 + wave) * 512) * 2); }
-  __device__ __forceinline__ void dma_b(int i, int kc, int slot) { dma16b(rb, vob[i], min(kc, nk - 1) * (CK_ * 2), lds0 + (RING * A_SLOT + slot * B_SLOT + (i * 4 + wave) * 512) * 2); }
+  __device__ __forceinline__ void dma_b(int i, int kc, int slot) { dma16b(rb, vob[i], min(kc, nk - 1) * sb, lds0 + (RING * A_SLOT + slot * B_SLOT + (i * 4 + wave) * 512) * 2); }
   __device__ __forceinline__ bf16x8 rd_a(int slot, int ks, int i) { return *reinterpret_cast<const bf16x8*>(fa_base[ks] + slot * A_SLOT + i * 32 * CK_); }
   __device__ __forceinline__ bf16x8 rd_b(int slot, int ks, int j) { return *reinterpret_cast<const bf16x8*>(fb_base[ks] + slot * B_SLOT + j * 32 * CK_); }
 };
@@ -357,7 +359,7 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
   }
 }
 
-template <int BM, int BN, int EPI>
+template <int BM, int BN, int EPI, bool BT>
 __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
                                                  const bf16_t* __restrict__ bias, const bf16_t* __restrict__ residual,
                                                  bf16_t* __restrict__ C, bf16_t* __restrict__ C2, float* __restrict__ Cacc,
@@ -370,7 +372,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  NtLayout<BM, BN> lay;
+  NtLayout<BM, BN, BT> lay;
   lay.init(smem, A, B, M, N, K, m0, n0, lane, wave);
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -604,12 +606,12 @@ template <int BM, int BN> constexpr size_t tile_lds_bytes() {
   return std::max((size_t)RING * (BM + BN) * CK_ * sizeof(bf16_t), epilogue_lds_bytes<BM, BN>());
 }
 
-template <int BM, int BN, int EPI>
-static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
+template <int BM, int BN, int EPI, bool BT>
+static hipError_t launch_nt_bt(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   constexpr size_t smem = tile_lds_bytes<BM, BN>();
-  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI>;
+  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, BT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -620,6 +622,10 @@ static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
           (const bf16_t*)g.A, (const bf16_t*)g.B, (const bf16_t*)g.bias, (const bf16_t*)g.residual, (bf16_t*)g.C,
           (bf16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
+}
+template <int BM, int BN, int EPI>
+static hipError_t launch_nt(const GemmArgs& g, hipStream_t s) {
+  return g.b_tiled ? launch_nt_bt<BM, BN, EPI, true>(g, s) : launch_nt_bt<BM, BN, EPI, false>(g, s);
 }
 
 template <int BM, int BN, int EPI>

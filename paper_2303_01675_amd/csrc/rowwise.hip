@@ -432,6 +432,33 @@ __global__ void __launch_bounds__(256) transpose_kernel(const U* __restrict__ in
   }
 }
 
+// Weight operand of the NT GEMMs in chunk-major form: dst[kc][n][kk] = B[n][32 kc + kk], B[N][K] being the operand
+// as the GEMM sees it.  TRANSPOSED: the source holds B^T, src[K][N] (a forward product reads W[in,out] as B = W^T);
+// otherwise src[N][K] (an input-gradient product reads W[in,out] as it is).  A 32-deep chunk of consecutive
+// rows is then one contiguous run of memory, whole cache lines for every load of the GEMM.
+template <bool TRANSPOSED>
+__global__ void __launch_bounds__(256) tile_weights_kernel(const uint16_t* __restrict__ src, uint16_t* __restrict__ dst, int N, int K) {
+  __shared__ uint16_t tile[32][33];
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;     // 32 x 8
+  const int n0 = blockIdx.x * 32, kc = blockIdx.y;
+#pragma unroll
+  for (int j = 0; j < 32; j += 8) {
+    if (TRANSPOSED) {                 // read src[32 kc + (ty + j)][n0 + tx]
+      const int k = kc * 32 + ty + j, n = n0 + tx;
+      tile[ty + j][tx] = (k < K && n < N) ? src[(size_t)k * N + n] : (uint16_t)0;     // tile[kk][nn]
+    } else {                          // read src[n0 + (ty + j)][32 kc + tx]
+      const int n = n0 + ty + j, k = kc * 32 + tx;
+      tile[tx][ty + j] = (k < K && n < N) ? src[(size_t)n * K + k] : (uint16_t)0;     // tile[kk][nn]
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int j = 0; j < 32; j += 8) {
+    const int n = n0 + ty + j;
+    if (n < N) dst[((size_t)kc * N + n) * 32 + tx] = tile[tx][ty + j];
+  }
+}
+
 // Returns after `ticks` ticks of the 100 MHz device wall clock.  One wave; it sleeps between polls
 // and always terminates because the clock is monotonic and `ticks` is bounded by the host.
 __global__ void delay_kernel(long long ticks) {
@@ -560,6 +587,14 @@ hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int col
     hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, rows, cols);
   else
     hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)in, (uint32_t*)out, rows, cols);
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_weights(const void* src, void* dst, int N, int K, bool transposed, hipStream_t s) {
+  if (N <= 0 || K <= 0) return hipSuccess;
+  const dim3 grid((N + 31) / 32, (K + 31) / 32);
+  if (transposed) hipLaunchKernelGGL(tile_weights_kernel<true>, grid, dim3(256), 0, s, (const uint16_t*)src, (uint16_t*)dst, N, K);
+  else hipLaunchKernelGGL(tile_weights_kernel<false>, grid, dim3(256), 0, s, (const uint16_t*)src, (uint16_t*)dst, N, K);
   return hipGetLastError();
 }
 
