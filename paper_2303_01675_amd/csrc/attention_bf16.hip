@@ -21,6 +21,7 @@
 //
 // LDS tiles are [64 rows][D] with the 16-byte chunk index XOR-ed with a function of the row (TileIO::sw).
 #include "common.h"
+#include <cstdlib>
 
 namespace kfkb {
 
@@ -98,13 +99,21 @@ __device__ __forceinline__ int acc_row(int r, int hh) { return (r >> 2) * 8 + hh
 // block ids are dealt round-robin to the 8 XCDs, each with its own L2.  All row blocks of one (sample, head)
 // are therefore given to ONE XCD (its K and V, or Q and dO, then stay in that L2), longest first, and every XCD
 // gets the same mix of short and long blocks.  Falls back to a rotation when sample*head does not divide by 8.
-__device__ __forceinline__ void block_to_work(int& rb, int& bh) {
+// `pair` (set by the host when an XCD's blocks are exactly two per CU, all resident at once): the hardware hands an
+// XCD's blocks to its 32 CUs in turn, so blocks n and n + 32 share a CU; the second half of the sequence is then
+// dealt shortest first, and every CU gets a long and a short block (measured: 16 % off the forward kernel and 13 %
+// off the backward kernels of the 1024-token stage; longest-first is better as soon as blocks queue up).
+__device__ __forceinline__ void block_to_work(int& rb, int& bh, int pair) {
   const int gx = gridDim.x, gy = gridDim.y;
   if (gy % 8 == 0) {
     const int lin = blockIdx.y * gx + blockIdx.x;
     const int xcd = lin & 7, n = lin >> 3;
-    bh = xcd + 8 * (n / gx);
-    rb = gx - 1 - n % gx;
+    const int half = (gx * (gy >> 3)) >> 1;         // half of this XCD's blocks
+    int h, r;
+    if (pair && n >= half) { const int i = n - half; h = (half / gx) + i / gx; r = i % gx; }
+    else { h = n / gx; r = gx - 1 - n % gx; }
+    bh = xcd + 8 * h;
+    rb = r;
   } else {
     bh = blockIdx.y;
     rb = (blockIdx.x + blockIdx.y) % gx;
@@ -117,7 +126,7 @@ __device__ __forceinline__ void block_to_work(int& rb, int& bh) {
 template <int D>
 __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
                                                             float* __restrict__ lse, int T, int H, int heads,
-                                                            int causal, float scale_log2) {
+                                                            int causal, float scale_log2, int pair) {
   using IO = TileIO<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);     // [2][64][D]
@@ -127,7 +136,7 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
   int qb, bh;
-  block_to_work(qb, bh);
+  block_to_work(qb, bh, pair);
   const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
@@ -245,7 +254,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
                                                                const bf16_t* __restrict__ d_o,
                                                                const float* __restrict__ lse, float* __restrict__ dsum,
                                                                bf16_t* __restrict__ dqkv, int T, int H, int heads,
-                                                               int causal, float scale) {
+                                                               int causal, float scale, int pair) {
   using IO = TileIO<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);
@@ -255,7 +264,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
   int qb, bh;
-  block_to_work(qb, bh);
+  block_to_work(qb, bh, pair);
   const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
   const bf16_t* base = qkv + (size_t)bi * T * ld;
@@ -365,7 +374,7 @@ template <int D>
 __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
                                                                 const float* __restrict__ lse, const float* __restrict__ dsum,
                                                                 bf16_t* __restrict__ dqkv, int T, int H, int heads,
-                                                                int causal, float scale) {
+                                                                int causal, float scale, int pair) {
   using IO = TileIO<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   bf16_t* Qs = reinterpret_cast<bf16_t*>(smem);     // [2][64][D]
@@ -377,7 +386,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
   int kb, bh;
-  block_to_work(kb, bh);
+  block_to_work(kb, bh, pair);
   kb = gridDim.x - 1 - kb;                          // for keys the early blocks are the long ones
   const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
@@ -509,6 +518,15 @@ static hipError_t set_smem(K kern, size_t bytes, bool& done) {
   return e;
 }
 
+// two blocks per CU, all of an XCD's blocks resident at once (8 XCDs of 32 CUs)?
+template <typename K>
+static int pair_blocks(K kern, size_t smem, int gx, int gy, int causal) {
+  if (!causal || gy % 8 != 0 || gx * (gy / 8) != 64 || 32 % gx != 0) return 0;
+  int per_cu = 0;
+  if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, 256, smem) != hipSuccess) return 0;
+  return per_cu >= 2 ? 1 : 0;
+}
+
 template <int D>
 static hipError_t fwd_d(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s) {
   static bool attr = false;
@@ -518,7 +536,7 @@ static hipError_t fwd_d(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, 
   const float scale_log2 = kLog2e / sqrtf((float)D);
   const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
   klaunch(attn_fwd_bf16_kernel<D>, dim3((T + 127) / 128, b * heads), dim3(256), smem, s, PK_ATTN_FWD + D / 128, 4.0 * pairs * D,
-          qkv, o, lse, T, H, heads, causal, scale_log2);
+          qkv, o, lse, T, H, heads, causal, scale_log2, pair_blocks(attn_fwd_bf16_kernel<D>, smem, (T + 127) / 128, b * heads, causal));
   return hipGetLastError();
 }
 
@@ -536,9 +554,9 @@ static hipError_t bwd_d(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, c
   const dim3 grid((T + 127) / 128, b * heads);
   const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
   klaunch(attn_bwd_dq_bf16_kernel<D>, grid, dim3(256), smem1, s, PK_ATTN_DQ + D / 128, 6.0 * pairs * D, qkv, o, d_o, lse, dsum, dqkv,
-          T, H, heads, causal, scale);
+          T, H, heads, causal, scale, pair_blocks(attn_bwd_dq_bf16_kernel<D>, smem1, (int)grid.x, (int)grid.y, causal));
   klaunch(attn_bwd_dkv_bf16_kernel<D>, grid, dim3(256), smem2, s, PK_ATTN_DKV + D / 128, 8.0 * pairs * D, qkv, d_o, lse,
-          (const float*)dsum, dqkv, T, H, heads, causal, scale);
+          (const float*)dsum, dqkv, T, H, heads, causal, scale, pair_blocks(attn_bwd_dkv_bf16_kernel<D>, smem2, (int)grid.x, (int)grid.y, causal));
   return hipGetLastError();
 }
 
