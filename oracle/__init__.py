@@ -12,4 +12,6 @@ Modules
               one whole iteration with gradient accumulation
   transfer_sim  discrete-event model of the delayed inter-stage transfers
                 (timing only: "parity unpinned" beyond its closed-form checks)
+  tuner       cost model and online choice of k (moving averages of measured
+              transfer times, estimated iteration length per candidate plan)
 """
