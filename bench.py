@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--lanes", type=int, default=2, choices=[1, 2],
                     help="compute lanes (the library's default is 2): ops in flight at once, within the plan's peak of live "
                          "micro-batches")
+    ap.add_argument("--adaptive", action="store_true",
+                    help="also time the same steps under the tuner (run_kFkB_adaptive: moving averages of the measured "
+                         "transfer times, k re-chosen every 2 iterations among the workload's k values)")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -145,6 +148,25 @@ def main():
                         activation_gb=kf.stage_activation_bytes(k, M) / 1e9)
     best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
 
+    adaptive = None
+    if args.adaptive:
+        cands = sorted(k for k in per_k)
+        kf.stage_sync()
+        kf.kfkb_tuner_config(2, 2, cands)
+        kf.stage_set_delays(None, None, None, None)
+        kf.stage_tuner_calibrate(M, 2)
+        chosen = []
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            set_delays(i, args.steps)
+            kf.stage_zero_grads()
+            chosen.append(kf.run_kFkB_adaptive(M, limit))
+        kf.stage_sync()
+        dt_s = time.perf_counter() - t0
+        adaptive = dict(ms_per_step=1e3 * dt_s / args.steps, samples_per_s=M * b * args.steps / dt_s, k_per_step=chosen,
+                        window=2, interval=2, candidates=cands)
+
     # per-kernel timing of the same steps at the best k: HIP start/stop events on the stream of each launch.
     # Kernels that share the chip stretch each other's durations, so this pass runs on one lane with the W steps
     # behind their chains: every duration below is that of a kernel running alone.
@@ -225,7 +247,7 @@ def main():
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
         "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,
         "per_k": {str(k): v for k, v in per_k.items()},
-        "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
+        "adaptive": adaptive, "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
     }
     st.close()
     if args.copy_calibration:

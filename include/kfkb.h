@@ -81,6 +81,39 @@ int kfkb_peak_live(int k, int num_microbatches, int warmup_groups);
 size_t kfkb_activation_bytes_per_microbatch(int layers, int micro_batch, int seq, int hidden, int heads,
                                             int mlp_width, int elem_bytes);
 
+/* ---- cost model and online choice of k (paper Sections 3.3 "auto tunner", 5.2, 5.4) -------------- *
+ * The pipeline length of a candidate plan is estimated from stage computation times, profiled once *
+ * per plan, and from communication times measured end to end and averaged over a moving window;    *
+ * at regular intervals the admissible candidate with the shortest estimate is taken (ties: the      *
+ * smaller k), and the switch costs nothing because no parameter moves.  The calls of this block are *
+ * host-only; times are in milliseconds.                                                            */
+
+/* Estimated iteration time of plan (k, M, w) on one stage whose neighbours do no compute: a discrete-event
+ * run of the transfer rules (three FIFO resources compute / receive / send; send Y_mb after F(mb), send dX_mb
+ * after B(mb), dY_mb arrives only after Y_mb has been sent, inputs are sent ahead as far as the slot pools
+ * allow, a slot returns to its pool when the backward that read it ends).  Every op takes t_fwd / t_bwd and
+ * every transfer of a direction its t_*.  x_slots / dy_slots: pool sizes, 0 = peak live + k and 2k.
+ * Returns a negative error code for an invalid plan. */
+double kfkb_predict_iteration_ms(int k, int num_microbatches, int warmup_groups, double t_fwd, double t_bwd,
+                                 double t_recv_x, double t_recv_dy, double t_send_y, double t_send_dx,
+                                 int x_slots, int dy_slots);
+
+/* Candidates (1..8 group sizes), window = samples of the moving averages, interval = iterations between
+ * evaluations.  Clears the windows, the computation profile and the iteration count; the current k becomes
+ * the smallest candidate. */
+int kfkb_tuner_config(int window, int interval, const int* candidates, int num_candidates);
+/* Stage computation time of one forward / backward under plan k (profiled once, reused afterwards). */
+int kfkb_tuner_set_compute_profile(int k, double t_fwd, double t_bwd);
+/* One sample per direction (the mean transfer time of one iteration) into the windows; counts an iteration. */
+int kfkb_tuner_push_sample(double t_recv_x, double t_recv_dy, double t_send_y, double t_send_dx);
+/* Group size of the next iteration: re-evaluated when the number of samples pushed so far is a positive
+ * multiple of `interval`, otherwise unchanged.  Candidates above num_microbatches, without a profile, or whose
+ * peak of live micro-batches times bytes_per_microbatch exceeds mem_limit (0 = no limit) are skipped.
+ * estimates (may be NULL): the estimate of every candidate at the last evaluation, in candidate order,
+ * -1 where skipped. */
+int kfkb_tuner_next_k(int num_microbatches, int warmup_groups, size_t mem_limit, size_t bytes_per_microbatch,
+                      double* estimates, int cap);
+
 /* ---- the stage ------------------------------------------------------------------------- */
 
 /* Optional; must precede stage_init.  Copies *cfg. */
@@ -174,6 +207,22 @@ int stage_destroy(void);
 /* Executed-order log of the ops enqueued since the last run_kFkB began (or since bind): up to
  * cap entries, returns the count.  Times are resolved from HIP events: call after stage_sync. */
 int stage_get_order(kfkb_op_t* out, int cap);
+
+/* Measured transfer times (ms, injected delay + copy, from the moment the stream was free to start it) of the
+ * micro-batches of the last iteration: direction 0 receive X, 1 receive dY, 2 send Y, 3 send dX.  Fills
+ * out[mb]; returns the number of micro-batches.  Call after stage_sync. */
+int stage_get_transfer_ms(int direction, double* out, int cap);
+
+/* Profiles the stage computation of every tuner candidate (paper Section 5.2): `repeats` iterations of
+ * `num_microbatches` per candidate with the injected delays switched off, mean forward / backward op times
+ * scaled so that they add up to the measured iteration (ops of two lanes overlap).  Accumulates into
+ * grad_accum: zero it afterwards.  Blocks until done. */
+int stage_tuner_calibrate(int num_microbatches, int repeats);
+
+/* One iteration under the tuner: waits for the previous adaptive iteration, pushes its mean transfer times
+ * into the windows, asks kfkb_tuner_next_k (mem_limit as in run_kFkB) and enqueues run_kFkB with that k.
+ * Returns the k used, or a negative error. */
+int run_kFkB_adaptive(int num_microbatches, size_t mem_limit);
 
 /* Milliseconds from the start of the last run_kFkB to the completion of its last op or
  * transfer, measured with HIP events on the library's streams.  Call after stage_sync. */

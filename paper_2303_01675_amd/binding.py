@@ -10,6 +10,8 @@ __all__ = [
     "GEMM_NN", "GEMM_NT", "GEMM_TN", "EPI_NONE", "EPI_BIAS", "EPI_BIAS_GELU", "EPI_BIAS_RES", "EPI_ACCUM",
     "EPI_GELU_BWD", "PARAM_ORDER", "param_shapes", "param_offsets", "pack_weights", "unpack_params",
     "kfkb_schedule", "kfkb_peak_live", "kfkb_activation_bytes_per_microbatch",
+    "kfkb_predict_iteration_ms", "kfkb_tuner_config", "kfkb_tuner_set_compute_profile", "kfkb_tuner_push_sample", "kfkb_tuner_next_k",
+    "stage_get_transfer_ms", "stage_tuner_calibrate", "run_kFkB_adaptive",
     "stage_config", "stage_init", "stage_param_count", "stage_activation_bytes", "stage_workspace_bytes",
     "stage_bind", "stage_set_delays", "stage_refresh_weights", "stage_forward", "stage_backward", "run_kFkB",
     "stage_last_k", "stage_side_streams_overlap", "stage_zero_grads", "stage_set_wgrad_stream", "stage_set_compute_lanes", "stage_sync", "stage_sync_timeout", "stage_destroy", "stage_get_order",
@@ -71,6 +73,14 @@ def load_library():
         "kfkb_schedule": (i, [i, i, i, C.POINTER(_Op), i]),
         "kfkb_peak_live": (i, [i, i, i]),
         "kfkb_activation_bytes_per_microbatch": (sz, [i, i, i, i, i, i, i]),
+        "kfkb_predict_iteration_ms": (C.c_double, [i, i, i] + [C.c_double] * 6 + [i, i]),
+        "kfkb_tuner_config": (i, [i, i, C.POINTER(C.c_int), i]),
+        "kfkb_tuner_set_compute_profile": (i, [i, C.c_double, C.c_double]),
+        "kfkb_tuner_push_sample": (i, [C.c_double] * 4),
+        "kfkb_tuner_next_k": (i, [i, i, sz, sz, C.POINTER(C.c_double), i]),
+        "stage_get_transfer_ms": (i, [i, C.POINTER(C.c_double), i]),
+        "stage_tuner_calibrate": (i, [i, i]),
+        "run_kFkB_adaptive": (i, [i, sz]),
         "stage_config": (i, [C.POINTER(_Config)]),
         "stage_init": (i, [vp, i, i, i, i]),
         "stage_param_count": (sz, []),
@@ -190,6 +200,49 @@ def kfkb_activation_bytes_per_microbatch(layers, micro_batch, seq, hidden, heads
 
 
 # ---- the stage -----------------------------------------------------------------------------------------
+
+def kfkb_predict_iteration_ms(k, num_microbatches, warmup_groups, t_fwd, t_bwd, t_recv_x, t_recv_dy, t_send_y, t_send_dx,
+                              x_slots=0, dy_slots=0):
+    t = load_library().kfkb_predict_iteration_ms(k, num_microbatches, warmup_groups, t_fwd, t_bwd, t_recv_x, t_recv_dy,
+                                                 t_send_y, t_send_dx, x_slots, dy_slots)
+    if t < 0:
+        _check(int(t))
+    return t
+
+
+def kfkb_tuner_config(window, interval, candidates):
+    arr = (C.c_int * len(candidates))(*candidates)
+    return _check(load_library().kfkb_tuner_config(window, interval, arr, len(candidates)))
+
+
+def kfkb_tuner_set_compute_profile(k, t_fwd, t_bwd):
+    return _check(load_library().kfkb_tuner_set_compute_profile(k, t_fwd, t_bwd))
+
+
+def kfkb_tuner_push_sample(t_recv_x, t_recv_dy, t_send_y, t_send_dx):
+    return _check(load_library().kfkb_tuner_push_sample(t_recv_x, t_recv_dy, t_send_y, t_send_dx))
+
+
+def kfkb_tuner_next_k(num_microbatches, warmup_groups=0, mem_limit=0, bytes_per_microbatch=0, num_candidates=8):
+    """(k, [estimate of every candidate at the last evaluation, -1 where skipped])"""
+    est = (C.c_double * num_candidates)(*([-1.0] * num_candidates))
+    k = _check(load_library().kfkb_tuner_next_k(num_microbatches, warmup_groups, mem_limit, bytes_per_microbatch, est, num_candidates))
+    return k, list(est)
+
+
+def stage_get_transfer_ms(direction, cap=4096):
+    buf = (C.c_double * cap)()
+    n = _check(load_library().stage_get_transfer_ms(direction, buf, cap))
+    return [buf[j] for j in range(n)]
+
+
+def stage_tuner_calibrate(num_microbatches, repeats=2):
+    return _check(load_library().stage_tuner_calibrate(num_microbatches, repeats))
+
+
+def run_kFkB_adaptive(num_microbatches, mem_limit=0):
+    return _check(load_library().run_kFkB_adaptive(num_microbatches, mem_limit))
+
 
 def stage_config(dtype=F32, micro_batch=1, mlp_ratio=4, causal=1, ln_eps=1e-5, num_stages=1, stage_index=0,
                  max_microbatches=1):

@@ -214,6 +214,8 @@ struct Stage {
   std::vector<hipEvent_t> ev_w;                            // per micro-batch: its last W step is done
   std::vector<hipEvent_t> stash_release;                   // per activation slot: last reader (or null)
   std::vector<hipEvent_t> ev_x, ev_dy, ev_f0, ev_f1, ev_b0, ev_b1, ev_ys, ev_dxs;
+  std::vector<hipEvent_t> ev_t0[4];                        // start of the transfer of each direction and micro-batch
+  bool adaptive_pending = false;                           // an iteration of run_kFkB_adaptive has not been observed yet
   hipEvent_t ev_epoch = nullptr, ev_run_end = nullptr;
   bool epoch_valid = false, run_timed = false;
   std::vector<int64_t> dl_x, dl_dy, dl_y, dl_dx;
@@ -487,6 +489,7 @@ int issue_recv(int op, int mbi) {
     const int slot = g.xs.take();
     if (slot < 0) return 1;
     if (g.xs.release[slot]) HIPCHK(hipStreamWaitEvent(g.sr, g.xs.release[slot], 0));
+    HIPCHK(hipEventRecord(g.ev_t0[0][mbi], g.sr));
     HIPCHK(launch_delay(g.dl_x[mbi], g.sr));
     HIPCHK(hipMemcpyAsync(g.xs.buf[slot], g.h_in + (size_t)mbi * bytes, bytes, hipMemcpyHostToDevice, g.sr));
     HIPCHK(hipEventRecord(g.ev_x[mbi], g.sr));
@@ -499,6 +502,7 @@ int issue_recv(int op, int mbi) {
   if (slot < 0) return 1;
   if (g.dys.release[slot]) HIPCHK(hipStreamWaitEvent(g.sr, g.dys.release[slot], 0));
   HIPCHK(hipStreamWaitEvent(g.sr, g.ev_ys[mbi], 0));
+  HIPCHK(hipEventRecord(g.ev_t0[1][mbi], g.sr));
   HIPCHK(launch_delay(g.dl_dy[mbi], g.sr));
   HIPCHK(hipMemcpyAsync(g.dys.buf[slot], g.h_up + (size_t)mbi * bytes, bytes, hipMemcpyHostToDevice, g.sr));
   HIPCHK(hipEventRecord(g.ev_dy[mbi], g.sr));
@@ -558,6 +562,7 @@ int end_forward(ActiveOp& a) {
   // send Y_mb as soon as the forward has delivered it
   const size_t bytes = g.n * g.esz;
   HIPCHK(hipStreamWaitEvent(g.ss, g.ev_f1[mbi], 0));
+  HIPCHK(hipEventRecord(g.ev_t0[2][mbi], g.ss));
   HIPCHK(launch_delay(g.dl_y[mbi], g.ss));
   HIPCHK(hipMemcpyAsync(g.h_out + (size_t)mbi * bytes, g.ys.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
   HIPCHK(hipEventRecord(g.ev_ys[mbi], g.ss));
@@ -607,6 +612,7 @@ int end_backward(ActiveOp& a) {
   }
   const size_t bytes = g.n * g.esz;
   HIPCHK(hipStreamWaitEvent(g.ss, g.ev_b1[mbi], 0));
+  HIPCHK(hipEventRecord(g.ev_t0[3][mbi], g.ss));
   HIPCHK(launch_delay(g.dl_dx[mbi], g.ss));
   HIPCHK(hipMemcpyAsync(g.h_ingrad + (size_t)mbi * bytes, g.dxs.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
   HIPCHK(hipEventRecord(g.ev_dxs[mbi], g.ss));
@@ -705,6 +711,73 @@ int pick_streams() {
   g_streams_picked = true;
   return 0;
 }
+
+
+// ---- cost model and tuner (host only) --------------------------------------------------------------
+// Discrete-event run of the engine's own transfer rules with constant op and transfer times.
+double predict_iteration(int k, int M, int w, double tf, double tb, const double (&tc)[4], int x_slots, int dy_slots) {
+  std::vector<kfkb_op_t> order, plan;
+  build_order(k, M, w, order);
+  build_receive_plan(order, plan);
+  const int live = peak_live_of(order);
+  constexpr double kBusy = -1.0;
+  std::vector<double> pool[2];
+  pool[0].assign(x_slots > 0 ? x_slots : live + k, 0.0);
+  pool[1].assign(dy_slots > 0 ? dy_slots : 2 * k, 0.0);
+  std::vector<double> arrive[2], sent_y(M, -1.0);
+  std::vector<int> slot[2];
+  for (int d = 0; d < 2; d++) { arrive[d].assign(M, -1.0); slot[d].assign(M, -1); }
+  double t_recv = 0.0, t_send = 0.0, t_comp = 0.0;
+  size_t rp = 0;
+  auto receives = [&]() {
+    while (rp < plan.size()) {
+      const int d = plan[rp].op == KFKB_OP_F ? 0 : 1, mb = plan[rp].mb;
+      if (d == 1 && sent_y[mb] < 0.0) return;          // the echo: dY follows the arrival of Y
+      int best = -1;
+      for (size_t i = 0; i < pool[d].size(); i++)
+        if (pool[d][i] != kBusy && (best < 0 || pool[d][i] < pool[d][best])) best = (int)i;
+      if (best < 0) return;
+      double begin = std::max(t_recv, pool[d][best]);
+      if (d == 1) begin = std::max(begin, sent_y[mb]);
+      pool[d][best] = kBusy;
+      t_recv = begin + tc[d];
+      arrive[d][mb] = t_recv;
+      slot[d][mb] = best;
+      rp++;
+    }
+  };
+  for (const auto& op : order) {
+    receives();
+    const int d = op.op == KFKB_OP_F ? 0 : 1;
+    if (arrive[d][op.mb] < 0.0) return -1.0;            // the receive plan cannot feed this op
+    t_comp = std::max(t_comp, arrive[d][op.mb]) + (d == 0 ? tf : tb);
+    t_send = std::max(t_send, t_comp) + tc[2 + d];
+    if (d == 0) {
+      sent_y[op.mb] = t_send;
+    } else {
+      pool[0][slot[0][op.mb]] = t_comp;
+      pool[1][slot[1][op.mb]] = t_comp;
+    }
+  }
+  return std::max(t_comp, std::max(t_send, t_recv));
+}
+
+struct TunerState {
+  int window = 4, interval = 4;
+  std::vector<int> candidates{1};
+  std::vector<double> tf, tb;                         // per candidate; < 0: not profiled
+  std::vector<double> samples[4];                     // last `window` samples per direction
+  std::vector<double> estimates;
+  long iterations = 0;
+  int k = 1;
+  double mean(int d) const {
+    if (samples[d].empty()) return 0.0;
+    double s = 0.0;
+    for (double v : samples[d]) s += v;
+    return s / (double)samples[d].size();
+  }
+};
+TunerState g_tuner;
 
 int make_events(std::vector<hipEvent_t>& v, int n) {
   v.resize(n);
@@ -808,6 +881,7 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   TRY(make_events(g.ev_f0, g.Mmax)); TRY(make_events(g.ev_f1, g.Mmax));
   TRY(make_events(g.ev_b0, g.Mmax)); TRY(make_events(g.ev_b1, g.Mmax));
   TRY(make_events(g.ev_ys, g.Mmax)); TRY(make_events(g.ev_dxs, g.Mmax));
+  for (auto& v : g.ev_t0) TRY(make_events(v, g.Mmax));
   HIPCHK(hipEventCreate(&g.ev_epoch));
   HIPCHK(hipEventCreate(&g.ev_run_end));
   g.inited = true;
@@ -982,6 +1056,160 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
   return 0;
 }
 
+
+double kfkb_predict_iteration_ms(int k, int num_microbatches, int warmup_groups, double t_fwd, double t_bwd,
+                                 double t_recv_x, double t_recv_dy, double t_send_y, double t_send_dx,
+                                 int x_slots, int dy_slots) {
+  const int M = num_microbatches;
+  if (M < 1 || k < 1 || k > M || warmup_groups < 0 || t_fwd < 0 || t_bwd < 0 || t_recv_x < 0 || t_recv_dy < 0 ||
+      t_send_y < 0 || t_send_dx < 0 || x_slots < 0 || dy_slots < 0)
+    return (double)fail(KFKB_E_ARG, "kfkb_predict_iteration_ms: need 1 <= k <= M, w >= 0 and non-negative times");
+  const double tc[4] = {t_recv_x, t_recv_dy, t_send_y, t_send_dx};
+  const double t = predict_iteration(k, M, warmup_groups, t_fwd, t_bwd, tc, x_slots, dy_slots);
+  if (t < 0.0) return (double)fail(KFKB_E_STATE, "kfkb_predict_iteration_ms: the slot pools cannot feed plan k=%d", k);
+  return t;
+}
+
+int kfkb_tuner_config(int window, int interval, const int* candidates, int num_candidates) {
+  if (window < 1 || interval < 1 || candidates == nullptr || num_candidates < 1 || num_candidates > 8)
+    return fail(KFKB_E_ARG, "kfkb_tuner_config: window, interval >= 1 and 1..8 candidates");
+  std::vector<int> c(candidates, candidates + num_candidates);
+  std::sort(c.begin(), c.end());
+  if (c.front() < 1 || std::adjacent_find(c.begin(), c.end()) != c.end())
+    return fail(KFKB_E_ARG, "kfkb_tuner_config: candidates must be distinct and positive");
+  g_tuner = TunerState{};
+  g_tuner.window = window; g_tuner.interval = interval; g_tuner.candidates = c;
+  g_tuner.tf.assign(c.size(), -1.0); g_tuner.tb.assign(c.size(), -1.0);
+  g_tuner.estimates.assign(c.size(), -1.0);
+  g_tuner.k = c.front();
+  return 0;
+}
+
+int kfkb_tuner_set_compute_profile(int k, double t_fwd, double t_bwd) {
+  if (t_fwd < 0 || t_bwd < 0) return fail(KFKB_E_ARG, "kfkb_tuner_set_compute_profile: negative time");
+  for (size_t i = 0; i < g_tuner.candidates.size(); i++)
+    if (g_tuner.candidates[i] == k) { g_tuner.tf[i] = t_fwd; g_tuner.tb[i] = t_bwd; return 0; }
+  return fail(KFKB_E_ARG, "kfkb_tuner_set_compute_profile: k = %d is not a candidate", k);
+}
+
+int kfkb_tuner_push_sample(double t_recv_x, double t_recv_dy, double t_send_y, double t_send_dx) {
+  const double v[4] = {t_recv_x, t_recv_dy, t_send_y, t_send_dx};
+  for (int d = 0; d < 4; d++) {
+    if (v[d] < 0) return fail(KFKB_E_ARG, "kfkb_tuner_push_sample: negative time");
+    g_tuner.samples[d].push_back(v[d]);
+    if ((int)g_tuner.samples[d].size() > g_tuner.window) g_tuner.samples[d].erase(g_tuner.samples[d].begin());
+  }
+  g_tuner.iterations++;
+  return 0;
+}
+
+int kfkb_tuner_next_k(int num_microbatches, int warmup_groups, size_t mem_limit, size_t bytes_per_microbatch,
+                      double* estimates, int cap) {
+  const int M = num_microbatches;
+  if (M < 1 || warmup_groups < 0) return fail(KFKB_E_ARG, "kfkb_tuner_next_k: need M >= 1 and w >= 0");
+  TunerState& t = g_tuner;
+  if (t.iterations > 0 && t.iterations % t.interval == 0) {
+    const double tc[4] = {t.mean(0), t.mean(1), t.mean(2), t.mean(3)};
+    int best = -1;
+    for (size_t i = 0; i < t.candidates.size(); i++) {
+      const int k = t.candidates[i];
+      t.estimates[i] = -1.0;
+      if (k > M || t.tf[i] < 0.0) continue;
+      const int G = (M + k - 1) / k;
+      const size_t live = (size_t)std::min((std::min(warmup_groups, G) + 1) * k, M);
+      if (mem_limit != 0 && live * bytes_per_microbatch > mem_limit) continue;
+      t.estimates[i] = predict_iteration(k, M, warmup_groups, t.tf[i], t.tb[i], tc, 0, 0);
+      if (t.estimates[i] >= 0.0 && (best < 0 || t.estimates[i] < t.estimates[best])) best = (int)i;
+    }
+    if (best < 0) return fail(KFKB_E_MEMLIMIT, "kfkb_tuner_next_k: no admissible candidate");
+    t.k = t.candidates[best];
+  }
+  if (estimates != nullptr)
+    for (int i = 0; i < cap && i < (int)t.estimates.size(); i++) estimates[i] = t.estimates[i];
+  return t.k;
+}
+
+int stage_get_transfer_ms(int direction, double* out, int cap) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_get_transfer_ms before stage_init");
+  if (direction < 0 || direction > 3 || (out == nullptr && cap > 0)) return fail(KFKB_E_ARG, "stage_get_transfer_ms: direction 0..3");
+  const std::vector<hipEvent_t>* t1[4] = {&g.ev_x, &g.ev_dy, &g.ev_ys, &g.ev_dxs};
+  int n = 0;
+  for (int mb = 0; mb < g.Mmax && n < cap; mb++) {
+    const MbState& st = g.mb[mb];
+    const bool done = direction == 0 ? st.x_issued : direction == 1 ? st.dy_issued : direction == 2 ? st.fwd_done : st.bwd_done;
+    if (!done) break;
+    float ms = 0.f;
+    HIPCHK(hipEventElapsedTime(&ms, g.ev_t0[direction][mb], (*t1[direction])[mb]));
+    out[n++] = (double)ms;
+  }
+  return n;
+}
+
+// mean transfer time per direction of the last iteration -> the tuner's windows
+static int tuner_observe_last() {
+  TRY(stage_sync());
+  double mean[4];
+  std::vector<double> buf(g.Mmax);
+  for (int d = 0; d < 4; d++) {
+    const int n = stage_get_transfer_ms(d, buf.data(), g.Mmax);
+    if (n < 0) return n;
+    if (n == 0) return fail(KFKB_E_STATE, "tuner: the last iteration has no transfers to observe");
+    double s = 0.0;
+    for (int i = 0; i < n; i++) s += buf[i];
+    mean[d] = s / n;
+  }
+  return kfkb_tuner_push_sample(mean[0], mean[1], mean[2], mean[3]);
+}
+
+int stage_tuner_calibrate(int num_microbatches, int repeats) {
+  if (!g.bound) return fail(KFKB_E_STATE, "stage_tuner_calibrate before stage_bind");
+  const int M = num_microbatches;
+  if (M < 1 || M > g.Mmax || repeats < 1) return fail(KFKB_E_ARG, "stage_tuner_calibrate: need 1 <= M <= %d and repeats >= 1", g.Mmax);
+  if (live_count() != 0) return fail(KFKB_E_STATE, "stage_tuner_calibrate while micro-batches are live");
+  const auto dx = g.dl_x, ddy = g.dl_dy, dy = g.dl_y, ddx = g.dl_dx;
+  auto restore = [&]() { g.dl_x = dx; g.dl_dy = ddy; g.dl_y = dy; g.dl_dx = ddx; };
+  for (auto* v : {&g.dl_x, &g.dl_dy, &g.dl_y, &g.dl_dx}) std::fill(v->begin(), v->end(), 0);
+  std::vector<kfkb_op_t> log(2 * (size_t)M);
+  for (size_t i = 0; i < g_tuner.candidates.size(); i++) {
+    const int k = g_tuner.candidates[i];
+    if (k > M || k > g.k_bound) continue;
+    double sf = 0.0, sb = 0.0, total = 0.0;
+    int rc = run_kFkB(k, M, 0);                       // warm-up of this plan
+    if (rc == 0) rc = stage_sync();
+    for (int r = 0; rc == 0 && r < repeats; r++) {
+      rc = run_kFkB(k, M, 0);
+      if (rc == 0) rc = stage_sync();
+      if (rc != 0) break;
+      const int n = stage_get_order(log.data(), (int)log.size());
+      if (n < 0) { rc = n; break; }
+      for (int j = 0; j < n; j++) (log[j].op == KFKB_OP_F ? sf : sb) += log[j].t_end_ms - log[j].t_start_ms;
+      total += stage_last_run_ms();
+    }
+    if (rc != 0) { restore(); return rc; }
+    const double tf = sf / ((double)repeats * M), tb = sb / ((double)repeats * M);
+    // ops of two lanes overlap: scale the op times so that M of each add up to the measured iteration
+    const double scale = (tf + tb) > 0.0 ? (total / repeats) / (M * (tf + tb)) : 1.0;
+    g_tuner.tf[i] = tf * scale; g_tuner.tb[i] = tb * scale;
+  }
+  restore();
+  g.adaptive_pending = false;
+  return 0;
+}
+
+int run_kFkB_adaptive(int num_microbatches, size_t mem_limit) {
+  if (!g.bound) return fail(KFKB_E_STATE, "run_kFkB_adaptive before stage_bind");
+  if (g.adaptive_pending) TRY(tuner_observe_last());
+  const int w = 0;                                    // evaluated with each plan's own warm-up depth below
+  (void)w;
+  const size_t per_mb = kfkb_activation_bytes_per_microbatch(g.L, g.b, g.T, g.H, g.heads, g.F, (int)g.esz);
+  const int S = std::max(1, g.cfg.num_stages);
+  const int k = kfkb_tuner_next_k(num_microbatches, std::max(0, S - 1 - g.cfg.stage_index), mem_limit, per_mb, nullptr, 0);
+  if (k < 0) return k;
+  TRY(run_kFkB(k, num_microbatches, mem_limit));
+  g.adaptive_pending = true;
+  return k;
+}
+
 int stage_last_k(void) { return g.last_k; }
 
 int stage_side_streams_overlap(void) {
@@ -1085,7 +1313,7 @@ int stage_destroy(void) {
   for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) hipStreamSynchronize(q);
   if (g.sw != nullptr) { hipStreamSynchronize(g.sw); hipStreamDestroy(g.sw); }
   hipEventDestroy(g.ev_sw_tail);
-  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w, &g.ev_g})
+  for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w, &g.ev_g, &g.ev_t0[0], &g.ev_t0[1], &g.ev_t0[2], &g.ev_t0[3]})
     for (auto e : *v) hipEventDestroy(e);
   for (auto& ln : g.lane) {
     for (int i = 0; i < Stage::kRing; i++) { hipEventDestroy(ln.ev_chain[i]); hipEventDestroy(ln.ev_wdone[i]); }
