@@ -117,6 +117,35 @@ def largest_admissible_k(M, w, mem_limit, per_mb_bytes):
     return best
 
 
+def enumerate_candidates(global_batch, mem_limit, bytes_per_sample, num_stages=1, stage_index=0, k_max=None):
+    """Candidate plans (k, b) on the memory-limit curve at a fixed global batch (Section 4.2, "Pruning for
+    Candidate Set": walk the group size k upward from 1 and, for each, greedily take the LARGEST micro-batch
+    size b the device accepts; combinations under the curve waste memory, those above it do not fit).
+    Readings: b must divide the global batch (M = global_batch / b micro-batches, M >= k); a plan's need is
+    its peak of live micro-batches times b times the bytes one sample keeps (activation memory is linear in b);
+    the walk stops at the first k for which even b = 1 does not fit, or at k_max.
+    Returns [(k, b), ...] in ascending k."""
+    out = []
+    k = 1
+    while k <= global_batch and (k_max is None or k <= k_max):
+        best = 0
+        for b in range(global_batch, 0, -1):
+            if global_batch % b:
+                continue
+            M = global_batch // b
+            if M < k:
+                continue
+            w = warmup_groups(num_stages, stage_index, k, M)
+            if peak_live(kfkb_order(k, M, w)) * b * bytes_per_sample <= mem_limit:
+                best = b
+                break
+        if best == 0:
+            break
+        out.append((k, best))
+        k += 1
+    return out
+
+
 def run_iteration(order, blocks, xs, dys, heads, causal=True, eps=1e-5):
     """Execute a plan: forwards stash their caches, backwards consume them and add their
     parameter gradients into the accumulator in the order they run (Section 2.4: gradient

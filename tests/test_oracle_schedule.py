@@ -124,3 +124,34 @@ def test_iteration_rejects_bad_orders(tiny):
         sch.kfkb_order(0, 4)
     with pytest.raises(ValueError):
         sch.kfkb_order(5, 4)
+
+
+def test_candidates_on_the_memory_limit_curve():
+    """Section 4.2 (pruning) and the granularity test of Section 6.3.1: global batch 192, k = 1..6 run with
+    micro-batch size 6 // k, i.e. a device that holds six samples per warm-up group."""
+    for S, s in ((1, 0), (8, 0), (8, 5)):
+        w = S - 1 - s
+        got = sch.enumerate_candidates(192, (w + 1) * 6 * 10, 10, S, s, k_max=6)
+        assert got == [(k, 6 // k) for k in range(1, 7)]
+    # brute force on small cases: every candidate fits, the next larger divisor does not, nothing after the
+    # walk's end fits with b = 1
+    for G in (12, 16, 30):
+        for limit in (35, 80, 240, 10 ** 6):
+            for S, s in ((1, 0), (4, 0), (4, 2)):
+                cand = sch.enumerate_candidates(G, limit, 10, S, s)
+
+                def need(k, b):
+                    M = G // b
+                    return sch.peak_live(sch.kfkb_order(k, M, sch.warmup_groups(S, s, k, M))) * b * 10
+                ks = [k for k, _ in cand]
+                assert ks == list(range(1, len(cand) + 1))
+                for k, b in cand:
+                    assert G % b == 0 and G // b >= k and need(k, b) <= limit
+                    bigger = [bb for bb in range(b + 1, G + 1) if G % bb == 0 and G // bb >= k]
+                    assert all(need(k, bb) > limit for bb in bigger)
+                k_next = len(cand) + 1
+                if k_next <= G:
+                    assert need(k_next, 1) > limit
+    # no limit worth the name: k = 1 takes the whole batch as one micro-batch, k = 2 halves it, ...
+    assert sch.enumerate_candidates(12, 10 ** 9, 10)[:4] == [(1, 12), (2, 6), (3, 4), (4, 3)]
+    assert sch.enumerate_candidates(12, 5, 10) == []
