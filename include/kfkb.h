@@ -81,6 +81,14 @@ int kfkb_peak_live(int k, int num_microbatches, int warmup_groups);
 size_t kfkb_activation_bytes_per_microbatch(int layers, int micro_batch, int seq, int hidden, int heads,
                                             int mlp_width, int elem_bytes);
 
+/* Candidate plans (k, b) on the memory-limit curve at a fixed global batch (paper Section 4.2, pruning of the
+ * candidate set): for k = 1, 2, ... the LARGEST micro-batch size b that divides global_batch, leaves at least k
+ * micro-batches and whose plan fits: peak live micro-batches (stage position as in kfkb_config_t) x b x
+ * bytes_per_sample <= mem_limit.  Stops at the first k for which b = 1 does not fit, or after k_max (0 = none).
+ * Writes out_k[i], out_b[i] for up to cap candidates; returns their number. */
+int kfkb_enumerate_candidates(int global_batch, size_t mem_limit, size_t bytes_per_sample, int num_stages,
+                              int stage_index, int k_max, int* out_k, int* out_b, int cap);
+
 /* ---- cost model and online choice of k (paper Sections 3.3 "auto tunner", 5.2, 5.4) -------------- *
  * The pipeline length of a candidate plan is estimated from stage computation times, profiled once *
  * per plan, and from communication times measured end to end and averaged over a moving window;    *

@@ -10,7 +10,7 @@ __all__ = [
     "GEMM_NN", "GEMM_NT", "GEMM_TN", "EPI_NONE", "EPI_BIAS", "EPI_BIAS_GELU", "EPI_BIAS_RES", "EPI_ACCUM",
     "EPI_GELU_BWD", "PARAM_ORDER", "param_shapes", "param_offsets", "pack_weights", "unpack_params",
     "kfkb_schedule", "kfkb_peak_live", "kfkb_activation_bytes_per_microbatch",
-    "kfkb_predict_iteration_ms", "kfkb_tuner_config", "kfkb_tuner_set_compute_profile", "kfkb_tuner_push_sample", "kfkb_tuner_next_k",
+    "kfkb_enumerate_candidates", "kfkb_predict_iteration_ms", "kfkb_tuner_config", "kfkb_tuner_set_compute_profile", "kfkb_tuner_push_sample", "kfkb_tuner_next_k",
     "stage_get_transfer_ms", "stage_tuner_calibrate", "run_kFkB_adaptive",
     "stage_config", "stage_init", "stage_param_count", "stage_activation_bytes", "stage_workspace_bytes",
     "stage_bind", "stage_set_delays", "stage_refresh_weights", "stage_forward", "stage_backward", "run_kFkB",
@@ -73,6 +73,7 @@ def load_library():
         "kfkb_schedule": (i, [i, i, i, C.POINTER(_Op), i]),
         "kfkb_peak_live": (i, [i, i, i]),
         "kfkb_activation_bytes_per_microbatch": (sz, [i, i, i, i, i, i, i]),
+        "kfkb_enumerate_candidates": (i, [i, sz, sz, i, i, i, C.POINTER(C.c_int), C.POINTER(C.c_int), i]),
         "kfkb_predict_iteration_ms": (C.c_double, [i, i, i] + [C.c_double] * 6 + [i, i]),
         "kfkb_tuner_config": (i, [i, i, C.POINTER(C.c_int), i]),
         "kfkb_tuner_set_compute_profile": (i, [i, C.c_double, C.c_double]),
@@ -200,6 +201,13 @@ def kfkb_activation_bytes_per_microbatch(layers, micro_batch, seq, hidden, heads
 
 
 # ---- the stage -----------------------------------------------------------------------------------------
+
+def kfkb_enumerate_candidates(global_batch, mem_limit, bytes_per_sample, num_stages=1, stage_index=0, k_max=0, cap=4096):
+    ks, bs = (C.c_int * cap)(), (C.c_int * cap)()
+    n = _check(load_library().kfkb_enumerate_candidates(global_batch, mem_limit, bytes_per_sample, num_stages, stage_index,
+                                                        k_max, ks, bs, cap))
+    return [(ks[j], bs[j]) for j in range(n)]
+
 
 def kfkb_predict_iteration_ms(k, num_microbatches, warmup_groups, t_fwd, t_bwd, t_recv_x, t_recv_dy, t_send_y, t_send_dx,
                               x_slots=0, dy_slots=0):

@@ -1057,6 +1057,31 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
 }
 
 
+int kfkb_enumerate_candidates(int global_batch, size_t mem_limit, size_t bytes_per_sample, int num_stages,
+                              int stage_index, int k_max, int* out_k, int* out_b, int cap) {
+  if (global_batch < 1 || num_stages < 1 || stage_index < 0 || stage_index >= num_stages || k_max < 0 || cap < 0 ||
+      (cap > 0 && (out_k == nullptr || out_b == nullptr)))
+    return fail(KFKB_E_ARG, "kfkb_enumerate_candidates: bad argument");
+  int n = 0;
+  for (int k = 1; k <= global_batch && (k_max == 0 || k <= k_max); k++) {
+    int best = 0;
+    for (int b = global_batch; b >= 1 && best == 0; b--) {
+      if (global_batch % b != 0) continue;
+      const int M = global_batch / b;
+      if (M < k) continue;
+      const int G = (M + k - 1) / k;
+      const int w = std::min(num_stages - 1 - stage_index, G);
+      const size_t live = (size_t)std::min((w + 1) * k, M);
+      // live * b * bytes_per_sample <= mem_limit without overflow
+      if (bytes_per_sample == 0 || live * (size_t)b <= mem_limit / bytes_per_sample) best = b;
+    }
+    if (best == 0) break;
+    if (n < cap) { out_k[n] = k; out_b[n] = best; }
+    n++;
+  }
+  return std::min(n, cap);
+}
+
 double kfkb_predict_iteration_ms(int k, int num_microbatches, int warmup_groups, double t_fwd, double t_bwd,
                                  double t_recv_x, double t_recv_dy, double t_send_y, double t_send_dx,
                                  int x_slots, int dy_slots) {

@@ -99,3 +99,17 @@ def test_tuner_argument_errors(lib):
     kf.kfkb_tuner_push_sample(0, 0, 0, 0); kf.kfkb_tuner_push_sample(0, 0, 0, 0)
     with pytest.raises(kf.KfkbError):
         kf.kfkb_tuner_next_k(8)
+
+
+def test_candidate_enumeration_matches_the_oracle(lib):
+    rnd = random.Random(5)
+    assert kf.kfkb_enumerate_candidates(192, 6 * 10, 10, k_max=6) == [(k, 6 // k) for k in range(1, 7)]   # paper, Section 6.3.1
+    for _ in range(200):
+        G = rnd.choice([6, 12, 16, 30, 64, 192])
+        S = rnd.randint(1, 6); s = rnd.randint(0, S - 1)
+        per = rnd.choice([1, 10, 1000])
+        limit = per * rnd.randint(0, 3 * G)
+        kmax = rnd.choice([0, 0, rnd.randint(1, 8)])
+        assert kf.kfkb_enumerate_candidates(G, limit, per, S, s, kmax) == sch.enumerate_candidates(G, limit, per, S, s, kmax or None)
+    with pytest.raises(kf.KfkbError):
+        kf.kfkb_enumerate_candidates(0, 10, 1)
