@@ -269,6 +269,16 @@ enum { KFKB_EPI_NONE = 0,       /* C = acc                                      
 int kfkb_op_gemm(int dtype, int kind, int epilogue, int M, int N, int K, const void* A, const void* B,
                  const void* bias, const void* residual, void* C, void* C2, float* Cacc, void* stream);
 
+/* The layout the stage keeps its bf16 weight copies in, and the NT product that reads it (bf16 only).
+ * kfkb_op_tile_weights: dst[kc][n][kk] = B[n][32 kc + kk], kc < K / 32, kk < 32, where B[N, K] is src itself
+ * (transposed == 0) or the transpose of src[K, N] (transposed != 0); N % 8 == 0, K % 32 == 0; src and dst are
+ * distinct device buffers of N * K bf16 values.
+ * kfkb_op_gemm_nt_tiled: kfkb_op_gemm(KFKB_BF16, KFKB_GEMM_NT, ...) with B given in that layout (Bt);
+ * N % 128 == 0, K % 64 == 0, any M.  Both enqueue only; a bad argument returns KFKB_E_ARG and launches nothing. */
+int kfkb_op_tile_weights(const void* src, void* dst, int N, int K, int transposed, void* stream);
+int kfkb_op_gemm_nt_tiled(int epilogue, int M, int N, int K, const void* A, const void* Bt, const void* bias,
+                          const void* residual, void* C, void* C2, float* Cacc, void* stream);
+
 /* y = LN(x) over H per row; mean, rstd: fp32 [rows]. */
 int kfkb_op_layernorm_fwd(int dtype, const void* x, const void* gamma, const void* beta, void* y,
                           float* mean, float* rstd, int rows, int H, float eps, void* stream);

@@ -16,7 +16,7 @@ __all__ = [
     "stage_bind", "stage_set_delays", "stage_refresh_weights", "stage_forward", "stage_backward", "run_kFkB",
     "stage_last_k", "stage_side_streams_overlap", "stage_zero_grads", "stage_set_wgrad_stream", "stage_set_compute_lanes", "stage_sync", "stage_sync_timeout", "stage_destroy", "stage_get_order",
     "stage_last_run_ms", "StageBuffers", "kfkb_profile", "kfkb_profile_report",
-    "kfkb_op_gemm", "kfkb_op_layernorm_fwd", "kfkb_op_layernorm_bwd", "kfkb_op_colsum_accum",
+    "kfkb_op_gemm", "kfkb_op_tile_weights", "kfkb_op_gemm_nt_tiled", "kfkb_op_layernorm_fwd", "kfkb_op_layernorm_bwd", "kfkb_op_colsum_accum",
     "kfkb_op_reduce_scratch_floats", "kfkb_op_gelu_bwd", "kfkb_op_attention_fwd", "kfkb_op_attention_bwd",
     "kfkb_op_transpose", "kfkb_op_delay",
 ]
@@ -106,6 +106,8 @@ def load_library():
         "kfkb_profile": (i, [i]),
         "kfkb_profile_report": (i, [C.POINTER(_KernelStat), i]),
         "kfkb_op_gemm": (i, [i, i, i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]),
+        "kfkb_op_tile_weights": (i, [vp, vp, i, i, i, vp]),
+        "kfkb_op_gemm_nt_tiled": (i, [i, i, i, i, vp, vp, vp, vp, vp, vp, vp, vp]),
         "kfkb_op_layernorm_fwd": (i, [i, vp, vp, vp, vp, vp, vp, i, i, C.c_float, vp]),
         "kfkb_op_layernorm_bwd": (i, [i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, vp]),
         "kfkb_op_colsum_accum": (i, [i, vp, vp, vp, i, i, vp]),
@@ -417,6 +419,15 @@ class StageBuffers:
 def kfkb_op_gemm(dtype, kind, epilogue, M, N, K, A, B, bias=None, residual=None, Cout=None, C2=None, Cacc=None, stream=None):
     return _check(load_library().kfkb_op_gemm(dtype, kind, epilogue, M, N, K, _ptr(A), _ptr(B), _ptr(bias), _ptr(residual),
                                               _ptr(Cout), _ptr(C2), _ptr(Cacc), _stream(stream)))
+
+
+def kfkb_op_tile_weights(src, dst, N, K, transposed, stream=None):
+    return _check(load_library().kfkb_op_tile_weights(_ptr(src), _ptr(dst), N, K, int(bool(transposed)), _stream(stream)))
+
+
+def kfkb_op_gemm_nt_tiled(epilogue, M, N, K, A, Bt, bias=None, residual=None, Cout=None, C2=None, Cacc=None, stream=None):
+    return _check(load_library().kfkb_op_gemm_nt_tiled(epilogue, M, N, K, _ptr(A), _ptr(Bt), _ptr(bias), _ptr(residual),
+                                                       _ptr(Cout), _ptr(C2), _ptr(Cacc), _stream(stream)))
 
 
 def kfkb_op_layernorm_fwd(dtype, x, gamma, beta, y, mean, rstd, rows, H, eps, stream=None):

@@ -1405,6 +1405,31 @@ int kfkb_op_gemm(int dtype, int kind, int epilogue, int M, int N, int K, const v
   return 0;
 }
 
+int kfkb_op_tile_weights(const void* src, void* dst, int N, int K, int transposed, void* stream) {
+  if (!src || !dst || N <= 0 || K <= 0 || N % 8 != 0 || K % 32 != 0)
+    return fail(KFKB_E_ARG, "kfkb_op_tile_weights: need N %% 8 == 0, K %% 32 == 0 and non-null pointers (N=%d K=%d)", N, K);
+  HIPCHK(launch_tile_weights(src, dst, N, K, transposed != 0, (hipStream_t)stream));
+  return 0;
+}
+
+int kfkb_op_gemm_nt_tiled(int epilogue, int M, int N, int K, const void* A, const void* Bt, const void* bias,
+                          const void* residual, void* C, void* C2, float* Cacc, void* stream) {
+  if (epilogue < KFKB_EPI_NONE || epilogue > KFKB_EPI_GELU_BWD) return fail(KFKB_E_ARG, "kfkb_op_gemm_nt_tiled: bad epilogue");
+  if (M < 0 || N < 0 || K < 0 || !A || !Bt) return fail(KFKB_E_ARG, "kfkb_op_gemm_nt_tiled: bad shape or null operand");
+  const bool need_bias = epilogue == KFKB_EPI_BIAS || epilogue == KFKB_EPI_BIAS_GELU || epilogue == KFKB_EPI_BIAS_RES;
+  const bool need_res = epilogue == KFKB_EPI_BIAS_RES || epilogue == KFKB_EPI_GELU_BWD;
+  if ((need_bias && !bias) || (need_res && !residual) || (epilogue == KFKB_EPI_BIAS_GELU && !C2) ||
+      (epilogue == KFKB_EPI_ACCUM ? !Cacc : !C))
+    return fail(KFKB_E_ARG, "kfkb_op_gemm_nt_tiled: epilogue %d misses an operand", epilogue);
+  if (M == 0 || N == 0) return 0;
+  GemmArgs a{KFKB_GEMM_NT, epilogue, M, N, K, A, Bt, bias, residual, C, C2, Cacc};
+  a.b_tiled = true;
+  const char* why = gemm_bf16_check(a);
+  if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
+  HIPCHK(launch_gemm_bf16(a, (hipStream_t)stream));
+  return 0;
+}
+
 static int check_rows(const char* who, int dtype, int rows, int H) {
   if (rows < 0 || H < 8 || H % 8 != 0 || H > 8192 * 4) return fail(KFKB_E_ARG, "%s: need rows >= 0 and width %% 8 == 0 (rows=%d width=%d)", who, rows, H);
   (void)dtype;

@@ -27,6 +27,7 @@
 #include "common.h"
 #include "../../include/kfkb.h"
 #include <algorithm>
+#include <type_traits>
 #include <cstdlib>
 
 namespace kfkb {
@@ -118,43 +119,38 @@ template <int N> __device__ __forceinline__ void wait_vmcnt() {
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // ------------------------------------------------------------------------------------------------
-// The main loop shared by the NT and TN kernels.  LAYOUT supplies the DMA source offsets and the fragment reads.
-//   chunk kc lives in ring slot kc % 4.  One chunk = two 16-deep k-steps; a k-step = TN groups of TM MFMAs.
-//   Every group carries one DMA instruction (B part of chunk kc+3 during k-step 0, A part of chunk kc+4 during
-//   k-step 1) and up to PER fragment reads of the next k-step.  A load that writes LDS keeps its wave from
+// The main loop shared by the NT and TN kernels.  LAYOUT owns the LDS rings, the DMA source offsets and the
+// fragment reads; the loop owns the order of instructions.
+//   One chunk = 32 reduction steps = two 16-deep k-steps; a k-step = TN groups of TM MFMAs.  Every group carries
+//   one DMA instruction (dma0 during k-step 0, dma1 during k-step 1: the layout decides which piece of which later
+//   chunk that is) and up to PER fragment reads of the next k-step.  A load that writes LDS keeps its wave from
 //   issuing anything else for about 32 clocks (measured: one wave alone moves 31 bytes per clock), which is the
 //   time one MFMA occupies the matrix pipe: in the 256 x 256 tiles every MFMA is therefore followed by exactly one
 //   memory instruction, pinned there, and the pipe never waits for the issue port.
-//   Between the k-steps every wave waits for its own loads of chunk kc+1 and all waves meet: after that chunk
-//   kc+1 is complete in LDS and slot kc % 4 is free.
+//   Between the k-steps every wave waits until at most WAIT_MID of its own loads are in flight (the layout's
+//   issue order makes that "chunk kc+1 has landed") and all waves meet: after that chunk kc+1 is complete in LDS
+//   and the ring slots that only chunk kc's first k-step still needed may be overwritten.
+//   The position pc of a chunk inside the layout's period (the least common multiple of its ring lengths) is a
+//   compile-time constant, so every LDS offset is an immediate.
 // ------------------------------------------------------------------------------------------------
 template <int TM, int TN, typename L>
 __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk) {
-  constexpr int LPC = 2 * TN;
   bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
-#pragma unroll
-  for (int c = 0; c < RING; c++) {
-#pragma unroll
-    for (int i = 0; i < TN; i++) lay.dma_a(i, c, c);
-    if (c < RING - 1) {
-#pragma unroll
-      for (int i = 0; i < TN; i++) lay.dma_b(i, c, c);
-    }
-  }
-  wait_vmcnt<2 * LPC + TN>();
+  lay.prologue();
+  wait_vmcnt<L::WAIT_PRO>();
   __syncthreads();
 #pragma unroll
   for (int j = 0; j < TN; j++) fb0[j] = lay.rd_b(0, 0, j);
 #pragma unroll
   for (int i = 0; i < TM; i++) fa0[i] = lay.rd_a(0, 0, i);
 
-  auto step = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], bf16x8 (&na)[TM], bf16x8 (&nb)[TN], int nslot, int nks, auto&& dma) {
+  auto step = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], bf16x8 (&na)[TM], bf16x8 (&nb)[TN], int npc, int nks, auto&& dma) {
     constexpr int NR = TM + TN;
     constexpr int PER = (NR + TN - 2) / (TN - 1);      // reads per group so that the last group has none
     auto rd = [&](int r) {
-      if (r == 0) nb[0] = lay.rd_b(nslot, nks, 0);
-      else if (r <= TM) na[r - 1] = lay.rd_a(nslot, nks, r - 1);
-      else nb[r - TM] = lay.rd_b(nslot, nks, r - TM);
+      if (r == 0) nb[0] = lay.rd_b(npc, nks, 0);
+      else if (r <= TM) na[r - 1] = lay.rd_a(npc, nks, r - 1);
+      else nb[r - TM] = lay.rd_b(npc, nks, r - TM);
     };
 #pragma unroll
     for (int j = 0; j < TN; j++) {
@@ -179,20 +175,20 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
       }
     }
   };
-  auto chunk = [&](int kc, int slot) {
-    step(fa0, fb0, fa1, fb1, slot, 1, [&](int j) { lay.dma_b(j, kc + 3, (slot + 3) & 3); });
-    wait_vmcnt<2 * LPC>();
+  auto chunk = [&](int kc, int pc) {
+    step(fa0, fb0, fa1, fb1, pc, 1, [&](int j) { lay.dma0(j, kc, pc); });
+    wait_vmcnt<L::WAIT_MID>();
     wait_lgkm0();
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
-    step(fa1, fb1, fa0, fb0, (slot + 1) & 3, 0, [&](int j) { lay.dma_a(j, kc + 4, slot); });
+    step(fa1, fb1, fa0, fb0, (pc + 1) % L::PERIOD, 0, [&](int j) { lay.dma1(j, kc, pc); });
   };
-  int kc = 0;
-  for (; kc + RING <= nk; kc += RING) {
+  for (int kc = 0; kc < nk; kc += L::PERIOD) {
 #pragma unroll
-    for (int s = 0; s < RING; s++) chunk(kc + s, s);
+    for (int pc = 0; pc < L::PERIOD; pc++) {
+      if (kc + pc < nk) chunk(kc + pc, pc);
+    }
   }
-  for (int s = 0; kc < nk; kc++, s++) chunk(kc, s);
   wait_vmcnt<0>();
 }
 
@@ -201,9 +197,11 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
 // BT: the B operand is stored chunk-major, [K/32][N][32] (the stage's weight copies): a chunk of B rows is then one
 // contiguous run, where row-major rows give every load half a cache line per row and make L2 serve each line twice.
 template <int BM, int BN, bool BT>
-struct NtLayout {
+struct NtLayout32 {
   static constexpr int TM = BM / 64, TN = BN / 64, A_SLOT = BM * CK_, B_SLOT = BN * CK_;
   static_assert(TM == TN, "one DMA instruction per MFMA group");
+  static constexpr int PERIOD = RING, WAIT_PRO = 5 * TN, WAIT_MID = 4 * TN;
+  static constexpr size_t LDS_BYTES = (size_t)RING * (A_SLOT + B_SLOT) * 2;
   i32x4 ra, rb; unsigned lds0; int wave, nk, sb; int voa[TN], vob[TN];
   const bf16_t* fa_base[2]; const bf16_t* fb_base[2];
   __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
@@ -228,8 +226,96 @@ struct NtLayout {
   }
   __device__ __forceinline__ void dma_a(int i, int kc, int slot) { dma16b(ra, voa[i], min(kc, nk - 1) * (CK_ * 2), lds0 + (slot * A_SLOT + (i * 4 + wave) * 512) * 2); }
   __device__ __forceinline__ void dma_b(int i, int kc, int slot) { dma16b(rb, vob[i], min(kc, nk - 1) * sb, lds0 + (RING * A_SLOT + slot * B_SLOT + (i * 4 + wave) * 512) * 2); }
+  // issue order: A then B of chunks 0..2, A of chunk 3; then per chunk kc: B of kc+3 (k-step 0), A of kc+4 (k-step 1)
+  __device__ __forceinline__ void prologue() {
+#pragma unroll
+    for (int c = 0; c < RING; c++) {
+#pragma unroll
+      for (int i = 0; i < TN; i++) dma_a(i, c, c);
+      if (c < RING - 1) {
+#pragma unroll
+        for (int i = 0; i < TN; i++) dma_b(i, c, c);
+      }
+    }
+  }
+  __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, kc + 3, (pc + 3) & 3); }
+  __device__ __forceinline__ void dma1(int j, int kc, int pc) { dma_a(j, kc + 4, pc); }
   __device__ __forceinline__ bf16x8 rd_a(int slot, int ks, int i) { return *reinterpret_cast<const bf16x8*>(fa_base[ks] + slot * A_SLOT + i * 32 * CK_); }
   __device__ __forceinline__ bf16x8 rd_b(int slot, int ks, int j) { return *reinterpret_cast<const bf16x8*>(fb_base[ks] + slot * B_SLOT + j * 32 * CK_); }
+};
+
+// NT operands with a chunk-major B (the stage's weight copies) and K % 64 == 0: A is staged in slices of 64
+// reduction steps, so that every DMA instruction reads eight whole 128-byte rows (a 32-deep chunk of a row-major
+// operand is half a cache line per row, and L2 then serves every line twice).  A slice feeds two chunks; the A ring
+// holds three slices, the B ring four chunks, together all 160 KiB of the CU for 256 x 256 tiles (half for
+// 128 x 128).  Slice S+3 overwrites slice S, which is free once chunk 2S+1 has passed its middle barrier: its
+// first half is issued in k-step 1 of chunk 2S+1, its second half in k-step 1 of chunk 2S+2, five and four
+// chunks before its first read.  B of chunk kc+3 goes out in k-step 0 of chunk kc.  Loads retire in order, so
+// "at most 4 TN in flight" at the middle of chunk kc means B of kc+1 and everything older (the A slice of kc+1
+// among it) has landed.
+// LDS slice [rows][64]: 16-byte piece p of row r holds logical piece p ^ ((r >> 1) & 7): the 16 rows a fragment
+// read touches per clock land on 16 different 16-byte bank groups.
+template <int BM, int BN>
+struct NtLayout64 {
+  static constexpr int TM = BM / 64, TN = BN / 64, A_SLICE = BM * 64, B_SLOT = BN * CK_, A_RING = 3;
+  static_assert(TM == TN, "one DMA instruction per MFMA group");
+  static constexpr int PERIOD = 12, WAIT_PRO = 5 * TN, WAIT_MID = 4 * TN;
+  static constexpr size_t LDS_BYTES = (size_t)(A_RING * A_SLICE + RING * B_SLOT) * 2;
+  i32x4 ra, rb; unsigned lds0; int wave, nk, ns, sb; int voa[2 * TN], vob[TN];
+  const bf16_t* fa_base[4]; const bf16_t* fb_base[2];
+  __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
+    wave = wave_; nk = K / CK_; ns = K / 64; sb = N * CK_ * 2;       // bytes from one chunk of B to the next
+    ra = make_rsrc(A, (size_t)M * K * 2); rb = make_rsrc(B, (size_t)N * K * 2);
+    lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    // A: instruction g = i * 4 + wave covers rows 8 g .. 8 g + 7, lane l row l / 8, physical piece l % 8
+    const int arow = lane >> 3, apiece = (lane & 7) ^ (((wave & 1) << 2) | (lane >> 4));
+#pragma unroll
+    for (int i = 0; i < 2 * TN; i++) voa[i] = ((m0 + (i * 4 + wave) * 8 + arow) * K + apiece * 8) * 2;
+    const int brow = lane >> 2, bpiece = (lane & 3) ^ ((lane >> 4) & 3);
+#pragma unroll
+    for (int i = 0; i < TN; i++) vob[i] = ((n0 + (i * 4 + wave) * 16 + brow) * CK_ + bpiece * 8) * 2;
+    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
+    const int frow = lane & 31, fhalf = lane >> 5, fsw_a = (lane >> 1) & 7, fsw_b = (lane >> 2) & 3;
+    const bf16_t* As = reinterpret_cast<const bf16_t*>(smem);
+    const bf16_t* Bs = As + A_RING * A_SLICE;
+#pragma unroll
+    for (int q = 0; q < 4; q++) fa_base[q] = As + (wm0 + frow) * 64 + (((q * 2 + fhalf) ^ fsw_a) << 3);   // q = 2 (chunk & 1) + k-step
+#pragma unroll
+    for (int ks = 0; ks < 2; ks++) fb_base[ks] = Bs + (wn0 + frow) * CK_ + (((ks * 2 + fhalf) ^ fsw_b) << 3);
+  }
+  __device__ __forceinline__ void dma_a(int instr, int slice, int slot) {
+    dma16b(ra, voa[instr], min(slice, ns - 1) * 128, lds0 + (slot * A_SLICE + (instr * 4 + wave) * 512) * 2);
+  }
+  __device__ __forceinline__ void dma_b(int i, int kc, int slot) {
+    dma16b(rb, vob[i], min(kc, nk - 1) * sb, lds0 + (A_RING * A_SLICE + slot * B_SLOT + (i * 4 + wave) * 512) * 2);
+  }
+  // The order keeps the loop's invariant from the first chunk on: behind B of chunk c+1 come exactly two halves
+  // of A slices and B of chunks c+2 and c+3 when chunk c reaches its middle.
+  __device__ __forceinline__ void prologue() {
+#pragma unroll
+    for (int i = 0; i < 2 * TN; i++) dma_a(i, 0, 0);
+#pragma unroll
+    for (int i = 0; i < TN; i++) dma_b(i, 0, 0);
+#pragma unroll
+    for (int i = 0; i < TN; i++) dma_a(i, 1, 1);
+#pragma unroll
+    for (int i = 0; i < TN; i++) dma_b(i, 1, 1);
+#pragma unroll
+    for (int i = 0; i < TN; i++) dma_a(TN + i, 1, 1);
+#pragma unroll
+    for (int i = 0; i < TN; i++) dma_b(i, 2, 2);
+#pragma unroll
+    for (int i = 0; i < TN; i++) dma_a(i, 2, 2);
+  }
+  __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, kc + 3, (pc + 3) & 3); }
+  __device__ __forceinline__ void dma1(int j, int kc, int pc) {
+    if (pc & 1) dma_a(j, (kc >> 1) + 3, (pc >> 1) % 3);
+    else dma_a(TN + j, (kc >> 1) + 2, ((pc >> 1) + 2) % 3);
+  }
+  __device__ __forceinline__ bf16x8 rd_a(int pc, int ks, int i) {
+    return *reinterpret_cast<const bf16x8*>(fa_base[(pc & 1) * 2 + ks] + ((pc >> 1) % 3) * A_SLICE + i * 32 * 64);
+  }
+  __device__ __forceinline__ bf16x8 rd_b(int pc, int ks, int j) { return *reinterpret_cast<const bf16x8*>(fb_base[ks] + (pc & 3) * B_SLOT + j * 32 * CK_); }
 };
 
 // TN operands: X[K, cols] row-major, both (K = reduction).  LDS chunk [32 reduction rows][cols] as in memory, the
@@ -239,6 +325,8 @@ template <int BM, int BN>
 struct TnLayout {
   static constexpr int TM = BM / 64, TN = BN / 64, A_SLOT = BM * CK_, B_SLOT = BN * CK_;
   static_assert(TM == TN, "one DMA instruction per MFMA group");
+  static constexpr int PERIOD = RING, WAIT_PRO = 5 * TN, WAIT_MID = 4 * TN;
+  static constexpr size_t LDS_BYTES = (size_t)RING * (A_SLOT + B_SLOT) * 2;
   static constexpr int CA = BM / 8, CB = BN / 8;           // 16-byte pieces per row
   static constexpr int RA = 64 / CA, RB = 64 / CB;         // rows one DMA instruction (1 KiB) covers
   i32x4 ra, rb; unsigned lds0; int wave, nk, sa, sb; int voa[TN], vob[TN];
@@ -274,6 +362,19 @@ struct TnLayout {
   }
   __device__ __forceinline__ void dma_a(int i, int kc, int slot) { dma16b(ra, voa[i], min(kc, nk - 1) * sa, lds0 + (slot * A_SLOT + (i * 4 + wave) * 512) * 2); }
   __device__ __forceinline__ void dma_b(int i, int kc, int slot) { dma16b(rb, vob[i], min(kc, nk - 1) * sb, lds0 + (RING * A_SLOT + slot * B_SLOT + (i * 4 + wave) * 512) * 2); }
+  __device__ __forceinline__ void prologue() {
+#pragma unroll
+    for (int c = 0; c < RING; c++) {
+#pragma unroll
+      for (int i = 0; i < TN; i++) dma_a(i, c, c);
+      if (c < RING - 1) {
+#pragma unroll
+        for (int i = 0; i < TN; i++) dma_b(i, c, c);
+      }
+    }
+  }
+  __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, kc + 3, (pc + 3) & 3); }
+  __device__ __forceinline__ void dma1(int j, int kc, int pc) { dma_a(j, kc + 4, pc); }
   static __device__ __forceinline__ bf16x8 tr_pair(const bf16_t* p, int second_offset) {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
@@ -372,7 +473,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  NtLayout<BM, BN, BT> lay;
+  typename std::conditional<BT, NtLayout64<BM, BN>, NtLayout32<BM, BN, false>>::type lay;
   lay.init(smem, A, B, M, N, K, m0, n0, lane, wave);
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -591,6 +692,7 @@ const char* gemm_bf16_check(const GemmArgs& g) {
   if (g.kind == KFKB_GEMM_NT) {
     if (g.N % 128 != 0) return "bf16 NT GEMM needs N % 128 == 0";
     if (g.K % 32 != 0) return "bf16 NT GEMM needs K % 32 == 0";
+    if (g.b_tiled && g.K % 64 != 0) return "bf16 NT GEMM with a chunk-major B needs K % 64 == 0";
   } else if (g.kind == KFKB_GEMM_TN) {
     if (g.M % 128 != 0 || g.N % 128 != 0) return "bf16 TN GEMM needs M % 128 == 0 and N % 128 == 0";
     if (g.epilogue != KFKB_EPI_ACCUM && g.epilogue != KFKB_EPI_NONE) return "bf16 TN GEMM supports epilogues NONE and ACCUM";
@@ -605,12 +707,13 @@ const char* gemm_bf16_check(const GemmArgs& g) {
 template <int BM, int BN> constexpr size_t tile_lds_bytes() {
   return std::max((size_t)RING * (BM + BN) * CK_ * sizeof(bf16_t), epilogue_lds_bytes<BM, BN>());
 }
+template <int BM, int BN> constexpr size_t tile64_lds_bytes() { return std::max(NtLayout64<BM, BN>::LDS_BYTES, epilogue_lds_bytes<BM, BN>()); }
 
 template <int BM, int BN, int EPI, bool BT>
 static hipError_t launch_nt_bt(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  constexpr size_t smem = tile_lds_bytes<BM, BN>();
+  constexpr size_t smem = BT ? tile64_lds_bytes<BM, BN>() : tile_lds_bytes<BM, BN>();
   auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, BT>;
   static bool attr_set = false;
   if (!attr_set) {

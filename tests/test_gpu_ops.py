@@ -87,7 +87,7 @@ def test_transpose(dt):
 
 
 # ---------------------------------------------------------------- GEMM
-def _gemm_case(dt, kind, epi, M, N, K, seed=20):
+def _gemm_case(dt, kind, epi, M, N, K, seed=20, tiled=0):
     """Runs one GEMM through the boundary and returns (got, reference) lists."""
     if kind == kf.GEMM_NN:
         A = rnd(seed, (M, K), dt); B = rnd(seed + 1, (K, N), dt, 0.05); acc = A @ B
@@ -100,7 +100,15 @@ def _gemm_case(dt, kind, epi, M, N, K, seed=20):
     C2 = torch.zeros(M, N, dtype=tdtype(dt), device="cuda")
     Cacc0 = rnd(seed + 4, (M, N), kf.F32)
     Cacc = dev(Cacc0, kf.F32)
-    kf.kfkb_op_gemm(dt, kind, epi, M, N, K, dev(A, dt), dev(B, dt), dev(bias, dt), dev(res, dt), Cout, C2, Cacc)
+    if tiled == 0:
+        kf.kfkb_op_gemm(dt, kind, epi, M, N, K, dev(A, dt), dev(B, dt), dev(bias, dt), dev(res, dt), Cout, C2, Cacc)
+    else:
+        # B handed over chunk-major, made on the device from B itself (tiled == 1) or from its transpose (tiled == 2)
+        assert dt == kf.BF16 and kind == kf.GEMM_NT
+        Bt = torch.empty(N * K, dtype=torch.bfloat16, device="cuda")
+        src = dev(B if tiled == 1 else np.ascontiguousarray(B.T), dt)
+        kf.kfkb_op_tile_weights(src, Bt, N, K, tiled == 2)
+        kf.kfkb_op_gemm_nt_tiled(epi, M, N, K, dev(A, dt), Bt, dev(bias, dt), dev(res, dt), Cout, C2, Cacc)
     _sync()
     if epi == kf.EPI_NONE:
         return [host(Cout)], [acc]
@@ -131,6 +139,33 @@ def test_gemm_bf16_nt(epi, M, N, K):
     for g, r in zip(got, ref):
         assert_close(g, r, kf.BF16 if epi != kf.EPI_ACCUM else kf.F32, "gemm bf16 NT epi %d" % epi,
                      factor=1 if epi != kf.EPI_ACCUM else 10)
+
+
+@pytest.mark.parametrize("epi", range(6))
+@pytest.mark.parametrize("M,N,K,tiled", [(128, 128, 64, 1), (300, 384, 448, 2), (515, 256, 832, 1), (2048 + 77, 2048, 1024, 2),
+                                         (4096 - 3, 4096, 128, 1), (4096, 1024, 768, 2)])
+def test_gemm_bf16_nt_chunk_major_weights(epi, M, N, K, tiled):
+    """The NT kernel that reads B chunk-major (and A in 64-deep slices): reduction lengths below, at and
+    beyond one period of its LDS rings (12 chunks of 32), ragged M, both tile sizes."""
+    got, ref = _gemm_case(kf.BF16, kf.GEMM_NT, epi, M, N, K, tiled=tiled)
+    for g, r in zip(got, ref):
+        assert_close(g, r, kf.BF16 if epi != kf.EPI_ACCUM else kf.F32, "gemm bf16 NT chunk-major epi %d" % epi,
+                     factor=1 if epi != kf.EPI_ACCUM else 10)
+
+
+def test_tile_weights_layout():
+    N, K = 72, 96
+    B = rnd(31, (N, K), kf.BF16)
+    want = np.ascontiguousarray(B.reshape(N, K // 32, 32).transpose(1, 0, 2)).reshape(-1)
+    for transposed in (False, True):
+        dst = torch.zeros(N * K, dtype=torch.bfloat16, device="cuda")
+        kf.kfkb_op_tile_weights(dev(np.ascontiguousarray(B.T) if transposed else B, kf.BF16), dst, N, K, transposed)
+        _sync()
+        assert np.array_equal(host(dst), want)
+    with pytest.raises(kf.KfkbError):
+        kf.kfkb_op_tile_weights(dst, dst, N, 48, False)
+    with pytest.raises(kf.KfkbError):
+        kf.kfkb_op_gemm_nt_tiled(kf.EPI_NONE, 128, 128, 96, dst, dst, None, None, dst, None, None)    # K % 64 != 0
 
 
 @pytest.mark.parametrize("epi", [kf.EPI_ACCUM, kf.EPI_NONE])
