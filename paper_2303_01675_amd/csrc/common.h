@@ -133,7 +133,20 @@ struct GemmArgs {
 };
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);   // NT and TN only
-hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s);   // up to 4 wgrads, one launch
+// The small reductions that belong to the same step as a group of weight-gradient products: column sums over the
+// token axis of up to four bf16 matrices dy[rows, width] (out[i][c] += sum_r dy[i][r][c]) and the finishing pass of
+// up to two LayerNorm backward reductions (partial rows left by launch_ln_bwd called with dgamma == nullptr;
+// ln_parts[i] = ln_bwd_partial_rows(rows, width); out0 += the first half of every partial row, out1 += the second).
+struct WStepReduce {
+  int rows, n_colsum, n_ln;
+  const void* dy[4]; float* out[4]; int width[4];
+  const float* ln_partial[2]; float* ln_out0[2]; float* ln_out1[2]; int ln_parts[2]; int ln_width[2];
+};
+// Up to 4 wgrads in one launch.  With `red`, workgroups of the same launch also do those reductions on the CUs the
+// tiles leave idle when the shapes allow (*red_done = true); otherwise *red_done = false and the caller runs them.
+hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
+                                     bool* red_done = nullptr);
+int ln_bwd_partial_rows(int rows, int H);        // partial rows launch_ln_bwd leaves in its scratch
 const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported
 
 hipError_t launch_attention_fwd_f32(const float* qkv, float* o, float* lse, int b, int T, int H, int heads,

@@ -202,6 +202,7 @@ struct Stage {
   Lane lane[2];
   int lanes = 2;
   bool wgrad_overlap = true;
+  bool fuse_w_reductions = true;   // KFKB_FUSE_W=0: the W step's small reductions as launches of their own
   // W steps get a stream of their own when the process has hardware queues to spare (GPU_MAX_HW_QUEUES >= 5:
   // two lanes, this one, send, receive); otherwise they borrow the other lane's stream while that lane is idle
   hipStream_t sw = nullptr;
@@ -453,22 +454,35 @@ int backward_block(ActiveOp& a) {
     HIPCHK(hipStreamWaitEvent(qw, ln.ev_chain[ring], 0));
   }
   if (s.ev_g_set[l]) HIPCHK(hipStreamWaitEvent(qw, s.ev_g[l], 0));     // the previous micro-batch's W step of this block
-  HIPCHK(launch_ln_bwd_final(ln.red_ln[par][1], s.m, s.H, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), qw));
-  HIPCHK(launch_ln_bwd_final(ln.red_ln[par][0], s.m, s.H, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), qw));
+  // the weight-gradient products in one launch; the bias-gradient column sums and the finishing pass of the two
+  // LayerNorm-parameter reductions ride along in it (bf16), or run as launches of their own
+  WStepReduce red{};
+  red.rows = s.m; red.n_colsum = 4; red.n_ln = 2;
   {
     const void* srcs[4] = {dqkv, du, dy, dx1};
     float* outs[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
     const int widths[4] = {3 * s.H, s.F, s.H, s.H};
-    HIPCHK(launch_colsum_group(s.dt, 4, srcs, outs, widths, ln.red_w[par], s.m, qw));
+    for (int i = 0; i < 4; i++) { red.dy[i] = srcs[i]; red.out[i] = outs[i]; red.width[i] = widths[i]; }
+    // partial rows: [sum dy | sum dy * xhat] -> beta, gamma
+    red.ln_partial[0] = ln.red_ln[par][1]; red.ln_out0[0] = gptr(s, l, s.po.ln2_b); red.ln_out1[0] = gptr(s, l, s.po.ln2_g);
+    red.ln_partial[1] = ln.red_ln[par][0]; red.ln_out0[1] = gptr(s, l, s.po.ln1_b); red.ln_out1[1] = gptr(s, l, s.po.ln1_g);
+    red.ln_parts[0] = red.ln_parts[1] = ln_bwd_partial_rows(s.m, s.H);
+    red.ln_width[0] = red.ln_width[1] = s.H;
   }
+  bool red_done = false;
   if (s.dt == DT_BF16) {
     for (int i = 0; i < 4; i++) {
       const char* why = gemm_bf16_check(wg[i]);
       if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
     }
-    HIPCHK(launch_gemm_bf16_tn_group(wg, 4, qw));
+    HIPCHK(launch_gemm_bf16_tn_group(wg, 4, qw, s.fuse_w_reductions ? &red : nullptr, &red_done));
   } else {
     for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], qw));
+  }
+  if (!red_done) {
+    HIPCHK(launch_ln_bwd_final(ln.red_ln[par][1], s.m, s.H, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), qw));
+    HIPCHK(launch_ln_bwd_final(ln.red_ln[par][0], s.m, s.H, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), qw));
+    HIPCHK(launch_colsum_group(s.dt, 4, red.dy, red.out, red.width, ln.red_w[par], s.m, qw));
   }
   HIPCHK(hipEventRecord(s.ev_g[l], qw));
   s.ev_g_set[l] = 1;
@@ -874,6 +888,7 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   g.ev_g_set.assign(g.L, 0);
   HIPCHK(hipEventCreate(&g.ev_zero));
   { const char* e = getenv("KFKB_WGRAD_STREAM"); g.wgrad_overlap = !(e && e[0] == '0'); }
+  { const char* e = getenv("KFKB_FUSE_W"); g.fuse_w_reductions = !(e && e[0] == '0'); }
   { const char* e = getenv("KFKB_LANES"); g.lanes = (e && e[0] == '1') ? 1 : 2; }
   { const char* e = getenv("GPU_MAX_HW_QUEUES"); if (e && atoi(e) >= 5) HIPCHK(hipStreamCreateWithFlags(&g.sw, hipStreamNonBlocking)); }
   HIPCHK(hipEventCreate(&g.ev_sw_tail));

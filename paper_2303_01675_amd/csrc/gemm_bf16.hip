@@ -552,9 +552,114 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
 struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const bf16_t* A; const bf16_t* B; float* Cacc; };
 struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 
+// The small reductions of the same step, done by extra workgroups of the same launch on the CUs the tiles leave
+// idle (192 tiles of 256 x 256 on 256 CUs for a GPT-2-medium block) instead of by launches of their own:
+//   column sums over the token axis of up to four bf16 matrices dy[rows, width] (the bias gradients), and
+//   the finishing pass of up to two LayerNorm-parameter reductions: sums over the partial rows
+//   partial[parts][2][width] (fp32) that the LayerNorm backward kernels left behind.
+// Work items are strips of 64 columns, dealt round-robin to the reduce workgroups; one workgroup owns a strip from
+// the first row to the last and adds in a fixed order, so the sums do not depend on timing or on the launch shape.
+struct RedColsum { const bf16_t* dy; float* out; int width, first_item; };
+struct RedLnFinal { const float* partial; float* out0; float* out1; int parts, width, first_item; };
+struct ReduceGroup { int n_colsum, n_ln, rows, total_items; RedColsum c[4]; RedLnFinal ln[2]; };
+
+__device__ __forceinline__ void reduce_colsum_strip(const RedColsum& pr, int strip, int rows, float* red) {
+  const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;              // 8 lanes x 16 bytes = one 128-byte row piece
+  const bf16_t* src = pr.dy + strip * 64 + cl * 8;
+  const size_t w = pr.width;
+  float a[8];
+#pragma unroll
+  for (int e = 0; e < 8; e++) a[e] = 0.f;
+  int r = rl;
+  for (; r + 32 * 7 < rows; r += 32 * 8) {                            // eight loads in flight per lane
+    bf16x8 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; u++) v[u] = *reinterpret_cast<const bf16x8*>(src + (size_t)(r + 32 * u) * w);
+#pragma unroll
+    for (int u = 0; u < 8; u++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) a[e] += (float)v[u][e];
+  }
+  for (; r < rows; r += 32) {
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(src + (size_t)r * w);
+#pragma unroll
+    for (int e = 0; e < 8; e++) a[e] += (float)v[e];
+  }
+#pragma unroll
+  for (int e = 0; e < 8; e++) red[rl * 65 + cl * 8 + e] = a[e];
+  __syncthreads();
+  if (threadIdx.x < 64) {
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 32; j++) t += red[j * 65 + threadIdx.x];
+    pr.out[strip * 64 + threadIdx.x] += t;
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ void reduce_ln_strip(const RedLnFinal& pr, int strip, float* red) {
+  const int c4 = threadIdx.x & 15, pl = threadIdx.x >> 4;             // 16 lanes x float4 = 64 columns, 16 part lanes
+  const size_t w = pr.width;
+  const float* src = pr.partial + strip * 64 + c4 * 4;
+  float4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
+  int p = pl;
+  for (; p + 16 * 3 < pr.parts; p += 16 * 4) {
+    float4 v0[4], v1[4];
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      v0[u] = *reinterpret_cast<const float4*>(src + (size_t)(p + 16 * u) * 2 * w);
+      v1[u] = *reinterpret_cast<const float4*>(src + (size_t)(p + 16 * u) * 2 * w + w);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; u++) {
+      s0.x += v0[u].x; s0.y += v0[u].y; s0.z += v0[u].z; s0.w += v0[u].w;
+      s1.x += v1[u].x; s1.y += v1[u].y; s1.z += v1[u].z; s1.w += v1[u].w;
+    }
+  }
+  for (; p < pr.parts; p += 16) {
+    const float4 v0 = *reinterpret_cast<const float4*>(src + (size_t)p * 2 * w);
+    const float4 v1 = *reinterpret_cast<const float4*>(src + (size_t)p * 2 * w + w);
+    s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
+    s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
+  }
+  float* r0 = red + pl * 65 + c4 * 4;
+  float* r1 = red + 16 * 65 + pl * 65 + c4 * 4;
+  r0[0] = s0.x; r0[1] = s0.y; r0[2] = s0.z; r0[3] = s0.w;
+  r1[0] = s1.x; r1[1] = s1.y; r1[2] = s1.z; r1[3] = s1.w;
+  __syncthreads();
+  if (threadIdx.x < 128) {
+    const int half = threadIdx.x >> 6, c = threadIdx.x & 63;
+    float t = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; j++) t += red[half * 16 * 65 + j * 65 + c];
+    float* out = half ? pr.out1 : pr.out0;
+    out[strip * 64 + c] += t;
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ void reduce_role(const ReduceGroup& rg, int rb, int nrb, char* smem) {
+  float* red = reinterpret_cast<float*>(smem);                        // 32 x 65 floats
+  for (int item = rb; item < rg.total_items; item += nrb) {
+    bool done = false;                              // items are numbered LayerNorm strips first, then column-sum strips
+#pragma unroll
+    for (int q = 3; q >= 0; q--) {
+      if (!done && q < rg.n_colsum && item >= rg.c[q].first_item) { reduce_colsum_strip(rg.c[q], item - rg.c[q].first_item, rg.rows, red); done = true; }
+    }
+#pragma unroll
+    for (int q = 1; q >= 0; q--) {
+      if (!done && q < rg.n_ln && item >= rg.ln[q].first_item) { reduce_ln_strip(rg.ln[q], item - rg.ln[q].first_item, red); done = true; }
+    }
+  }
+}
+
 template <int BM, int BN>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp) {
+__global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp, ReduceGroup rg, int gemm_blocks) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  if ((int)blockIdx.x >= gemm_blocks) {             // the last blocks of the grid: dispatched after every tile has a CU
+    reduce_role(rg, blockIdx.x - gemm_blocks, gridDim.x - gemm_blocks, smem);
+    return;
+  }
   const int t = linear_of_block(grp.total_tiles);
   if (t >= grp.total_tiles) return;
   int i = 0;
@@ -767,8 +872,17 @@ static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
 }
 
 template <int BM, int BN>
-static hipError_t launch_group(const TnGroup& grp, double flops, hipStream_t s) {
-  const int grid = ((grp.total_tiles + 7) / 8) * 8;
+static hipError_t launch_group(const TnGroup& grp, const ReduceGroup& rg, double flops, hipStream_t s) {
+  const int gemm_blocks = ((grp.total_tiles + 7) / 8) * 8;
+  int reduce_blocks = 0;
+  if (rg.total_items > 0) {
+    // as many as the tiles leave CU slots idle in their last round, within 32 .. 128
+    constexpr size_t lds_cu = 160 * 1024;
+    const int slots = 256 * (int)(lds_cu / tile_lds_bytes<BM, BN>());
+    const int idle = (slots - gemm_blocks % slots) % slots;
+    reduce_blocks = std::min(std::max(idle, 32), 128) / 8 * 8;
+    reduce_blocks = std::min(reduce_blocks, (rg.total_items + 7) / 8 * 8);
+  }
   constexpr size_t smem = tile_lds_bytes<BM, BN>();
   auto kern = gemm_bf16_tn_grouped_kernel<BM, BN>;
   static bool attr_set = false;
@@ -777,7 +891,7 @@ static hipError_t launch_group(const TnGroup& grp, double flops, hipStream_t s) 
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 301 : 300), flops, grp);
+  klaunch(kern, dim3(gemm_blocks + reduce_blocks), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 301 : 300), flops, grp, rg, gemm_blocks);
   return hipGetLastError();
 }
 
@@ -789,7 +903,8 @@ static long big_tile_min() {
   return v;
 }
 
-hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
+hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
+  if (red_done) *red_done = false;
   if (n <= 0) return hipSuccess;
   bool groupable = n <= 4;
   for (int i = 0; i < n; i++)
@@ -821,8 +936,27 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s) {
     grp.total_tiles += p.tiles_m * p.tiles_n;
     flops += 2.0 * g[i].M * g[i].N * g[i].K;
   }
-  if (big) return launch_group<256, 256>(grp, flops, s);
-  return launch_group<128, 128>(grp, flops, s);
+  // the reductions ride along when they divide into strips of 64 columns
+  ReduceGroup rg{};
+  if (red != nullptr && red->rows > 0 && red->n_colsum <= 4 && red->n_ln <= 2) {
+    bool ok = true;
+    for (int i = 0; i < red->n_colsum; i++) ok = ok && red->width[i] > 0 && red->width[i] % 64 == 0;
+    for (int i = 0; i < red->n_ln; i++) ok = ok && red->ln_width[i] > 0 && red->ln_width[i] % 64 == 0 && red->ln_parts[i] > 0;
+    if (ok) {
+      rg.n_colsum = red->n_colsum; rg.n_ln = red->n_ln; rg.rows = red->rows;
+      for (int i = 0; i < red->n_ln; i++) {
+        rg.ln[i] = RedLnFinal{red->ln_partial[i], red->ln_out0[i], red->ln_out1[i], red->ln_parts[i], red->ln_width[i], rg.total_items};
+        rg.total_items += red->ln_width[i] / 64;
+      }
+      for (int i = 0; i < red->n_colsum; i++) {
+        rg.c[i] = RedColsum{(const bf16_t*)red->dy[i], red->out[i], red->width[i], rg.total_items};
+        rg.total_items += red->width[i] / 64;
+      }
+      if (red_done) *red_done = true;
+    }
+  }
+  if (big) return launch_group<256, 256>(grp, rg, flops, s);
+  return launch_group<128, 128>(grp, rg, flops, s);
 }
 
 // Large tiles when they still give most CUs a tile; small tiles otherwise.

@@ -541,15 +541,17 @@ hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mea
 
 // The finishing pass of launch_ln_bwd called with dgamma == nullptr: adds the partial sums it left in `scratch`
 // into dgamma / dbeta.  rows and H must be those of that call (they fix the number of partial rows).
-hipError_t launch_ln_bwd_final(const float* scratch, int rows, int H, float* dgamma, float* dbeta, hipStream_t s) {
-  if (rows <= 0) return hipSuccess;
-  int parts;
+int ln_bwd_partial_rows(int rows, int H) {
   if (nch_for(H) <= 4) {
     const int rpb = std::max(8, ((rows + 511) / 512 + 3) / 4 * 4);
-    parts = (rows + rpb - 1) / rpb;
-  } else {
-    parts = reduce_parts(rows);
+    return (rows + rpb - 1) / rpb;
   }
+  return reduce_parts(rows);
+}
+
+hipError_t launch_ln_bwd_final(const float* scratch, int rows, int H, float* dgamma, float* dbeta, hipStream_t s) {
+  if (rows <= 0) return hipSuccess;
+  const int parts = ln_bwd_partial_rows(rows, H);
   klaunch(colsum_final_kernel, dim3((H + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL, (double)parts * H * 8, scratch, parts, H,
           dbeta, dgamma);
   return hipGetLastError();
