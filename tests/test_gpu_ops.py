@@ -143,7 +143,8 @@ def test_gemm_bf16_nt(epi, M, N, K):
 
 @pytest.mark.parametrize("epi", range(6))
 @pytest.mark.parametrize("M,N,K,tiled", [(128, 128, 64, 1), (300, 384, 448, 2), (515, 256, 832, 1), (2048 + 77, 2048, 1024, 2),
-                                         (4096 - 3, 4096, 128, 1), (4096, 1024, 768, 2)])
+                                         (4096 - 3, 4096, 128, 1), (4096, 1024, 768, 2), (1000, 1024, 1024, 1),
+                                         (2048, 512, 1536, 2)])
 def test_gemm_bf16_nt_chunk_major_weights(epi, M, N, K, tiled):
     """The NT kernel that reads B chunk-major (and A in 64-deep slices): reduction lengths below, at and
     beyond one period of its LDS rings (12 chunks of 32), ragged M, both tile sizes."""
