@@ -45,9 +45,9 @@ __device__ __forceinline__ void tile_from_linear(int t, int tiles_m, int tiles_n
   tn = in_group / gsz;
 }
 // block -> position in the tile order such that every XCD owns a contiguous run of it
-__device__ __forceinline__ int linear_of_block(int total_tiles) {
+__device__ __forceinline__ int linear_of_block(int total_tiles, int block = blockIdx.x) {
   const int per_xcd = (total_tiles + 7) / 8;
-  return (blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+  return (block % 8) * per_xcd + block / 8;
 }
 __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn, bool& valid) {
   const int t = linear_of_block(tiles_m * tiles_n);
@@ -552,8 +552,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
 struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const bf16_t* A; const bf16_t* B; float* Cacc; };
 struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 
-// The small reductions of the same step, done by extra workgroups of the same launch on the CUs the tiles leave
-// idle (192 tiles of 256 x 256 on 256 CUs for a GPT-2-medium block) instead of by launches of their own:
+// The small reductions of the same step, done by extra workgroups of the same launch, on the CUs the tiles leave
+// idle (192 tiles of 256 x 256 on 256 CUs for a GPT-2-medium block), instead of by launches of their own:
 //   column sums over the token axis of up to four bf16 matrices dy[rows, width] (the bias gradients), and
 //   the finishing pass of up to two LayerNorm-parameter reductions: sums over the partial rows
 //   partial[parts][2][width] (fp32) that the LayerNorm backward kernels left behind.
@@ -571,12 +571,12 @@ __device__ __forceinline__ void reduce_colsum_strip(const RedColsum& pr, int str
 #pragma unroll
   for (int e = 0; e < 8; e++) a[e] = 0.f;
   int r = rl;
-  for (; r + 32 * 7 < rows; r += 32 * 8) {                            // eight loads in flight per lane
-    bf16x8 v[8];
+  for (; r + 32 * 15 < rows; r += 32 * 16) {                          // sixteen loads in flight per lane
+    bf16x8 v[16];
 #pragma unroll
-    for (int u = 0; u < 8; u++) v[u] = *reinterpret_cast<const bf16x8*>(src + (size_t)(r + 32 * u) * w);
+    for (int u = 0; u < 16; u++) v[u] = *reinterpret_cast<const bf16x8*>(src + (size_t)(r + 32 * u) * w);
 #pragma unroll
-    for (int u = 0; u < 8; u++)
+    for (int u = 0; u < 16; u++)
 #pragma unroll
       for (int e = 0; e < 8; e++) a[e] += (float)v[u][e];
   }
@@ -654,13 +654,15 @@ __device__ __forceinline__ void reduce_role(const ReduceGroup& rg, int rb, int n
 }
 
 template <int BM, int BN>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp, ReduceGroup rg, int gemm_blocks) {
+__global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp, ReduceGroup rg, int reduce_blocks) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  if ((int)blockIdx.x >= gemm_blocks) {             // the last blocks of the grid: dispatched after every tile has a CU
-    reduce_role(rg, blockIdx.x - gemm_blocks, gridDim.x - gemm_blocks, smem);
+  // The first blocks of the grid (a multiple of 8, so the tiles keep their XCDs) reduce: they are on their CUs from
+  // the start and finish in the shadow of the tiles, also when the tiles need several rounds.
+  if ((int)blockIdx.x < reduce_blocks) {
+    reduce_role(rg, blockIdx.x, reduce_blocks, smem);
     return;
   }
-  const int t = linear_of_block(grp.total_tiles);
+  const int t = linear_of_block(grp.total_tiles, blockIdx.x - reduce_blocks);
   if (t >= grp.total_tiles) return;
   int i = 0;
 #pragma unroll
@@ -876,11 +878,12 @@ static hipError_t launch_group(const TnGroup& grp, const ReduceGroup& rg, double
   const int gemm_blocks = ((grp.total_tiles + 7) / 8) * 8;
   int reduce_blocks = 0;
   if (rg.total_items > 0) {
-    // as many as the tiles leave CU slots idle in their last round, within 32 .. 128
+    // as many as the tiles leave CU slots idle in their last round; where that is few (the tiles fill their rounds)
+    // 128 of them take the first round's slots for a while instead
     constexpr size_t lds_cu = 160 * 1024;
     const int slots = 256 * (int)(lds_cu / tile_lds_bytes<BM, BN>());
     const int idle = (slots - gemm_blocks % slots) % slots;
-    reduce_blocks = std::min(std::max(idle, 32), 128) / 8 * 8;
+    reduce_blocks = (idle >= 48 ? std::min(idle, 128) : 128) / 8 * 8;
     reduce_blocks = std::min(reduce_blocks, (rg.total_items + 7) / 8 * 8);
   }
   constexpr size_t smem = tile_lds_bytes<BM, BN>();
@@ -891,7 +894,7 @@ static hipError_t launch_group(const TnGroup& grp, const ReduceGroup& rg, double
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  klaunch(kern, dim3(gemm_blocks + reduce_blocks), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 301 : 300), flops, grp, rg, gemm_blocks);
+  klaunch(kern, dim3(gemm_blocks + reduce_blocks), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 301 : 300), flops, grp, rg, reduce_blocks);
   return hipGetLastError();
 }
 
