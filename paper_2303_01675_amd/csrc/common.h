@@ -26,8 +26,19 @@ template <> __device__ __forceinline__ float from_f<float>(float v) { return v; 
 template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return (bf16_t)v; }
 
 // 8 consecutive elements of T <-> 8 floats, vector loads (16 B for bf16, 2 x 16 B for fp32).
+// eight values as they come from memory: loaded now, converted where they are first used (a load whose
+// result is converted at once cannot be kept in flight across other work)
+template <typename T> struct Raw8;
+template <> struct Raw8<float> { float4 a, b; };
+template <> struct Raw8<bf16_t> { bf16x8 v; };
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {
+  static __device__ __forceinline__ Raw8<float> load_raw(const float* p) {
+    Raw8<float> r; r.a = *reinterpret_cast<const float4*>(p); r.b = *reinterpret_cast<const float4*>(p + 4); return r;
+  }
+  static __device__ __forceinline__ void unpack(const Raw8<float>& r, float (&v)[8]) {
+    v[0] = r.a.x; v[1] = r.a.y; v[2] = r.a.z; v[3] = r.a.w; v[4] = r.b.x; v[5] = r.b.y; v[6] = r.b.z; v[7] = r.b.w;
+  }
   static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
     const float4 a = *reinterpret_cast<const float4*>(p);
     const float4 b = *reinterpret_cast<const float4*>(p + 4);
@@ -39,6 +50,13 @@ template <> struct Vec8<float> {
   }
 };
 template <> struct Vec8<bf16_t> {
+  static __device__ __forceinline__ Raw8<bf16_t> load_raw(const bf16_t* p) {
+    Raw8<bf16_t> r; r.v = *reinterpret_cast<const bf16x8*>(p); return r;
+  }
+  static __device__ __forceinline__ void unpack(const Raw8<bf16_t>& r, float (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (float)r.v[i];
+  }
   static __device__ __forceinline__ void load(const bf16_t* p, float (&v)[8]) {
     const bf16x8 a = *reinterpret_cast<const bf16x8*>(p);
 #pragma unroll

@@ -134,18 +134,38 @@ __global__ void __launch_bounds__(256) ln_bwd_fused_kernel(const T* __restrict__
     for (int e = 0; e < 8; e++) { sb[i][e] = 0.f; sg[i][e] = 0.f; gm[i][e] = 0.f; }
     if (c < nchunks) Vec8<T>::load(gamma + c * 8, gm[i]);
   }
+  // The loads of a wave's next row are in flight while it works on the current one (and the residual gradient
+  // comes in with the row, not after the row sums): a wave has only a few rows, one after the other, and
+  // every wait for memory it cannot overlap is time the whole kernel waits.
+  struct RowIn { Raw8<T> x[NCH], g[NCH], r[NCH]; float mu, rs; };
+  // every lane issues the same number of loads whatever its columns and whether or not there is a residual
+  // gradient (lanes past the end re-read the last chunk, no residual re-reads x; neither value is used): the
+  // compiler can then count the loads in flight and wait for the current row's only
+  const T* rsrc = dres != nullptr ? dres : x;
+  auto fetch = [&](int row, RowIn& in) {
+    in.mu = mean[row]; in.rs = rstd[row];
+#pragma unroll
+    for (int i = 0; i < NCH; i++) {
+      const size_t off = (size_t)row * H + min(lane + 64 * i, nchunks - 1) * 8;
+      in.x[i] = Vec8<T>::load_raw(x + off);
+      in.g[i] = Vec8<T>::load_raw(dy + off);
+      in.r[i] = Vec8<T>::load_raw(rsrc + off);
+    }
+  };
+  RowIn cur, nxt;
+  if (r0 + wave < r1) fetch(r0 + wave, cur);
   for (int row = r0 + wave; row < r1; row += 4) {
-    const float mu = mean[row], rs = rstd[row];
-    const T* xr = x + (size_t)row * H;
-    const T* dyr = dy + (size_t)row * H;
+    const bool more = row + 4 < r1;
+    fetch(more ? row + 4 : row, nxt);               // the last turn re-reads its own row (in bounds, unused)
+    const float mu = cur.mu, rs = cur.rs;
     float xh[NCH][8], g[NCH][8];
     float s1 = 0.f, s2 = 0.f;
 #pragma unroll
     for (int i = 0; i < NCH; i++) {
       const int c = lane + 64 * i;
       if (c < nchunks) {
-        Vec8<T>::load(xr + c * 8, xh[i]);
-        Vec8<T>::load(dyr + c * 8, g[i]);
+        Vec8<T>::unpack(cur.x[i], xh[i]);
+        Vec8<T>::unpack(cur.g[i], g[i]);
 #pragma unroll
         for (int e = 0; e < 8; e++) {
           xh[i][e] = (xh[i][e] - mu) * rs;
@@ -169,13 +189,14 @@ __global__ void __launch_bounds__(256) ln_bwd_fused_kernel(const T* __restrict__
         for (int e = 0; e < 8; e++) o[e] = rs * (g[i][e] - m1 - xh[i][e] * m2);
         if (dres != nullptr) {
           float r[8];
-          Vec8<T>::load(dres + (size_t)row * H + c * 8, r);
+          Vec8<T>::unpack(cur.r[i], r);
 #pragma unroll
           for (int e = 0; e < 8; e++) o[e] += r[e];
         }
         Vec8<T>::store(dxr + c * 8, o);
       }
     }
+    if (more) cur = nxt;
   }
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
