@@ -14,4 +14,7 @@ Modules
                 (timing only: "parity unpinned" beyond its closed-form checks)
   tuner       cost model and online choice of k (moving averages of measured
               transfer times, estimated iteration length per candidate plan)
+  pipeline    S stages, each under its own kFkB plan: the order one executor
+              issues their ops in, one iteration, a timing model (the timing
+              is "parity unpinned" beyond its closed forms)
 """
