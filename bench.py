@@ -56,6 +56,10 @@ def main():
     ap.add_argument("--adaptive", action="store_true",
                     help="also time the same steps under the tuner (run_kFkB_adaptive: moving averages of the measured "
                          "transfer times, k re-chosen every 2 iterations among the workload's k values)")
+    ap.add_argument("--pipeline-stages", type=int, default=0,
+                    help="also time the same iteration run as a pipeline of this many virtual stages on the one GPU "
+                         "(run_pipeline_kFkB: every stage under its own kFkB plan, boundary crossings delayed by the "
+                         "workload's delay model); reported under \"pipeline_sim\", the headline value is unchanged")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -90,7 +94,7 @@ def main():
         blocks = [one] * L
     else:
         blocks = synth.stage_weights(L, H, 4 * H, w["dtype"])
-    st = kf.StageBuffers(blocks, dt, heads, T, b, M, M if 0 in w["ks"] else max(w["ks"]))
+    st = kf.StageBuffers(blocks, dt, heads, T, b, M, M if (0 in w["ks"] or args.pipeline_stages > 1) else max(w["ks"]))
     distinct = 2 if w.get("tiled") else M
     cache = {}
     for mb in range(M):
@@ -147,6 +151,49 @@ def main():
                         tflops_megatron=flops_iter_megatron * args.steps / dt_s / 1e12,
                         activation_gb=kf.stage_activation_bytes(k, M) / 1e9)
     best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
+
+    pipeline_sim = None
+    if args.pipeline_stages > 1:
+        S = args.pipeline_stages
+        wire = torch.empty(kf.stage_pipeline_bytes(S, M), dtype=torch.uint8, device="cuda")
+        kf.stage_sync()
+        kf.stage_pipeline_bind(wire, S, M)
+
+        def boundary_delays(step_index, n_steps):
+            n = (S - 1) * M
+            if delay_model == "none":
+                return None, None
+            if delay_model == "lognormal":
+                return tuple(synth.delays_lognormal(n, 2.0, 0.5, seed=9000 + 2 * step_index + i) for i in range(2))
+            if delay_model == "bimodal":
+                return tuple(synth.delays_bimodal(n, 0.5, 10.0, 0.7, seed=9000 + 2 * step_index + i) for i in range(2))
+            d = np.tile(synth.delays_drift(M, step_index, n_steps, 20.0), S - 1)
+            return d, d
+
+        def pstep(k, i=0):
+            set_delays(i, args.steps)
+            kf.stage_set_pipeline_delays(*boundary_delays(i, args.steps))
+            kf.stage_zero_grads()
+            kf.run_pipeline_kFkB(k)
+
+        pk = {}
+        for k in sorted({k for k in per_k} | {M}):
+            for _ in range(args.warmup):
+                pstep(k)
+            kf.stage_sync()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                pstep(k, i)
+            kf.stage_sync()
+            dt_s = time.perf_counter() - t0
+            peaks = [kf.kfkb_peak_live(k, M, min(S - 1 - v, -(-M // k))) for v in range(S)]
+            pk[str(k)] = dict(ms_per_step=1e3 * dt_s / args.steps, samples_per_s=M * b * args.steps / dt_s,
+                              peak_live_per_stage=peaks)
+        kf.stage_set_pipeline_delays(None, None)
+        pipeline_sim = dict(stages=S, blocks_per_stage=L // S, delay=delay_model, per_k=pk,
+                            note="S virtual stages share the one GPU: total work equals the single stage's, so the "
+                                 "figures show what the schedule and the boundary delays cost, not a pipeline speed-up")
 
     adaptive = None
     if args.adaptive:
@@ -247,7 +294,7 @@ def main():
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
         "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,
         "per_k": {str(k): v for k, v in per_k.items()},
-        "adaptive": adaptive, "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
+        "adaptive": adaptive, "pipeline_sim": pipeline_sim, "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
     }
     st.close()
     if args.copy_calibration:

@@ -251,6 +251,51 @@ typedef struct kfkb_kernel_stat {
 int kfkb_profile(int enable);
 int kfkb_profile_report(kfkb_kernel_stat_t* out, int cap);
 
+/* ---- the pipeline of S stages, rehearsed on the one GPU (paper Sections 2.2, 3.2.1, 5) ------------------- *
+ * The bound stage's L blocks are cut into S consecutive virtual stages of L / S blocks.  Virtual stage v runs
+ * its own kFkB plan with w = min(S-1-v, ceil(M/k)) warm-up groups (so earlier stages hold more live
+ * micro-batches), forwards a micro-batch after stage v-1 has and backwards it after stage v+1 has.  An
+ * activation crosses a boundary as a delayed device-to-device copy on the send stream, a gradient on the
+ * receive stream; the delay counts from the moment the producing op finished.  Stage 0 receives X and sends dX,
+ * stage S-1 sends Y and receives dY exactly as the single stage does (stage_set_delays).  The result (Y, dX,
+ * gradient accumulators) equals that of run_kFkB on the whole stage bit for bit.
+ * The GPU issues the ops of all stages in list-schedule order: every stage imagined on a device of its own,
+ * forward 1 time unit, backward 2, transfers free; the op that would start earliest goes next, ties go to
+ * the later stage (the paper does not say how one executor should order S stages; this is this library's rule). */
+typedef struct kfkb_pipe_op {
+  int stage;             /* virtual stage, 0 .. S-1 */
+  int op;                /* KFKB_OP_F or KFKB_OP_B */
+  int mb;                /* micro-batch index */
+  double t_start_ms;     /* as in kfkb_op_t; zero from kfkb_pipeline_schedule */
+  double t_end_ms;
+} kfkb_pipe_op_t;
+
+/* Host only: the 2*S*M ops of one iteration in the order they are issued.  Returns their number or < 0. */
+int kfkb_pipeline_schedule(int num_stages, int k, int num_microbatches, kfkb_pipe_op_t* out, int cap);
+
+/* Bytes of device memory the boundary tensors of S stages and M micro-batches need (3 (S-1) M tensors of
+ * b*T*H elements and their clock stamps); 0 before stage_init. */
+size_t stage_pipeline_bytes(int num_stages, int num_microbatches);
+
+/* Borrows `buffer` (device, 256-byte aligned, >= stage_pipeline_bytes) until the next stage_bind,
+ * stage_pipeline_bind or stage_destroy.  Needs stage_bind with a workspace that holds one activation slot per
+ * micro-batch (stage_workspace_bytes(M) on a stage configured as the last one), L % S == 0, M <= the
+ * configured maximum.  KFKB_E_STATE / _ARG / _MEMLIMIT otherwise. */
+int stage_pipeline_bind(void* buffer, size_t bytes, int num_stages, int num_microbatches);
+
+/* Injected delay in ns per boundary crossing: forward_ns[v * M + mb] for the activation of micro-batch mb
+ * from stage v to v+1, backward_ns[v * M + mb] for its gradient from v+1 to v, v < S-1; NULL = none.
+ * Host arrays, copied. */
+int stage_set_pipeline_delays(const int64_t* forward_ns, const int64_t* backward_ns);
+
+/* Enqueues one iteration of the S-stage pipeline with group size k (1 <= k <= M) and returns; stage_sync waits.
+ * Accumulates into grad_accum, writes host_outputs and host_input_grads like run_kFkB. */
+int run_pipeline_kFkB(int k);
+
+/* The ops of the last run_pipeline_kFkB in the order they were issued, with their measured times.  Call after
+ * stage_sync.  Returns the number written. */
+int stage_get_pipeline_order(kfkb_pipe_op_t* out, int cap);
+
 /* ---- per-kernel entry points (building blocks, used by unit tests and kernel benchmarks) -- *
  * All pointers are device pointers; dtype is KFKB_F32 or KFKB_BF16 and names the storage type *
  * of every "T" buffer; `stream` is a hipStream_t (NULL = default stream).  Calls enqueue only. */

@@ -12,6 +12,8 @@ __all__ = [
     "kfkb_schedule", "kfkb_peak_live", "kfkb_activation_bytes_per_microbatch",
     "kfkb_enumerate_candidates", "kfkb_predict_iteration_ms", "kfkb_tuner_config", "kfkb_tuner_set_compute_profile", "kfkb_tuner_push_sample", "kfkb_tuner_next_k",
     "stage_get_transfer_ms", "stage_tuner_calibrate", "run_kFkB_adaptive",
+    "kfkb_pipeline_schedule", "stage_pipeline_bytes", "stage_pipeline_bind", "stage_set_pipeline_delays",
+    "run_pipeline_kFkB", "stage_get_pipeline_order",
     "stage_config", "stage_init", "stage_param_count", "stage_activation_bytes", "stage_workspace_bytes",
     "stage_bind", "stage_set_delays", "stage_refresh_weights", "stage_forward", "stage_backward", "run_kFkB",
     "stage_last_k", "stage_side_streams_overlap", "stage_zero_grads", "stage_set_wgrad_stream", "stage_set_compute_lanes", "stage_sync", "stage_sync_timeout", "stage_destroy", "stage_get_order",
@@ -48,6 +50,10 @@ class _KernelStat(C.Structure):
 
 class _Op(C.Structure):
     _fields_ = [("op", C.c_int), ("mb", C.c_int), ("t_start_ms", C.c_double), ("t_end_ms", C.c_double)]
+
+
+class _PipeOp(C.Structure):
+    _fields_ = [("stage", C.c_int), ("op", C.c_int), ("mb", C.c_int), ("t_start_ms", C.c_double), ("t_end_ms", C.c_double)]
 
 
 _LIB = None
@@ -102,6 +108,12 @@ def load_library():
         "stage_sync_timeout": (i, [C.c_double]),
         "stage_destroy": (i, []),
         "stage_get_order": (i, [C.POINTER(_Op), i]),
+        "kfkb_pipeline_schedule": (i, [i, i, i, C.POINTER(_PipeOp), i]),
+        "stage_pipeline_bytes": (sz, [i, i]),
+        "stage_pipeline_bind": (i, [vp, sz, i, i]),
+        "stage_set_pipeline_delays": (i, [C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+        "run_pipeline_kFkB": (i, [i]),
+        "stage_get_pipeline_order": (i, [C.POINTER(_PipeOp), i]),
         "stage_last_run_ms": (C.c_double, []),
         "kfkb_profile": (i, [i]),
         "kfkb_profile_report": (i, [C.POINTER(_KernelStat), i]),
@@ -347,6 +359,44 @@ def stage_get_order(cap=4096):
     buf = (_Op * cap)()
     n = _check(load_library().stage_get_order(buf, cap))
     return [("F" if buf[j].op == OP_F else "B", buf[j].mb, buf[j].t_start_ms, buf[j].t_end_ms) for j in range(n)]
+
+
+def kfkb_pipeline_schedule(num_stages, k, num_microbatches):
+    cap = 2 * max(num_stages, 1) * max(num_microbatches, 1)
+    buf = (_PipeOp * cap)()
+    n = _check(load_library().kfkb_pipeline_schedule(num_stages, k, num_microbatches, buf, cap))
+    return [(buf[j].stage, "F" if buf[j].op == OP_F else "B", buf[j].mb) for j in range(n)]
+
+
+def stage_pipeline_bytes(num_stages, num_microbatches):
+    return load_library().stage_pipeline_bytes(num_stages, num_microbatches)
+
+
+def stage_pipeline_bind(buffer, num_stages, num_microbatches):
+    nbytes = buffer.numel() * buffer.element_size() if buffer is not None else 0
+    return _check(load_library().stage_pipeline_bind(_ptr(buffer), nbytes, num_stages, num_microbatches))
+
+
+def stage_set_pipeline_delays(forward_ns=None, backward_ns=None):
+    keep = []
+
+    def arr(a):
+        if a is None:
+            return None
+        a = np.ascontiguousarray(a, dtype=np.int64)
+        keep.append(a)
+        return a.ctypes.data_as(C.POINTER(C.c_int64))
+    return _check(load_library().stage_set_pipeline_delays(arr(forward_ns), arr(backward_ns)))
+
+
+def run_pipeline_kFkB(k):
+    return _check(load_library().run_pipeline_kFkB(k))
+
+
+def stage_get_pipeline_order(cap=16384):
+    buf = (_PipeOp * cap)()
+    n = _check(load_library().stage_get_pipeline_order(buf, cap))
+    return [(buf[j].stage, "F" if buf[j].op == OP_F else "B", buf[j].mb, buf[j].t_start_ms, buf[j].t_end_ms) for j in range(n)]
 
 
 def stage_last_run_ms():

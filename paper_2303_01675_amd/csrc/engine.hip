@@ -375,6 +375,11 @@ struct ActiveOp {
   hipStream_t w_stream = nullptr; // where W steps of this op went, if not to the op's own stream
   int out_buf = -1;               // Y buffer (forward) or dX buffer (backward)
   const char* cur = nullptr;      // forward: input of the next block; backward: output gradient of the next block
+  // an op over blocks [first, ...) of a stage that has been cut into virtual stages: where the input of block
+  // `first` lies and where the gradient with respect to it goes (null: the stage's own rule)
+  int first = 0;
+  const char* x_first = nullptr;
+  char* dx_first = nullptr;
 };
 
 int forward_block(ActiveOp& a) {
@@ -416,8 +421,8 @@ int backward_block(ActiveOp& a) {
   StashView v = view(s, st.stash, l);
   const bool bt = s.dt == DT_BF16;                      // bf16 input-gradient products read the chunk-major copies
   WtView w = bt ? wt_view(s, l) : WtView{};
-  const char* x = (l == 0) ? s.xs.buf[st.x_slot] : view(s, st.stash, l - 1).y;
-  char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : ln.t_dxr[seq % 3];
+  const char* x = (l == 0) ? s.xs.buf[st.x_slot] : (a.x_first != nullptr && l == a.first) ? a.x_first : view(s, st.stash, l - 1).y;
+  char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : (a.dx_first != nullptr && l == a.first) ? a.dx_first : ln.t_dxr[seq % 3];
   // where the W step of this block goes: the other lane's stream, beside this chain, when that lane has nothing
   // of its own to do; behind the chain otherwise (the other lane's op then fills the chip beside it)
   hipStream_t qw = !s.wgrad_overlap ? q : s.sw != nullptr ? s.sw : !a.other_busy ? s.lane[1 - a.lane].s : q;
@@ -799,6 +804,199 @@ int make_events(std::vector<hipEvent_t>& v, int n) {
   return 0;
 }
 
+// ---- S virtual stages on the one GPU (the multi-stage pipeline, rehearsed on one device) ---------------------
+// The stage's L blocks are cut into S consecutive virtual stages of L / S blocks; virtual stage v follows its own
+// kFkB plan with w = min(S-1-v, G) warm-up groups, forwards a micro-batch after stage v-1 has and backwards it
+// after stage v+1 has.  Activations cross a boundary as a delayed device-to-device copy on the send stream,
+// gradients on the receive stream; a delay counts from the moment the producer finished (a device clock stamp),
+// so delays of different boundaries overlap as they would on separate links while copies stay FIFO per stream.
+// The one GPU issues the ops of all stages in list-schedule order: every stage imagined on a device of its own,
+// forward 1 time unit, backward 2, transfers free; the op that would start earliest goes next, ties to the later
+// stage.  Micro-batch mb keeps activation slot mb for the whole iteration (the workspace must hold M slots).
+struct PipeEntry { int stage, op, mb; };
+
+int pipeline_list_schedule(int S, int k, int M, std::vector<PipeEntry>& out) {
+  std::vector<std::vector<kfkb_op_t>> orders(S);
+  const int G = (M + k - 1) / k;
+  for (int v = 0; v < S; v++) build_order(k, M, std::min(S - 1 - v, G), orders[v]);
+  std::vector<size_t> nxt(S, 0);
+  std::vector<long long> clock(S, 0);
+  std::vector<long long> fdone((size_t)S * M, -1), bdone((size_t)S * M, -1);
+  out.clear();
+  const size_t total = (size_t)2 * M * S;
+  while (out.size() < total) {
+    int best_v = -1; long long best_start = 0;
+    for (int v = 0; v < S; v++) {
+      if (nxt[v] >= orders[v].size()) continue;
+      const kfkb_op_t& o = orders[v][nxt[v]];
+      long long ready = 0;
+      if (o.op == KFKB_OP_F) {
+        if (v > 0) { const long long d = fdone[(size_t)(v - 1) * M + o.mb]; if (d < 0) continue; ready = d; }
+      } else {
+        const long long d = fdone[(size_t)v * M + o.mb];
+        if (d < 0) continue;
+        ready = d;
+        if (v < S - 1) { const long long e = bdone[(size_t)(v + 1) * M + o.mb]; if (e < 0) continue; ready = std::max(ready, e); }
+      }
+      const long long start = std::max(clock[v], ready);
+      if (best_v < 0 || start < best_start || (start == best_start && v > best_v)) { best_v = v; best_start = start; }
+    }
+    if (best_v < 0) return fail(KFKB_E_STATE, "pipeline plans dead-lock (S=%d k=%d M=%d)", S, k, M);
+    const kfkb_op_t& o = orders[best_v][nxt[best_v]++];
+    const long long fin = best_start + (o.op == KFKB_OP_F ? 1 : 2);
+    clock[best_v] = fin;
+    (o.op == KFKB_OP_F ? fdone : bdone)[(size_t)best_v * M + o.mb] = fin;
+    out.push_back(PipeEntry{best_v, o.op, o.mb});
+  }
+  return 0;
+}
+
+struct PipeSim {
+  bool bound = false;
+  int S = 0, M = 0;
+  char* wire = nullptr;                       // [3][S-1][M] boundary tensors: forward copy, gradient as produced, gradient copy
+  long long* stamps = nullptr;                // [2][S-1][M] device clock when the producer finished
+  std::vector<hipEvent_t> ev_f0, ev_f1, ev_b0, ev_b1, ev_w, ev_tf, ev_tb;
+  std::vector<int64_t> dl_f, dl_b;            // [S-1][M]
+  std::vector<PipeEntry> log;
+  hipEvent_t ev_join[4] = {};
+  size_t act() const { return align_up(g.n * g.esz); }
+  char* tensor(int which, int boundary, int mb) const { return wire + (((size_t)which * (S - 1) + boundary) * M + mb) * act(); }
+  long long* stamp(int which, int boundary, int mb) const { return stamps + ((size_t)which * (S - 1) + boundary) * M + mb; }
+};
+PipeSim gp;
+
+// Drops the pipeline binding.  Its events may still be named as "last reader" of a pooled buffer: everything is
+// waited for first and those references are cleared, so nothing keeps a handle to a destroyed event.
+void pipeline_release() {
+  if (gp.bound && g.inited) {
+    for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) (void)hipStreamSynchronize(q);
+    if (g.sw != nullptr) (void)hipStreamSynchronize(g.sw);
+    for (Pool* p : {&g.xs, &g.dys, &g.ys, &g.dxs}) std::fill(p->release.begin(), p->release.end(), nullptr);
+    std::fill(g.stash_release.begin(), g.stash_release.end(), nullptr);
+    g.last_done = nullptr;
+  }
+  for (auto* v : {&gp.ev_f0, &gp.ev_f1, &gp.ev_b0, &gp.ev_b1, &gp.ev_w, &gp.ev_tf, &gp.ev_tb})
+    for (auto e : *v) (void)hipEventDestroy(e);
+  for (auto e : gp.ev_join) if (e) (void)hipEventDestroy(e);
+  gp = PipeSim{};
+}
+
+int pipe_begin_forward(int v, int mbi, int lane, ActiveOp& a) {
+  MbState& st = g.mb[mbi];
+  const int S = gp.S, M = gp.M, Ls = g.L / S;
+  hipStream_t q = g.lane[lane].s;
+  int ybuf = -1;
+  if (v == S - 1 && g.ys.free_list.empty()) return 1;
+  if (v == 0) {
+    if (!st.x_issued) {
+      const int rc = issue_recv(KFKB_OP_F, mbi);
+      if (rc != 0) return rc;
+    }
+    HIPCHK(hipStreamWaitEvent(q, g.ev_x[mbi], 0));
+  } else {
+    HIPCHK(hipStreamWaitEvent(q, gp.ev_tf[(size_t)(v - 1) * M + mbi], 0));
+  }
+  if (v == S - 1) {
+    ybuf = g.ys.take();
+    if (g.ys.release[ybuf]) HIPCHK(hipStreamWaitEvent(q, g.ys.release[ybuf], 0));
+  }
+  HIPCHK(hipEventRecord(gp.ev_f0[(size_t)v * M + mbi], q));
+  gp.log.push_back(PipeEntry{v, KFKB_OP_F, mbi});
+  a = ActiveOp{};
+  a.op = KFKB_OP_F; a.mb = mbi; a.lane = lane; a.next = v * Ls; a.left = Ls; a.out_buf = ybuf; a.first = v * Ls;
+  a.cur = v == 0 ? g.xs.buf[st.x_slot] : gp.tensor(0, v - 1, mbi);
+  return 0;
+}
+
+int pipe_end_forward(ActiveOp& a, int v) {
+  const int mbi = a.mb, S = gp.S, M = gp.M, Ls = g.L / S;
+  MbState& st = g.mb[mbi];
+  hipStream_t q = g.lane[a.lane].s;
+  const size_t bytes = g.n * g.esz;
+  if (v == S - 1) {
+    HIPCHK(hipEventRecord(gp.ev_f1[(size_t)v * M + mbi], q));
+    HIPCHK(hipStreamWaitEvent(g.ss, gp.ev_f1[(size_t)v * M + mbi], 0));
+    HIPCHK(hipEventRecord(g.ev_t0[2][mbi], g.ss));
+    HIPCHK(launch_delay(g.dl_y[mbi], g.ss));
+    HIPCHK(hipMemcpyAsync(g.h_out + (size_t)mbi * bytes, g.ys.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
+    HIPCHK(hipEventRecord(g.ev_ys[mbi], g.ss));
+    g.ys.give(a.out_buf, g.ev_ys[mbi]);
+    st.fwd_done = true;
+    return 0;
+  }
+  HIPCHK(launch_clock_stamp(gp.stamp(0, v, mbi), q));
+  HIPCHK(hipEventRecord(gp.ev_f1[(size_t)v * M + mbi], q));
+  HIPCHK(hipStreamWaitEvent(g.ss, gp.ev_f1[(size_t)v * M + mbi], 0));
+  HIPCHK(launch_delay_since(gp.stamp(0, v, mbi), gp.dl_f[(size_t)v * M + mbi], g.ss));
+  HIPCHK(hipMemcpyAsync(gp.tensor(0, v, mbi), view(g, st.stash, (v + 1) * Ls - 1).y, bytes, hipMemcpyDeviceToDevice, g.ss));
+  HIPCHK(hipEventRecord(gp.ev_tf[(size_t)v * M + mbi], g.ss));
+  return 0;
+}
+
+int pipe_begin_backward(int v, int mbi, int lane, ActiveOp& a) {
+  MbState& st = g.mb[mbi];
+  const int S = gp.S, M = gp.M, Ls = g.L / S;
+  hipStream_t q = g.lane[lane].s;
+  if (v == 0 && g.dxs.free_list.empty()) return 1;
+  if (v == S - 1) {
+    if (!st.dy_issued) {
+      const int rc = issue_recv(KFKB_OP_B, mbi);
+      if (rc != 0) return rc;
+    }
+    HIPCHK(hipStreamWaitEvent(q, g.ev_dy[mbi], 0));
+  } else {
+    HIPCHK(hipStreamWaitEvent(q, gp.ev_tb[(size_t)v * M + mbi], 0));
+  }
+  HIPCHK(hipStreamWaitEvent(q, gp.ev_f1[(size_t)v * M + mbi], 0));      // its forward may have run on the other lane
+  int dxbuf = -1;
+  if (v == 0) {
+    dxbuf = g.dxs.take();
+    if (g.dxs.release[dxbuf]) HIPCHK(hipStreamWaitEvent(q, g.dxs.release[dxbuf], 0));
+  }
+  HIPCHK(hipEventRecord(gp.ev_b0[(size_t)v * M + mbi], q));
+  gp.log.push_back(PipeEntry{v, KFKB_OP_B, mbi});
+  a = ActiveOp{};
+  a.op = KFKB_OP_B; a.mb = mbi; a.lane = lane; a.next = (v + 1) * Ls - 1; a.left = Ls; a.out_buf = dxbuf; a.first = v * Ls;
+  a.cur = v == S - 1 ? g.dys.buf[st.dy_slot] : gp.tensor(2, v, mbi);
+  if (v > 0) { a.x_first = gp.tensor(0, v - 1, mbi); a.dx_first = gp.tensor(1, v - 1, mbi); }
+  return 0;
+}
+
+int pipe_end_backward(ActiveOp& a, int v) {
+  const int mbi = a.mb, S = gp.S, M = gp.M;
+  MbState& st = g.mb[mbi];
+  hipStream_t q = g.lane[a.lane].s;
+  const size_t bytes = g.n * g.esz;
+  if (v > 0) HIPCHK(launch_clock_stamp(gp.stamp(1, v - 1, mbi), q));
+  hipEvent_t ev_b1 = gp.ev_b1[(size_t)v * M + mbi];
+  HIPCHK(hipEventRecord(ev_b1, q));
+  hipEvent_t ev_done = ev_b1;                          // after it nothing of this op reads its operands any more
+  if (a.w_stream != nullptr) {
+    HIPCHK(hipStreamWaitEvent(a.w_stream, ev_b1, 0));
+    HIPCHK(hipEventRecord(gp.ev_w[(size_t)v * M + mbi], a.w_stream));
+    ev_done = gp.ev_w[(size_t)v * M + mbi];
+  }
+  if (v == S - 1) { g.dys.give(st.dy_slot, ev_done); st.dy_slot = -1; }
+  if (v == 0) {
+    HIPCHK(hipStreamWaitEvent(g.ss, ev_b1, 0));
+    HIPCHK(hipEventRecord(g.ev_t0[3][mbi], g.ss));
+    HIPCHK(launch_delay(g.dl_dx[mbi], g.ss));
+    HIPCHK(hipMemcpyAsync(g.h_ingrad + (size_t)mbi * bytes, g.dxs.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
+    HIPCHK(hipEventRecord(g.ev_dxs[mbi], g.ss));
+    g.dxs.give(a.out_buf, g.ev_dxs[mbi]);
+    g.xs.give(st.x_slot, ev_done);
+    st.x_slot = -1;
+    st.bwd_done = true;
+  } else {
+    HIPCHK(hipStreamWaitEvent(g.sr, ev_b1, 0));
+    HIPCHK(launch_delay_since(gp.stamp(1, v - 1, mbi), gp.dl_b[(size_t)(v - 1) * M + mbi], g.sr));
+    HIPCHK(hipMemcpyAsync(gp.tensor(2, v - 1, mbi), gp.tensor(1, v - 1, mbi), bytes, hipMemcpyDeviceToDevice, g.sr));
+    HIPCHK(hipEventRecord(gp.ev_tb[(size_t)(v - 1) * M + mbi], g.sr));
+  }
+  g.last_done = ev_done;
+  return 0;
+}
 }  // namespace
 
 // =================================================================================================
@@ -960,6 +1158,7 @@ int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum, const
   g.stash_release.assign(c.n_stash, nullptr);
   reset_iteration_state();
   g.epoch_valid = false; g.run_timed = false; g.log.clear();
+  pipeline_release();                                 // a pipeline binding refers to the previous workspace
   g.bound = true;
   TRY(refresh_weights());
   HIPCHK(hipStreamSynchronize(g.lane[0].s));
@@ -1250,6 +1449,137 @@ int run_kFkB_adaptive(int num_microbatches, size_t mem_limit) {
   return k;
 }
 
+
+int kfkb_pipeline_schedule(int num_stages, int k, int num_microbatches, kfkb_pipe_op_t* out, int cap) {
+  const int S = num_stages, M = num_microbatches;
+  if (S < 1 || M < 1 || k < 1 || k > M) return fail(KFKB_E_ARG, "kfkb_pipeline_schedule: need S >= 1 and 1 <= k <= M (S=%d k=%d M=%d)", S, k, M);
+  if ((long long)2 * S * M > cap || out == nullptr) return fail(KFKB_E_ARG, "kfkb_pipeline_schedule: out holds %d ops, %lld needed", cap, (long long)2 * S * M);
+  std::vector<PipeEntry> sched;
+  TRY(pipeline_list_schedule(S, k, M, sched));
+  for (size_t i = 0; i < sched.size(); i++) out[i] = kfkb_pipe_op_t{sched[i].stage, sched[i].op, sched[i].mb, 0.0, 0.0};
+  return (int)sched.size();
+}
+
+size_t stage_pipeline_bytes(int num_stages, int num_microbatches) {
+  if (!g.inited || num_stages < 1 || num_microbatches < 1) return 0;
+  const size_t cells = (size_t)(num_stages - 1) * num_microbatches;
+  return 3 * cells * align_up(g.n * g.esz) + align_up(2 * cells * sizeof(long long)) + 256;
+}
+
+int stage_pipeline_bind(void* buffer, size_t bytes, int num_stages, int num_microbatches) {
+  const int S = num_stages, M = num_microbatches;
+  if (!g.bound) return fail(KFKB_E_STATE, "stage_pipeline_bind before stage_bind");
+  if (S < 1 || M < 1 || M > g.Mmax) return fail(KFKB_E_ARG, "stage_pipeline_bind: need S >= 1 and 1 <= M <= %d (S=%d M=%d)", g.Mmax, S, M);
+  if (g.L % S != 0) return fail(KFKB_E_ARG, "stage_pipeline_bind: %d blocks do not divide into %d stages", g.L, S);
+  if (g.n_stash < M) return fail(KFKB_E_MEMLIMIT, "stage_pipeline_bind: the bound workspace holds %d activation slots, %d micro-batches need one each", g.n_stash, M);
+  if (S > 1 && (buffer == nullptr || ((uintptr_t)buffer & 255) != 0)) return fail(KFKB_E_ARG, "stage_pipeline_bind: buffer must be non-null and 256-byte aligned");
+  if (bytes < stage_pipeline_bytes(S, M)) return fail(KFKB_E_MEMLIMIT, "stage_pipeline_bind: %zu bytes given, stage_pipeline_bytes(%d, %d) = %zu", bytes, S, M, stage_pipeline_bytes(S, M));
+  if (live_count() != 0) return fail(KFKB_E_STATE, "stage_pipeline_bind while micro-batches are live");
+  TRY(stage_sync());
+  pipeline_release();
+  gp.S = S; gp.M = M;
+  const size_t cells = (size_t)(S - 1) * M;
+  gp.wire = (char*)buffer;
+  gp.stamps = reinterpret_cast<long long*>(gp.wire + 3 * cells * align_up(g.n * g.esz));
+  TRY(make_events(gp.ev_f0, S * M)); TRY(make_events(gp.ev_f1, S * M));
+  TRY(make_events(gp.ev_b0, S * M)); TRY(make_events(gp.ev_b1, S * M)); TRY(make_events(gp.ev_w, S * M));
+  TRY(make_events(gp.ev_tf, (int)cells)); TRY(make_events(gp.ev_tb, (int)cells));
+  for (auto& e : gp.ev_join) HIPCHK(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+  gp.dl_f.assign(cells, 0); gp.dl_b.assign(cells, 0);
+  gp.bound = true;
+  return 0;
+}
+
+int stage_set_pipeline_delays(const int64_t* forward_ns, const int64_t* backward_ns) {
+  if (!gp.bound) return fail(KFKB_E_STATE, "stage_set_pipeline_delays before stage_pipeline_bind");
+  for (size_t i = 0; i < gp.dl_f.size(); i++) {
+    gp.dl_f[i] = forward_ns ? std::max<int64_t>(0, forward_ns[i]) : 0;
+    gp.dl_b[i] = backward_ns ? std::max<int64_t>(0, backward_ns[i]) : 0;
+  }
+  return 0;
+}
+
+int run_pipeline_kFkB(int k) {
+  if (!gp.bound || !g.bound) return fail(KFKB_E_STATE, "run_pipeline_kFkB before stage_pipeline_bind");
+  const int S = gp.S, M = gp.M;
+  if (k < 1 || k > M) return fail(KFKB_E_ARG, "run_pipeline_kFkB: need 1 <= k <= M (k=%d M=%d)", k, M);
+  if (live_count() != 0) return fail(KFKB_E_STATE, "run_pipeline_kFkB while micro-batches are live");
+  std::vector<PipeEntry> sched;
+  TRY(pipeline_list_schedule(S, k, M, sched));
+  // nothing of an earlier iteration may still be running: every stream waits for every other
+  hipStream_t all[4] = {g.lane[0].s, g.lane[1].s, g.ss, g.sr};
+  if (g.sw != nullptr) { HIPCHK(hipEventRecord(g.ev_sw_tail, g.sw)); for (hipStream_t q : all) HIPCHK(hipStreamWaitEvent(q, g.ev_sw_tail, 0)); }
+  for (int i = 0; i < 4; i++) HIPCHK(hipEventRecord(gp.ev_join[i], all[i]));
+  for (int i = 0; i < 4; i++)
+    for (int j = 0; j < 4; j++) if (i != j) HIPCHK(hipStreamWaitEvent(all[i], gp.ev_join[j], 0));
+  reset_iteration_state();
+  g.stash_free.clear();                                  // micro-batch mb owns activation slot mb
+  for (int mbi = 0; mbi < M; mbi++) { g.mb[mbi].stash = mbi; g.stash_release[mbi] = nullptr; }
+  g.last_k = k;
+  TRY(begin_log_epoch());
+  HIPCHK(hipStreamWaitEvent(g.ss, g.ev_epoch, 0));
+  HIPCHK(hipStreamWaitEvent(g.sr, g.ev_epoch, 0));
+  gp.log.clear();
+  std::vector<char> f_ended((size_t)S * M, 0), b_ended((size_t)S * M, 0);
+  struct Act { ActiveOp a; int stage; };
+  std::vector<Act> act;
+  size_t next = 0;
+  while (next < sched.size() || !act.empty()) {
+    while (next < sched.size() && (int)act.size() < g.lanes) {
+      const PipeEntry e = sched[next];
+      const size_t me = (size_t)e.stage * M + e.mb;
+      bool ready;
+      if (e.op == KFKB_OP_F) ready = e.stage == 0 || f_ended[me - M];
+      else ready = f_ended[me] && (e.stage == S - 1 || b_ended[me + M]);
+      if (!ready) break;                                // its producer is still being enqueued
+      int lane = 0;
+      for (const auto& x : act) if (x.a.lane == lane) lane = 1 - lane;
+      Act n; n.stage = e.stage;
+      const int rc = e.op == KFKB_OP_F ? pipe_begin_forward(e.stage, e.mb, lane, n.a) : pipe_begin_backward(e.stage, e.mb, lane, n.a);
+      if (rc < 0) return rc;
+      if (rc == 1) break;                               // a buffer an op in flight still holds
+      act.push_back(n);
+      next++;
+    }
+    if (act.empty()) return fail(KFKB_E_STATE, "run_pipeline_kFkB: op %zu of the schedule cannot start (stage %d, micro-batch %d)", next, sched[next].stage, sched[next].mb);
+    for (size_t i = 0; i < act.size();) {
+      ActiveOp& a = act[i].a;
+      a.other_busy = act.size() > 1;
+      TRY(a.op == KFKB_OP_F ? forward_block(a) : backward_block(a));
+      if (a.left == 0) {
+        TRY(a.op == KFKB_OP_F ? pipe_end_forward(a, act[i].stage) : pipe_end_backward(a, act[i].stage));
+        (a.op == KFKB_OP_F ? f_ended : b_ended)[(size_t)act[i].stage * M + a.mb] = 1;
+        act.erase(act.begin() + i);
+      } else {
+        i++;
+      }
+    }
+  }
+  hipStream_t q0 = g.lane[0].s;
+  HIPCHK(hipStreamWaitEvent(q0, g.ev_dxs[sched.back().mb], 0));
+  TRY(join_compute_streams(q0));
+  HIPCHK(hipEventRecord(g.ev_run_end, q0));
+  g.run_timed = true;
+  // whoever takes an activation slot next (a single-stage run on the same binding) waits for the end of this run
+  for (int mbi = 0; mbi < M; mbi++) { g.stash_release[mbi] = g.ev_run_end; g.mb[mbi].stash = -1; }
+  return 0;
+}
+
+int stage_get_pipeline_order(kfkb_pipe_op_t* out, int cap) {
+  if (!gp.bound) return fail(KFKB_E_STATE, "stage_get_pipeline_order before stage_pipeline_bind");
+  if (out == nullptr && cap > 0) return fail(KFKB_E_ARG, "stage_get_pipeline_order: null output");
+  const int n = std::min<int>(cap, (int)gp.log.size());
+  for (int i = 0; i < n; i++) {
+    const PipeEntry& e = gp.log[i];
+    const size_t c = (size_t)e.stage * gp.M + e.mb;
+    float t0 = 0.f, t1 = 0.f;
+    HIPCHK(hipEventElapsedTime(&t0, g.ev_epoch, e.op == KFKB_OP_F ? gp.ev_f0[c] : gp.ev_b0[c]));
+    HIPCHK(hipEventElapsedTime(&t1, g.ev_epoch, e.op == KFKB_OP_F ? gp.ev_f1[c] : gp.ev_b1[c]));
+    out[i] = kfkb_pipe_op_t{e.stage, e.op, e.mb, (double)t0, (double)t1};
+  }
+  return n;
+}
+
 int stage_last_k(void) { return g.last_k; }
 
 int stage_side_streams_overlap(void) {
@@ -1351,6 +1681,7 @@ double stage_last_run_ms(void) {
 int stage_destroy(void) {
   if (!g.inited) return 0;
   for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) hipStreamSynchronize(q);
+  pipeline_release();
   if (g.sw != nullptr) { hipStreamSynchronize(g.sw); hipStreamDestroy(g.sw); }
   hipEventDestroy(g.ev_sw_tail);
   for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w, &g.ev_g, &g.ev_t0[0], &g.ev_t0[1], &g.ev_t0[2], &g.ev_t0[3]})

@@ -487,6 +487,18 @@ __global__ void delay_kernel(long long ticks) {
   while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
 }
 
+// The device wall clock, for a delay that counts from an event on another stream: the producer's stream stamps
+// the clock when it is done, the transfer's stream waits until `ticks` after that stamp.  The wait also ends
+// `ticks` after its own start, so it is bounded whatever the stamp holds.
+__global__ void clock_stamp_kernel(long long* stamp) {
+  if (threadIdx.x == 0) *stamp = wall_clock64();
+}
+__global__ void delay_since_kernel(const long long* stamp, long long ticks) {
+  const long long since = *stamp, me = wall_clock64();
+  long long now = me;
+  while (now - since < ticks && now - me < ticks) { __builtin_amdgcn_s_sleep(32); now = wall_clock64(); }
+}
+
 // ------------------------------------------------------------------------------------------------
 // launchers
 // ------------------------------------------------------------------------------------------------
@@ -625,6 +637,18 @@ hipError_t launch_delay(int64_t ns, hipStream_t s) {
   if (ns <= 0) return hipSuccess;
   if (ns > 2000000000LL) ns = 2000000000LL;                   // never spin longer than two seconds
   hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, s, (long long)(ns / 10));
+  return hipGetLastError();
+}
+
+hipError_t launch_clock_stamp(long long* stamp, hipStream_t s) {
+  hipLaunchKernelGGL(clock_stamp_kernel, dim3(1), dim3(64), 0, s, stamp);
+  return hipGetLastError();
+}
+
+hipError_t launch_delay_since(const long long* stamp, int64_t ns, hipStream_t s) {
+  if (ns <= 0) return hipSuccess;
+  if (ns > 2000000000LL) ns = 2000000000LL;
+  hipLaunchKernelGGL(delay_since_kernel, dim3(1), dim3(64), 0, s, stamp, (long long)(ns / 10));
   return hipGetLastError();
 }
 
