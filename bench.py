@@ -60,6 +60,11 @@ def main():
                     help="also time the same iteration run as a pipeline of this many virtual stages on the one GPU "
                          "(run_pipeline_kFkB: every stage under its own kFkB plan, boundary crossings delayed by the "
                          "workload's delay model); reported under \"pipeline_sim\", the headline value is unchanged")
+    ap.add_argument("--candidates-gb", type=float, default=0.0,
+                    help="also time every candidate plan (k, b) on the memory-limit curve (paper Section 4.2): the global "
+                         "batch stays fixed, for each k the largest micro-batch size b whose (w+1) k live micro-batches fit "
+                         "this many GB of stashed activations; the stage is set up anew for every b; reported under "
+                         "\"candidates\", the headline value is unchanged")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -297,6 +302,40 @@ def main():
         "adaptive": adaptive, "pipeline_sim": pipeline_sim, "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
     }
     st.close()
+    if args.candidates_gb > 0:
+        per_sample = kf.kfkb_activation_bytes_per_microbatch(L, 1, T, H, heads, 4 * H, 2 if w["dtype"] == "bf16" else 4)
+        cands = kf.kfkb_enumerate_candidates(M * b, int(args.candidates_gb * 1e9), per_sample)
+        rows = []
+        for ck, cb in cands:
+            cM = M * b // cb
+            cst = kf.StageBuffers(blocks if not w.get("tiled") else [one] * L, dt, heads, T, cb, cM, ck)
+            pair = [(synth.microbatch_inputs(j, cb, T, H, w["dtype"]), synth.microbatch_upstream_grads(j, cb, T, H, w["dtype"])) for j in range(2)]
+            for mb in range(cM):
+                cst.set_inputs_one(mb, *pair[mb % 2])
+            kf.stage_set_wgrad_stream(args.wgrad_stream)
+            kf.stage_set_compute_lanes(args.lanes)
+
+            def cstep(i):
+                if delay_model == "lognormal":
+                    kf.stage_set_delays(*[synth.delays_lognormal(cM, 2.0, 0.5, seed=4242 + 4 * i + j) for j in range(4)])
+                elif delay_model == "bimodal":
+                    kf.stage_set_delays(*[synth.delays_bimodal(cM, 0.5, 10.0, 0.7, seed=4242 + 4 * i + j) for j in range(4)])
+                elif delay_model == "drift":
+                    kf.stage_set_delays(*([synth.delays_drift(cM, i, args.steps, 20.0)] * 4))
+                kf.stage_zero_grads()
+                kf.run_kFkB(ck, cM, int(args.candidates_gb * 1e9))
+            for _ in range(args.warmup):
+                cstep(0)
+            kf.stage_sync()
+            t0 = time.perf_counter()
+            for i in range(args.steps):
+                cstep(i)
+            kf.stage_sync()
+            dt_s = time.perf_counter() - t0
+            rows.append(dict(k=ck, micro_batch=cb, num_microbatches=cM, ms_per_step=1e3 * dt_s / args.steps,
+                             samples_per_s=M * b * args.steps / dt_s, activation_gb=kf.stage_activation_bytes(ck, cM) / 1e9))
+            cst.close()
+        out["candidates"] = dict(global_batch=M * b, activation_limit_gb=args.candidates_gb, delay=delay_model, plans=rows)
     if args.copy_calibration:
         a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").fill_(1.0)
         c = torch.empty_like(a)
