@@ -65,6 +65,9 @@ def main():
                          "batch stays fixed, for each k the largest micro-batch size b whose (w+1) k live micro-batches fit "
                          "this many GB of stashed activations; the stage is set up anew for every b; reported under "
                          "\"candidates\", the headline value is unchanged")
+    ap.add_argument("--recompute", action="store_true",
+                    help="activation recomputation: LayerNorm and GELU outputs are formed again in the backward pass "
+                         "instead of being stashed (10 instead of 16 activation tensors per block)")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -99,7 +102,8 @@ def main():
         blocks = [one] * L
     else:
         blocks = synth.stage_weights(L, H, 4 * H, w["dtype"])
-    st = kf.StageBuffers(blocks, dt, heads, T, b, M, M if (0 in w["ks"] or args.pipeline_stages > 1) else max(w["ks"]))
+    st = kf.StageBuffers(blocks, dt, heads, T, b, M, M if (0 in w["ks"] or args.pipeline_stages > 1) else max(w["ks"]),
+                         recompute=int(args.recompute))
     distinct = 2 if w.get("tiled") else M
     cache = {}
     for mb in range(M):
@@ -295,7 +299,8 @@ def main():
         "config": {"workload": args.workload, "layers": L, "hidden": H, "heads": heads, "seq_len": T, "micro_batch": b,
                    "num_microbatches": M, "global_batch": M * b, "k": best_k, "delay": delay_model,
                    "activation_limit_bytes": limit,
-                   "side_streams_overlap": bool(overlap), "wgrad_stream": bool(args.wgrad_stream), "compute_lanes": args.lanes},
+                   "side_streams_overlap": bool(overlap), "wgrad_stream": bool(args.wgrad_stream), "compute_lanes": args.lanes,
+                   "recompute": bool(args.recompute)},
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
         "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,
         "per_k": {str(k): v for k, v in per_k.items()},
@@ -303,12 +308,13 @@ def main():
     }
     st.close()
     if args.candidates_gb > 0:
-        per_sample = kf.kfkb_activation_bytes_per_microbatch(L, 1, T, H, heads, 4 * H, 2 if w["dtype"] == "bf16" else 4)
+        per_sample = kf.kfkb_activation_bytes_per_microbatch(L, 1, T, H, heads, 4 * H, 2 if w["dtype"] == "bf16" else 4,
+                                                             recompute=int(args.recompute))
         cands = kf.kfkb_enumerate_candidates(M * b, int(args.candidates_gb * 1e9), per_sample)
         rows = []
         for ck, cb in cands:
             cM = M * b // cb
-            cst = kf.StageBuffers(blocks if not w.get("tiled") else [one] * L, dt, heads, T, cb, cM, ck)
+            cst = kf.StageBuffers(blocks if not w.get("tiled") else [one] * L, dt, heads, T, cb, cM, ck, recompute=int(args.recompute))
             pair = [(synth.microbatch_inputs(j, cb, T, H, w["dtype"]), synth.microbatch_upstream_grads(j, cb, T, H, w["dtype"])) for j in range(2)]
             for mb in range(cM):
                 cst.set_inputs_one(mb, *pair[mb % 2])

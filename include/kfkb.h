@@ -55,6 +55,11 @@ typedef struct kfkb_config {
   int num_stages;        /* S: pipeline depth this stage pretends to sit in; 0 means 1 */
   int stage_index;       /* s in [0, S): the stage runs w = min(S-1-s, ceil(M/k)) warm-up groups */
   int max_microbatches;  /* upper bound on num_microbatches of any later run_kFkB (>= 1) */
+  int recompute;         /* 1: activation recomputation (paper Section 2.2: with it more micro-batches fit, i.e. a
+                            larger k under the same limit).  The two LayerNorm outputs and the GELU output of a block
+                            are not kept from forward to backward; the backward forms them again from the kept
+                            block input, x1 and pre-activation with the same kernels (same bits): 6 b*T*H + b*T*F
+                            stashed elements per block instead of 8 b*T*H + 2 b*T*F.  Results do not change. */
 } kfkb_config_t;
 
 typedef struct kfkb_op {
@@ -80,6 +85,9 @@ int kfkb_peak_live(int k, int num_microbatches, int warmup_groups);
  * for a stage of the given shape; elem_bytes = 4 (fp32) or 2 (bf16). */
 size_t kfkb_activation_bytes_per_microbatch(int layers, int micro_batch, int seq, int hidden, int heads,
                                             int mlp_width, int elem_bytes);
+/* The same with the choice of kfkb_config_t.recompute (0: as above). */
+size_t kfkb_activation_bytes_per_microbatch_ex(int layers, int micro_batch, int seq, int hidden, int heads,
+                                               int mlp_width, int elem_bytes, int recompute);
 
 /* Candidate plans (k, b) on the memory-limit curve at a fixed global batch (paper Section 4.2, pruning of the
  * candidate set): for k = 1, 2, ... the LARGEST micro-batch size b that divides global_batch, leaves at least k

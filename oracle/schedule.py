@@ -91,15 +91,18 @@ def peak_live(order):
     return max(live_counts(order))
 
 
-def activation_bytes_per_microbatch(L, b, T, H, heads, F_mlp, elem_bytes):
+def activation_bytes_per_microbatch(L, b, T, H, heads, F_mlp, elem_bytes, recompute=False):
     """Bytes one micro-batch keeps from its forward until its backward (Section 4.1: the
     forward activations must be preserved until the backward completes).  Per block, in the
     stage's storage type: block input x, LN1 output, qkv (3), attention output, x1, LN2 output
     (1 each), MLP pre-activation u and activation g (F/H each); in fp32: mean and rstd of both
-    LayerNorms per token and the softmax log-sum-exp per (head, token)."""
+    LayerNorms per token and the softmax log-sum-exp per (head, token).
+    recompute (Section 2.2, gradient checkpointing lets more micro-batches in): the two
+    LayerNorm outputs and g are formed again in the backward pass instead of being kept."""
     m = b * T
     n = m * H
-    per_block = (8 * n + 2 * m * F_mlp) * elem_bytes + (4 * m + b * heads * T) * 4
+    kept = (6 * n + m * F_mlp) if recompute else (8 * n + 2 * m * F_mlp)
+    per_block = kept * elem_bytes + (4 * m + b * heads * T) * 4
     return L * per_block
 
 

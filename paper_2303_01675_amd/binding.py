@@ -40,7 +40,7 @@ class KfkbError(RuntimeError):
 class _Config(C.Structure):
     _fields_ = [("dtype", C.c_int), ("micro_batch", C.c_int), ("mlp_ratio", C.c_int), ("causal", C.c_int),
                 ("ln_eps", C.c_float), ("num_stages", C.c_int), ("stage_index", C.c_int),
-                ("max_microbatches", C.c_int)]
+                ("max_microbatches", C.c_int), ("recompute", C.c_int)]
 
 
 class _KernelStat(C.Structure):
@@ -79,6 +79,7 @@ def load_library():
         "kfkb_schedule": (i, [i, i, i, C.POINTER(_Op), i]),
         "kfkb_peak_live": (i, [i, i, i]),
         "kfkb_activation_bytes_per_microbatch": (sz, [i, i, i, i, i, i, i]),
+        "kfkb_activation_bytes_per_microbatch_ex": (sz, [i, i, i, i, i, i, i, i]),
         "kfkb_enumerate_candidates": (i, [i, sz, sz, i, i, i, C.POINTER(C.c_int), C.POINTER(C.c_int), i]),
         "kfkb_predict_iteration_ms": (C.c_double, [i, i, i] + [C.c_double] * 6 + [i, i]),
         "kfkb_tuner_config": (i, [i, i, C.POINTER(C.c_int), i]),
@@ -210,8 +211,9 @@ def kfkb_peak_live(k, num_microbatches, warmup_groups=0):
     return _check(load_library().kfkb_peak_live(k, num_microbatches, warmup_groups))
 
 
-def kfkb_activation_bytes_per_microbatch(layers, micro_batch, seq, hidden, heads, mlp_width, elem_bytes):
-    return load_library().kfkb_activation_bytes_per_microbatch(layers, micro_batch, seq, hidden, heads, mlp_width, elem_bytes)
+def kfkb_activation_bytes_per_microbatch(layers, micro_batch, seq, hidden, heads, mlp_width, elem_bytes, recompute=0):
+    return load_library().kfkb_activation_bytes_per_microbatch_ex(layers, micro_batch, seq, hidden, heads, mlp_width, elem_bytes,
+                                                                  int(recompute))
 
 
 # ---- the stage -----------------------------------------------------------------------------------------
@@ -267,8 +269,8 @@ def run_kFkB_adaptive(num_microbatches, mem_limit=0):
 
 
 def stage_config(dtype=F32, micro_batch=1, mlp_ratio=4, causal=1, ln_eps=1e-5, num_stages=1, stage_index=0,
-                 max_microbatches=1):
-    cfg = _Config(dtype, micro_batch, mlp_ratio, causal, ln_eps, num_stages, stage_index, max_microbatches)
+                 max_microbatches=1, recompute=0):
+    cfg = _Config(dtype, micro_batch, mlp_ratio, causal, ln_eps, num_stages, stage_index, max_microbatches, int(recompute))
     return _check(load_library().stage_config(C.byref(cfg)))
 
 
@@ -420,7 +422,7 @@ class StageBuffers:
     """Allocates, with PyTorch, every buffer the stage borrows, and binds them.  Marshalling only."""
 
     def __init__(self, blocks, dtype, heads, seq, micro_batch, max_microbatches, k_max, causal=1, mlp_ratio=4,
-                 num_stages=1, stage_index=0, ln_eps=1e-5):
+                 num_stages=1, stage_index=0, ln_eps=1e-5, recompute=0):
         self.dtype = dtype
         self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float32
         self.L = len(blocks)
@@ -430,7 +432,7 @@ class StageBuffers:
         assert self.F == mlp_ratio * self.H
         stage_destroy()
         stage_config(dtype=dtype, micro_batch=micro_batch, mlp_ratio=mlp_ratio, causal=causal, ln_eps=ln_eps,
-                     num_stages=num_stages, stage_index=stage_index, max_microbatches=max_microbatches)
+                     num_stages=num_stages, stage_index=stage_index, max_microbatches=max_microbatches, recompute=recompute)
         self.weights = pack_weights(blocks, dtype)
         stage_init(self.weights, self.L, self.H, heads, seq)
         nbytes = stage_workspace_bytes(k_max)

@@ -136,6 +136,7 @@ hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratc
 hipError_t launch_colsum_group(int dt, int n, const void* const* dy, float* const* out, const int* widths, float* scratch,
                                int rows, hipStream_t s);   // up to 4 column sums over the same rows
 hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size_t n, hipStream_t s);
+hipError_t launch_gelu_fwd(int dt, const void* u, void* g, size_t n, hipStream_t s);   // g = gelu(u), n % 8 == 0
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s);
 hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int cols, hipStream_t s);
 // bf16 weight operand B[N][K] of an NT GEMM -> chunk-major [K/32][N][32]; transposed: src holds B^T as [K][N]

@@ -48,6 +48,7 @@ void prof_key_name(int key, char* out, size_t cap, int* bound) {
   else if (key >= PK_COLSUM && key < PK_COLSUM_XHAT) snprintf(out, cap, "colsum_partial_kernel<%s,false>", key - PK_COLSUM == 4 ? "float" : "bf16");
   else if (key >= PK_COLSUM_XHAT && key < PK_COLSUM_FINAL) snprintf(out, cap, "colsum_partial_kernel<%s,true>", key - PK_COLSUM_XHAT == 4 ? "float" : "bf16");
   else if (key == PK_COLSUM_FINAL) snprintf(out, cap, "colsum_final_kernel");
+  else if (key >= PK_GELU_BWD + 10 && key < PK_GEMM_F32) snprintf(out, cap, "gelu_fwd_kernel<%s>", key - PK_GELU_BWD == 14 ? "float" : "bf16");
   else if (key >= PK_GELU_BWD && key < PK_GEMM_F32) snprintf(out, cap, "gelu_bwd_kernel<%s>", key - PK_GELU_BWD == 4 ? "float" : "bf16");
   else if (key >= PK_GEMM_F32 && key < PK_ATTN_F32) { *bound = 2; snprintf(out, cap, "gemm_f32_kernel<%s>", epi[key - PK_GEMM_F32]); }
   else snprintf(out, cap, "kernel_%d", key);
@@ -194,6 +195,9 @@ struct Stage {
     char* t_n0 = nullptr; char* t_dx1[2] = {nullptr, nullptr}; char* t_dxr[3] = {nullptr, nullptr, nullptr};
     char* t_mf[2] = {nullptr, nullptr}; char* t_3n[2] = {nullptr, nullptr};
     float* dsum = nullptr; float* red_ln[2][2] = {{nullptr, nullptr}, {nullptr, nullptr}}; float* red_w[2] = {nullptr, nullptr};
+    // recompute only: forward temporaries (a, c, g) and the backward's recomputed copies, two of each like du
+    char* f_a = nullptr; char* f_c = nullptr; char* f_g = nullptr;
+    char* r_a[2] = {nullptr, nullptr}; char* r_c[2] = {nullptr, nullptr}; char* r_g[2] = {nullptr, nullptr};
     hipEvent_t ev_chain[kRing] = {}, ev_wdone[kRing] = {};   // per block of a backward pass, reused round-robin
     bool w_elsewhere[kRing] = {};                            // that block's W step ran on the other lane's stream
     uint64_t seq = 0;                                        // blocks of backward passes issued on this lane
@@ -202,6 +206,9 @@ struct Stage {
   Lane lane[2];
   int lanes = 2;
   bool wgrad_overlap = true;
+  // cfg.recompute: the LayerNorm outputs a, c and the GELU output g are not stashed; a forward keeps them in
+  // per-lane temporaries, a backward forms them again from x, x1 and u (same kernels, same bits)
+  bool recompute = false;
   bool fuse_w_reductions = true;   // KFKB_FUSE_W=0: the W step's small reductions as launches of their own
   // W steps get a stream of their own when the process has hardware queues to spare (GPU_MAX_HW_QUEUES >= 5:
   // two lanes, this one, send, receive); otherwise they borrow the other lane's stream while that lane is idle
@@ -232,7 +239,9 @@ bool g_cfg_set = false;
 
 size_t stash_block_bytes_of(const Stage& s) {
   // a, qkv(3), o, x1, c, y : 8 n ; u, g : 2 m F ; LN statistics 4 m floats ; lse b*heads*T floats
-  return align_up((8 * s.n + 2 * (size_t)s.m * s.F) * s.esz) + align_up((4 * (size_t)s.m + (size_t)s.b * s.heads * s.T) * 4);
+  // with recomputation a, c and g are not kept: 6 n and m F
+  const size_t elems = s.recompute ? 6 * s.n + (size_t)s.m * s.F : 8 * s.n + 2 * (size_t)s.m * s.F;
+  return align_up(elems * s.esz) + align_up((4 * (size_t)s.m + (size_t)s.b * s.heads * s.T) * 4);
 }
 
 int warmup_for(const Stage& s, int k, int M) {
@@ -250,7 +259,7 @@ int peak_live_for(const Stage& s, int k, int M) {
 size_t red_w_floats(const Stage& s) { return (size_t)128 * (s.F + 5 * (size_t)s.H); }
 size_t red_ln_floats(const Stage& s) { return (size_t)1024 * s.H; }
 
-struct LaneCarve { size_t tn, tmf, t3n, dsum, red_ln, red_w, total; };
+struct LaneCarve { size_t tn, tmf, t3n, dsum, red_ln, red_w, rec, total; };
 LaneCarve lane_carve(const Stage& s) {
   LaneCarve c{};
   const size_t act = align_up(s.n * s.esz);
@@ -261,6 +270,8 @@ LaneCarve lane_carve(const Stage& s) {
   c.dsum = off; off += align_up((size_t)s.b * s.heads * s.T * 4);
   c.red_ln = off; off += 4 * align_up(red_ln_floats(s) * 4);
   c.red_w = off; off += 2 * align_up(red_w_floats(s) * 4);
+  c.rec = off;
+  if (s.recompute) off += 3 * (2 * act + align_up((size_t)s.m * s.F * s.esz));      // forward temporaries + two backward sets
   c.total = off;
   return c;
 }
@@ -294,9 +305,16 @@ StashView view(const Stage& s, int slot, int l) {
   char* p = s.stash[slot] + (size_t)l * s.stash_block_bytes;
   const size_t nb = s.n * s.esz, fb = (size_t)s.m * s.F * s.esz;
   StashView v;
-  v.a = p; v.qkv = p + nb; v.o = p + 4 * nb; v.x1 = p + 5 * nb; v.c = p + 6 * nb; v.y = p + 7 * nb;
-  v.u = p + 8 * nb; v.gact = p + 8 * nb + fb;
-  float* st = reinterpret_cast<float*>(p + align_up(8 * nb + 2 * fb));
+  float* st;
+  if (s.recompute) {                                   // a, c, gact: the caller's temporaries
+    v.a = nullptr; v.c = nullptr; v.gact = nullptr;
+    v.qkv = p; v.o = p + 3 * nb; v.x1 = p + 4 * nb; v.y = p + 5 * nb; v.u = p + 6 * nb;
+    st = reinterpret_cast<float*>(p + align_up(6 * nb + fb));
+  } else {
+    v.a = p; v.qkv = p + nb; v.o = p + 4 * nb; v.x1 = p + 5 * nb; v.c = p + 6 * nb; v.y = p + 7 * nb;
+    v.u = p + 8 * nb; v.gact = p + 8 * nb + fb;
+    st = reinterpret_cast<float*>(p + align_up(8 * nb + 2 * fb));
+  }
   v.mean1 = st; v.rstd1 = st + s.m; v.mean2 = st + 2 * s.m; v.rstd2 = st + 3 * s.m; v.lse = st + 4 * (size_t)s.m;
   return v;
 }
@@ -391,6 +409,7 @@ int forward_block(ActiveOp& a) {
   WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{};
   const char* x = a.cur;
   char* y = (l == s.L - 1) ? s.ys.buf[a.out_buf] : v.y;
+  if (s.recompute) { const Stage::Lane& ln = s.lane[a.lane]; v.a = ln.f_a; v.c = ln.f_c; v.gact = ln.f_g; }
   HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, q));
   TRY(linear_fwd(s, q, KFKB_EPI_BIAS, s.H, 3 * s.H, v.a, wptr(s, l, s.po.w_qkv), w.qkv, wptr(s, l, s.po.b_qkv), nullptr, v.qkv, nullptr));
   TRY(attention_fwd(s, q, v.qkv, v.o, v.lse));
@@ -428,6 +447,14 @@ int backward_block(ActiveOp& a) {
   hipStream_t qw = !s.wgrad_overlap ? q : s.sw != nullptr ? s.sw : !a.other_busy ? s.lane[1 - a.lane].s : q;
   // the buffers about to be overwritten were last read by the W step of two blocks ago
   if (seq >= 2 && ln.w_elsewhere[(seq - 2) % Stage::kRing]) HIPCHK(hipStreamWaitEvent(q, ln.ev_wdone[(seq - 2) % Stage::kRing], 0));
+  if (s.recompute) {
+    // what the forward did not keep: LayerNorm outputs from the kept inputs (the statistics come out as they were),
+    // GELU output from the kept pre-activation
+    v.a = ln.r_a[par]; v.c = ln.r_c[par]; v.gact = ln.r_g[par];
+    HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, q));
+    HIPCHK(launch_ln_fwd(s.dt, v.x1, wptr(s, l, s.po.ln2_g), wptr(s, l, s.po.ln2_b), v.c, v.mean2, v.rstd2, s.m, s.H, s.cfg.ln_eps, q));
+    HIPCHK(launch_gelu_fwd(s.dt, v.u, v.gact, (size_t)s.m * s.F, q));
+  }
   // the four weight-gradient products of a block are issued together: one launch fills the chip where each
   // alone would not
   GemmArgs wg[4];
@@ -1022,10 +1049,16 @@ int kfkb_peak_live(int k, int num_microbatches, int warmup_groups) {
   return peak_live_of(order);
 }
 
+size_t kfkb_activation_bytes_per_microbatch_ex(int layers, int micro_batch, int seq, int hidden, int heads, int mlp_width,
+                                               int elem_bytes, int recompute) {
+  const size_t m = (size_t)micro_batch * seq, n = m * hidden;
+  const size_t elems = recompute ? 6 * n + m * mlp_width : 8 * n + 2 * m * mlp_width;
+  return (size_t)layers * (elems * elem_bytes + (4 * m + (size_t)micro_batch * heads * seq) * 4);
+}
+
 size_t kfkb_activation_bytes_per_microbatch(int layers, int micro_batch, int seq, int hidden, int heads, int mlp_width,
                                             int elem_bytes) {
-  const size_t m = (size_t)micro_batch * seq, n = m * hidden;
-  return (size_t)layers * ((8 * n + 2 * m * mlp_width) * elem_bytes + (4 * m + (size_t)micro_batch * heads * seq) * 4);
+  return kfkb_activation_bytes_per_microbatch_ex(layers, micro_batch, seq, hidden, heads, mlp_width, elem_bytes, 0);
 }
 
 int stage_config(const kfkb_config_t* cfg) {
@@ -1064,6 +1097,8 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   Stage s;
   s.cfg = c; s.dt = c.dtype; s.L = layers; s.H = hidden; s.heads = heads; s.d = d; s.T = seq; s.b = c.micro_batch;
   s.F = c.mlp_ratio * hidden; s.m = s.b * s.T; s.n = (size_t)s.m * s.H; s.esz = dt_bytes(s.dt); s.Mmax = c.max_microbatches;
+  s.recompute = c.recompute != 0;
+  if (s.recompute && ((size_t)s.m * s.F) % 8 != 0) return fail(KFKB_E_ARG, "stage_init: recomputation needs tokens * mlp width %% 8 == 0");
   const size_t H = hidden, F = s.F;
   BlockParams& p = s.po;
   size_t o = 0;
@@ -1106,7 +1141,7 @@ size_t stage_param_count(void) { return g.inited ? (size_t)g.L * g.po.total : 0;
 size_t stage_activation_bytes(int k, int num_microbatches) {
   if (!g.inited || k < 1 || num_microbatches < 1 || k > num_microbatches) return 0;
   return (size_t)peak_live_for(g, k, num_microbatches) *
-         kfkb_activation_bytes_per_microbatch(g.L, g.b, g.T, g.H, g.heads, g.F, (int)g.esz);
+         kfkb_activation_bytes_per_microbatch_ex(g.L, g.b, g.T, g.H, g.heads, g.F, (int)g.esz, g.recompute ? 1 : 0);
 }
 
 size_t stage_workspace_bytes(int k_max) {
@@ -1154,6 +1189,12 @@ int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum, const
     ln.dsum = reinterpret_cast<float*>(base + lc.dsum);
     for (int j = 0; j < 4; j++) ln.red_ln[j >> 1][j & 1] = reinterpret_cast<float*>(base + lc.red_ln + (size_t)j * align_up(red_ln_floats(g) * 4));
     for (int j = 0; j < 2; j++) ln.red_w[j] = reinterpret_cast<float*>(base + lc.red_w + (size_t)j * align_up(red_w_floats(g) * 4));
+    if (g.recompute) {
+      const size_t set = 2 * act + align_up((size_t)g.m * g.F * g.esz);
+      char* r = base + lc.rec;
+      ln.f_a = r; ln.f_c = r + act; ln.f_g = r + 2 * act;
+      for (int j = 0; j < 2; j++) { char* q = r + (size_t)(1 + j) * set; ln.r_a[j] = q; ln.r_c[j] = q + act; ln.r_g[j] = q + 2 * act; }
+    }
   }
   g.stash_release.assign(c.n_stash, nullptr);
   reset_iteration_state();
@@ -1440,7 +1481,7 @@ int run_kFkB_adaptive(int num_microbatches, size_t mem_limit) {
   if (g.adaptive_pending) TRY(tuner_observe_last());
   const int w = 0;                                    // evaluated with each plan's own warm-up depth below
   (void)w;
-  const size_t per_mb = kfkb_activation_bytes_per_microbatch(g.L, g.b, g.T, g.H, g.heads, g.F, (int)g.esz);
+  const size_t per_mb = kfkb_activation_bytes_per_microbatch_ex(g.L, g.b, g.T, g.H, g.heads, g.F, (int)g.esz, g.recompute ? 1 : 0);
   const int S = std::max(1, g.cfg.num_stages);
   const int k = kfkb_tuner_next_k(num_microbatches, std::max(0, S - 1 - g.cfg.stage_index), mem_limit, per_mb, nullptr, 0);
   if (k < 0) return k;

@@ -426,6 +426,20 @@ __global__ void __launch_bounds__(256) gelu_bwd_kernel(const T* __restrict__ dg,
   }
 }
 
+// g = gelu(u) of the stored pre-activation, as the fc1 epilogues form it (recomputation in the backward pass)
+template <typename T>
+__global__ void __launch_bounds__(256) gelu_fwd_kernel(const T* __restrict__ u, T* __restrict__ g, size_t nvec) {
+  size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < nvec; i += stride) {
+    float a[8], o[8];
+    Vec8<T>::load(u + i * 8, a);
+#pragma unroll
+    for (int e = 0; e < 8; e++) o[e] = gelu_f(a[e]);
+    Vec8<T>::store(g + i * 8, o);
+  }
+}
+
 __global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ p, size_t n) {
   size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * blockDim.x;
@@ -605,6 +619,17 @@ hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size
     klaunch(gelu_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 2, 3.0 * n * 2, (const bf16_t*)dg, (const bf16_t*)u, (bf16_t*)du, nvec);
   else
     klaunch(gelu_bwd_kernel<float>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 4, 3.0 * n * 4, (const float*)dg, (const float*)u, (float*)du, nvec);
+  return hipGetLastError();
+}
+
+hipError_t launch_gelu_fwd(int dt, const void* u, void* g, size_t n, hipStream_t s) {
+  const size_t nvec = n / 8;
+  if (nvec == 0) return hipSuccess;
+  const int grid = (int)std::min<size_t>((nvec + 255) / 256, 8192);
+  if (dt == DT_BF16)
+    klaunch(gelu_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 12, 2.0 * n * 2, (const bf16_t*)u, (bf16_t*)g, nvec);
+  else
+    klaunch(gelu_fwd_kernel<float>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 14, 2.0 * n * 4, (const float*)u, (float*)g, nvec);
   return hipGetLastError();
 }
 

@@ -12,11 +12,11 @@ from _util import NAME, assert_close
 pytestmark = pytest.mark.gpu
 
 
-def _make(dt, L, H, heads, T, b, M, k_max, causal=1, S=1, s=0):
+def _make(dt, L, H, heads, T, b, M, k_max, causal=1, S=1, s=0, recompute=0):
     blocks = synth.stage_weights(L, H, 4 * H, NAME[dt])
     xs = [synth.microbatch_inputs(mb, b, T, H, NAME[dt]) for mb in range(M)]
     dys = [synth.microbatch_upstream_grads(mb, b, T, H, NAME[dt]) for mb in range(M)]
-    st = kf.StageBuffers(blocks, dt, heads, T, b, M, k_max, causal=causal, num_stages=S, stage_index=s)
+    st = kf.StageBuffers(blocks, dt, heads, T, b, M, k_max, causal=causal, num_stages=S, stage_index=s, recompute=recompute)
     st.set_inputs(xs, dys)
     return st, blocks, xs, dys
 
@@ -234,3 +234,35 @@ def test_lanes_and_w_step_placement_change_timing_not_results(dt):
         kf.stage_set_compute_lanes(2)
         kf.stage_set_wgrad_stream(1)
         st.close()
+
+
+@pytest.mark.parametrize("dt,L,H,heads,T,b,M", [(kf.F32, 2, 128, 4, 64, 2, 6), (kf.BF16, 3, 128, 2, 96, 3, 6)])
+def test_recomputation_keeps_every_bit_and_lets_a_larger_k_in(dt, L, H, heads, T, b, M):
+    """Activation recomputation (paper Section 2.2): the LayerNorm and GELU outputs are formed again in the backward
+    pass by the kernels that formed them in the forward pass, so nothing changes but the memory a plan needs."""
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=M)
+    G, Y, dX, order = _run(st, 2, M)
+    plain = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+    per_plain = kf.stage_activation_bytes(1, M)
+    ws_plain = kf.stage_workspace_bytes(M)
+    st.close()
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=M, recompute=1)
+    per_rec = kf.stage_activation_bytes(1, M)
+    esz = 2 if dt == kf.BF16 else 4
+    assert per_plain == sch.activation_bytes_per_microbatch(L, b, T, H, heads, 4 * H, esz)
+    assert per_rec == sch.activation_bytes_per_microbatch(L, b, T, H, heads, 4 * H, esz, recompute=True)
+    assert per_rec < 0.66 * per_plain and kf.stage_workspace_bytes(M) < ws_plain
+    for k in (1, 2, M):
+        G, Y, dX, order = _run(st, k, M)
+        _check_against_oracle(dt, st, blocks, xs, dys, heads, 1, G, Y, dX, order, k)
+        for a, b_ in zip(plain, (st.grads, st.h_out, st.h_ingrad)):
+            assert torch.equal(a, b_)
+    # a limit that holds 2 micro-batches without recomputation holds 3 with it
+    limit = 2 * per_plain
+    kf.stage_zero_grads()
+    kf.run_kFkB(0, M, limit)
+    kf.stage_sync()
+    assert kf.stage_last_k() == 3 and 3 * per_rec <= limit < 4 * per_rec
+    for a, b_ in zip(plain, (st.grads, st.h_out, st.h_ingrad)):
+        assert torch.equal(a, b_)
+    st.close()

@@ -52,6 +52,8 @@ def test_memory_model_matches_oracle(lib):
                                    (2, 1, 4096, 8192, 64, 32768, 2)]:
         assert kf.kfkb_activation_bytes_per_microbatch(L, b, T, H, h, F, eb) == \
             sch.activation_bytes_per_microbatch(L, b, T, H, h, F, eb)
+        assert kf.kfkb_activation_bytes_per_microbatch(L, b, T, H, h, F, eb, recompute=1) == \
+            sch.activation_bytes_per_microbatch(L, b, T, H, h, F, eb, recompute=True)
 
 
 def test_calls_before_init_fail_cleanly(lib):

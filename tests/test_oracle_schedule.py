@@ -69,6 +69,11 @@ def test_memory_grows_with_k():              # Section 3.1: 1F1B is the most mem
     # 16 n elements of bf16 + fp32 statistics, n = b T H
     n = 4 * 1024 * 1024
     assert per == 6 * (16 * n * 2 + (4 * 4096 + 4 * 16 * 1024) * 4)
+    # with the LayerNorm outputs and the GELU output recomputed: 10 n elements (Section 2.2: more micro-batches fit)
+    rec = sch.activation_bytes_per_microbatch(6, 4, 1024, 1024, 16, 4096, 2, recompute=True)
+    assert rec == 6 * (10 * n * 2 + (4 * 4096 + 4 * 16 * 1024) * 4)
+    assert sch.largest_admissible_k(16, 0, 4 * per, rec) == 4 and sch.largest_admissible_k(16, 0, 8 * rec, rec) == 8
+    assert 8 * rec < 6 * per                 # what held 5 micro-batches now holds 8
     sizes = [sch.plan_activation_bytes(k, 16, 0, 6, 4, 1024, 1024, 16, 4096, 2) for k in (1, 2, 4, 8, 16)]
     assert sizes == sorted(sizes) and sizes[0] == per and sizes[-1] == 16 * per
     assert sch.largest_admissible_k(16, 0, 4 * per, per) == 4
