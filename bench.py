@@ -68,6 +68,9 @@ def main():
     ap.add_argument("--recompute", action="store_true",
                     help="activation recomputation: LayerNorm and GELU outputs are formed again in the backward pass "
                          "instead of being stashed (10 instead of 16 activation tensors per block)")
+    ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
+                    help="storage type of a 16-bit workload (default: the workload's own, bf16; f16 is the paper's "
+                         "precision and runs the same kernels)")
     ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
                     help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
                          "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
@@ -87,9 +90,11 @@ def main():
         sys.exit(2)
     kf.load_library()                      # fails loudly if libkfkb.so was not built
 
-    w = WORKLOADS[args.workload]
+    w = dict(WORKLOADS[args.workload])
+    if args.dtype is not None and w["dtype"] != "f32":
+        w["dtype"] = args.dtype
     L, H, heads, T, b, M = w["L"], w["H"], w["heads"], w["T"], w["b"], w["M"]
-    dt = kf.BF16 if w["dtype"] == "bf16" else kf.F32
+    dt = {"bf16": kf.BF16, "f16": kf.F16, "f32": kf.F32}[w["dtype"]]
     delay_model = args.delay or w["delay"]
     t0 = time.time()
     if w.get("tiled"):
@@ -97,7 +102,8 @@ def main():
 
         def tensor(name, shp):
             v = np.resize(base, int(np.prod(shp)))
-            return synth.round_to_bf16(v + 1.0 if name in ("ln1_g", "ln2_g") else v).reshape(shp)
+            v = v + 1.0 if name in ("ln1_g", "ln2_g") else v
+            return (synth.round_to_bf16(v) if w["dtype"] == "bf16" else v.astype(np.float16).astype(np.float32)).reshape(shp)
         one = {n: tensor(n, shp) for n, shp in synth.param_shapes(H, 4 * H).items()}
         blocks = [one] * L
     else:
@@ -302,13 +308,13 @@ def main():
                    "side_streams_overlap": bool(overlap), "wgrad_stream": bool(args.wgrad_stream), "compute_lanes": args.lanes,
                    "recompute": bool(args.recompute)},
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
-        "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] == "bf16" else None,
+        "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] != "f32" else None,   # fp16 has the same peak
         "per_k": {str(k): v for k, v in per_k.items()},
         "adaptive": adaptive, "pipeline_sim": pipeline_sim, "roofline": roofline, "kernels": kernels[:12], "cpu_baseline": cpu, "setup_seconds": t_setup,
     }
     st.close()
     if args.candidates_gb > 0:
-        per_sample = kf.kfkb_activation_bytes_per_microbatch(L, 1, T, H, heads, 4 * H, 2 if w["dtype"] == "bf16" else 4,
+        per_sample = kf.kfkb_activation_bytes_per_microbatch(L, 1, T, H, heads, 4 * H, 2 if w["dtype"] != "f32" else 4,
                                                              recompute=int(args.recompute))
         cands = kf.kfkb_enumerate_candidates(M * b, int(args.candidates_gb * 1e9), per_sample)
         rows = []

@@ -41,12 +41,12 @@ enum {
   KFKB_E_TIMEOUT = -5    /* stage_sync_timeout() gave up */
 };
 
-enum { KFKB_F32 = 0, KFKB_BF16 = 1 };
+enum { KFKB_F32 = 0, KFKB_BF16 = 1, KFKB_F16 = 2 };   /* fp16: the paper's own precision; same kernels as bf16 */
 enum { KFKB_OP_F = 0, KFKB_OP_B = 1 };
 
 /* Options fixed before stage_init().  Zero-initialise, then set what differs from the default. */
 typedef struct kfkb_config {
-  int dtype;             /* KFKB_F32 or KFKB_BF16: storage type of weights and activations; all
+  int dtype;             /* KFKB_F32, KFKB_BF16 or KFKB_F16: storage type of weights and activations; all
                             reductions, statistics and gradient accumulators are fp32 either way */
   int micro_batch;       /* b: samples per micro-batch (>= 1) */
   int mlp_ratio;         /* MLP width F = mlp_ratio * hidden; 0 means 4 */
@@ -305,7 +305,8 @@ int run_pipeline_kFkB(int k);
 int stage_get_pipeline_order(kfkb_pipe_op_t* out, int cap);
 
 /* ---- per-kernel entry points (building blocks, used by unit tests and kernel benchmarks) -- *
- * All pointers are device pointers; dtype is KFKB_F32 or KFKB_BF16 and names the storage type *
+ * All pointers are device pointers; dtype is KFKB_F32, KFKB_BF16 or KFKB_F16 (which follows every  *
+ * rule stated for bf16) and names the storage type                                            *
  * of every "T" buffer; `stream` is a hipStream_t (NULL = default stream).  Calls enqueue only. */
 
 enum { KFKB_GEMM_NN = 0,   /* C[M,N] = A[M,K] . B[K,N]                       (forward, fp32 only)   */

@@ -76,11 +76,13 @@ def round_to_bf16(x):
 def _condition(x, dtype):
     if dtype == "bf16":
         return round_to_bf16(x).astype(np.float64)
+    if dtype == "f16":
+        return np.asarray(x, dtype=np.float32).astype(np.float16).astype(np.float64)
     if dtype == "f32":
         return x.astype(np.float32).astype(np.float64)
     if dtype == "f64":
         return x
-    raise ValueError("dtype must be 'f32', 'bf16' or 'f64'")
+    raise ValueError("dtype must be 'f32', 'bf16', 'f16' or 'f64'")
 
 
 def stage_weights(L, H, F, dtype="f32", seed=1234, std=0.02):

@@ -6,7 +6,7 @@ import numpy as np
 import torch
 
 __all__ = [
-    "KfkbError", "load_library", "library_path", "F32", "BF16", "OP_F", "OP_B",
+    "KfkbError", "load_library", "library_path", "F32", "BF16", "F16", "OP_F", "OP_B",
     "GEMM_NN", "GEMM_NT", "GEMM_TN", "EPI_NONE", "EPI_BIAS", "EPI_BIAS_GELU", "EPI_BIAS_RES", "EPI_ACCUM",
     "EPI_GELU_BWD", "PARAM_ORDER", "param_shapes", "param_offsets", "pack_weights", "unpack_params",
     "kfkb_schedule", "kfkb_peak_live", "kfkb_activation_bytes_per_microbatch",
@@ -23,7 +23,7 @@ __all__ = [
     "kfkb_op_transpose", "kfkb_op_delay",
 ]
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 OP_F, OP_B = 0, 1
 GEMM_NN, GEMM_NT, GEMM_TN = 0, 1, 2
 EPI_NONE, EPI_BIAS, EPI_BIAS_GELU, EPI_BIAS_RES, EPI_ACCUM, EPI_GELU_BWD = range(6)
@@ -181,6 +181,8 @@ def pack_weights(blocks, dtype, device="cuda"):
     t = torch.from_numpy(flat)
     if dtype == BF16:
         t = t.to(torch.bfloat16)
+    elif dtype == F16:
+        t = t.to(torch.float16)
     return t.to(device)
 
 
@@ -424,7 +426,7 @@ class StageBuffers:
     def __init__(self, blocks, dtype, heads, seq, micro_batch, max_microbatches, k_max, causal=1, mlp_ratio=4,
                  num_stages=1, stage_index=0, ln_eps=1e-5, recompute=0):
         self.dtype = dtype
-        self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float32
+        self.tdtype = torch.bfloat16 if dtype == BF16 else torch.float16 if dtype == F16 else torch.float32
         self.L = len(blocks)
         self.H = int(np.asarray(blocks[0]["ln1_g"]).shape[0])
         self.F = int(np.asarray(blocks[0]["b_1"]).shape[0])

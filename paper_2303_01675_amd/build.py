@@ -8,13 +8,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libkfkb.so")
-SOURCES = ["engine.hip", "rowwise.hip", "f32_path.hip", "gemm_bf16.hip", "attention_bf16.hip"]
+SOURCES = ["engine.hip", "rowwise.hip", "f32_path.hip", "gemm_bf16.hip", "attention_bf16.hip", "gemm_f16.hip", "attention_f16.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include")]
 # The attention kernels do vector arithmetic on MFMA results (softmax): keeping those accumulators in
 # ordinary vector registers saves a register-file move per element and per direction.
-EXTRA = {"attention_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA = {"attention_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"], "attention_f16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose=False, jobs=8):

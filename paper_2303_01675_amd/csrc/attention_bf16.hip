@@ -24,6 +24,22 @@
 #include <cstdlib>
 
 namespace kfkb {
+// Built once per 16-bit storage type: this file as it is for bf16, through attention_f16.hip (which defines
+// KFKB_H16_IS_F16) for fp16; everything type-dependent lives in a namespace of its own.
+#ifdef KFKB_H16_IS_F16
+namespace f16k {
+typedef f16_t h16_t;
+typedef f16x8 h16x8;
+typedef f16x4 h16x4;
+#define KFKB_MFMA_H16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
+#else
+namespace bf16k {
+typedef bf16_t h16_t;
+typedef bf16x8 h16x8;
+typedef bf16x4 h16x4;
+#define KFKB_MFMA_H16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+#endif
+
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -42,44 +58,44 @@ struct TileIO {
   }
   static constexpr int NL = D / 32;           // chunks per thread for a 64-row tile
   // rows row0 .. row0+63 of a [*, ld] matrix, clamped to row_max, columns col0 .. col0+D
-  static __device__ __forceinline__ void load(bf16x8 (&r)[NL], const bf16_t* __restrict__ src, size_t ld, int row0,
+  static __device__ __forceinline__ void load(h16x8 (&r)[NL], const h16_t* __restrict__ src, size_t ld, int row0,
                                               int row_max, int col0) {
     const int c = threadIdx.x % CH;
 #pragma unroll
     for (int i = 0; i < NL; i++) {
       const int row = min(row0 + (int)threadIdx.x / CH + (256 / CH) * i, row_max);
-      r[i] = *reinterpret_cast<const bf16x8*>(src + (size_t)row * ld + col0 + c * 8);
+      r[i] = *reinterpret_cast<const h16x8*>(src + (size_t)row * ld + col0 + c * 8);
     }
   }
-  static __device__ __forceinline__ void store(bf16_t* tile, const bf16x8 (&r)[NL]) {
+  static __device__ __forceinline__ void store(h16_t* tile, const h16x8 (&r)[NL]) {
     const int c = threadIdx.x % CH;
 #pragma unroll
     for (int i = 0; i < NL; i++) {
       const int row = threadIdx.x / CH + (256 / CH) * i;
-      *reinterpret_cast<bf16x8*>(tile + (row * CH + (c ^ sw(row))) * 8) = r[i];
+      *reinterpret_cast<h16x8*>(tile + (row * CH + (c ^ sw(row))) * 8) = r[i];
     }
   }
   // 8 reduction-contiguous values of row `row`, chunk `chunk`
-  static __device__ __forceinline__ bf16x8 frag(const bf16_t* tile, int row, int chunk) {
-    return *reinterpret_cast<const bf16x8*>(tile + (row * CH + (chunk ^ sw(row))) * 8);
+  static __device__ __forceinline__ h16x8 frag(const h16_t* tile, int row, int chunk) {
+    return *reinterpret_cast<const h16x8*>(tile + (row * CH + (chunk ^ sw(row))) * 8);
   }
   // transpose read: this lane points at (row, col .. col+4) and (row + 8, col .. col+4)
-  static __device__ __forceinline__ bf16x8 frag_tr(const bf16_t* tile, int row, int col) {
+  static __device__ __forceinline__ h16x8 frag_tr(const h16_t* tile, int row, int col) {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-    const bf16_t* p = tile + (row * CH + ((col >> 3) ^ sw(row))) * 8 + (col & 7);
-    const bf16_t* p8 = tile + ((row + 8) * CH + ((col >> 3) ^ sw(row + 8))) * 8 + (col & 7);
+    const h16_t* p = tile + (row * CH + ((col >> 3) ^ sw(row))) * 8 + (col & 7);
+    const h16_t* p8 = tile + ((row + 8) * CH + ((col >> 3) ^ sw(row + 8))) * 8 + (col & 7);
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p8);
-    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    union { struct { s16x4 a, b; } s; h16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
   }
 };
 
-__device__ __forceinline__ bf16x8 pack8(const f32x16& a, int first) {
-  bf16x8 v;
+__device__ __forceinline__ h16x8 pack8(const f32x16& a, int first) {
+  h16x8 v;
 #pragma unroll
-  for (int s = 0; s < 8; s++) v[s] = (bf16_t)a[first + s];
+  for (int s = 0; s < 8; s++) v[s] = (h16_t)a[first + s];
   return v;
 }
 __device__ __forceinline__ f32x16 zero16() {
@@ -124,13 +140,13 @@ __device__ __forceinline__ void block_to_work(int& rb, int& bh, int pair) {
 // forward
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __restrict__ qkv, bf16_t* __restrict__ o,
+__global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restrict__ qkv, h16_t* __restrict__ o,
                                                             float* __restrict__ lse, int T, int H, int heads,
                                                             int causal, float scale_log2, int pair) {
   using IO = TileIO<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);     // [2][64][D]
-  bf16_t* Vs = Ks + 2 * 64 * D;                     // [2][64][D]
+  h16_t* Ks = reinterpret_cast<h16_t*>(smem);     // [2][64][D]
+  h16_t* Vs = Ks + 2 * 64 * D;                     // [2][64][D]
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
@@ -139,15 +155,15 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
   block_to_work(qb, bh, pair);
   const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
-  const bf16_t* base = qkv + (size_t)bi * T * ld;
+  const h16_t* base = qkv + (size_t)bi * T * ld;
   const int q0 = qb * 128, qw0 = q0 + wave * 32;
   const int i = qw0 + l32;
   const int ic = min(i, T - 1);
 
-  bf16x8 qf[D / 16];
+  h16x8 qf[D / 16];
 #pragma unroll
   for (int ds = 0; ds < D / 16; ds++)
-    qf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)ic * ld + hd * D + ds * 16 + hh * 8);
+    qf[ds] = *reinterpret_cast<const h16x8*>(base + (size_t)ic * ld + hd * D + ds * 16 + hh * 8);
 
   const int nkv_all = (T + 63) / 64;
   const int nkv = causal ? min(nkv_all, (min(q0 + 127, T - 1)) / 64 + 1) : nkv_all;
@@ -157,7 +173,7 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
   for (int t = 0; t < D / 32; t++) oacc[t] = zero16();
   float mrun = -INFINITY, lsum = 0.f;
 
-  bf16x8 rk[IO::NL], rv[IO::NL];
+  h16x8 rk[IO::NL], rv[IO::NL];
   IO::load(rk, base, ld, 0, T - 1, H + hd * D);
   IO::load(rv, base, ld, 0, T - 1, 2 * H + hd * D);
   IO::store(Ks, rk);
@@ -169,15 +185,15 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
       IO::load(rk, base, ld, j0 + 64, T - 1, H + hd * D);
       IO::load(rv, base, ld, j0 + 64, T - 1, 2 * H + hd * D);
     }
-    const bf16_t* Kt = Ks + cur * 64 * D;
-    const bf16_t* Vt = Vs + cur * 64 * D;
+    const h16_t* Kt = Ks + cur * 64 * D;
+    const h16_t* Vt = Vs + cur * 64 * D;
     if (!(causal && j0 > qw0 + 31)) {               // wave-uniform: some key of the tile is visible
       f32x16 st[2] = {zero16(), zero16()};
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int ds = 0; ds < D / 16; ds++)
-          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt], 0, 0, 0);
+          st[jt] = KFKB_MFMA_H16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt]);
       // masking is needed only where the tile crosses the diagonal or the end of the sequence
       if (j0 + 63 >= T || (causal && j0 + 63 > qw0)) {
 #pragma unroll
@@ -217,10 +233,10 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int t16 = 0; t16 < 2; t16++) {
-          const bf16x8 pb = pack8(st[jt], t16 * 8);
+          const h16x8 pb = pack8(st[jt], t16 * 8);
 #pragma unroll
           for (int t = 0; t < D / 32; t++)
-            oacc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Vt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, oacc[t], 0, 0, 0);
+            oacc[t] = KFKB_MFMA_H16(IO::frag_tr(Vt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, oacc[t]);
         }
     }
     if (kb + 1 < nkv) {
@@ -232,15 +248,15 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
   lsum += __shfl_xor(lsum, 32, 64);
   if (i < T) {
     const float inv = 1.0f / lsum;
-    bf16_t* orow = o + ((size_t)bi * T + i) * H + hd * D;
+    h16_t* orow = o + ((size_t)bi * T + i) * H + hd * D;
 #pragma unroll
     for (int t = 0; t < D / 32; t++)
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        bf16x4 v;
+        h16x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; e++) v[e] = (bf16_t)(oacc[t][q * 4 + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + t * 32 + q * 8 + hh * 4) = v;
+        for (int e = 0; e < 4; e++) v[e] = (h16_t)(oacc[t][q * 4 + e] * inv);
+        *reinterpret_cast<h16x4*>(orow + t * 32 + q * 8 + hh * 4) = v;
       }
     if (hh == 0) lse[((size_t)bi * heads + hd) * T + i] = (mrun + log2f(lsum)) * kLn2;
   }
@@ -250,15 +266,15 @@ __global__ void __launch_bounds__(256) attn_fwd_bf16_kernel(const bf16_t* __rest
 // backward, dQ: own rows = queries, streamed rows = keys
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ o,
-                                                               const bf16_t* __restrict__ d_o,
+__global__ void __launch_bounds__(256) attn_bwd_dq_h16_kernel(const h16_t* __restrict__ qkv, const h16_t* __restrict__ o,
+                                                               const h16_t* __restrict__ d_o,
                                                                const float* __restrict__ lse, float* __restrict__ dsum,
-                                                               bf16_t* __restrict__ dqkv, int T, int H, int heads,
+                                                               h16_t* __restrict__ dqkv, int T, int H, int heads,
                                                                int causal, float scale, int pair) {
   using IO = TileIO<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  bf16_t* Ks = reinterpret_cast<bf16_t*>(smem);
-  bf16_t* Vs = Ks + 2 * 64 * D;
+  h16_t* Ks = reinterpret_cast<h16_t*>(smem);
+  h16_t* Vs = Ks + 2 * 64 * D;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int hh = lane >> 5, l32 = lane & 31;
   const int tr_row = hh * 4 + ((lane & 15) >> 2);
@@ -267,17 +283,17 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
   block_to_work(qb, bh, pair);
   const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
-  const bf16_t* base = qkv + (size_t)bi * T * ld;
+  const h16_t* base = qkv + (size_t)bi * T * ld;
   const int q0 = qb * 128, qw0 = q0 + wave * 32;
   const int i = qw0 + l32;
   const int ic = min(i, T - 1);
   const float scale_log2 = scale * kLog2e;
 
-  bf16x8 qf[D / 16], dof[D / 16];
+  h16x8 qf[D / 16], dof[D / 16];
 #pragma unroll
   for (int ds = 0; ds < D / 16; ds++) {
-    qf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)ic * ld + hd * D + ds * 16 + hh * 8);
-    dof[ds] = *reinterpret_cast<const bf16x8*>(d_o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
+    qf[ds] = *reinterpret_cast<const h16x8*>(base + (size_t)ic * ld + hd * D + ds * 16 + hh * 8);
+    dof[ds] = *reinterpret_cast<const h16x8*>(d_o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
   }
   const float lse_i = lse[((size_t)bi * heads + hd) * T + ic] * kLog2e;
   // dsum_i = sum_t dO[i,t] O[i,t]: this kernel owns the query rows, so it forms the sum (each lane half holds
@@ -285,7 +301,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
   float dpart = 0.f;
 #pragma unroll
   for (int ds = 0; ds < D / 16; ds++) {
-    const bf16x8 of = *reinterpret_cast<const bf16x8*>(o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
+    const h16x8 of = *reinterpret_cast<const h16x8*>(o + ((size_t)bi * T + ic) * H + hd * D + ds * 16 + hh * 8);
 #pragma unroll
     for (int e = 0; e < 8; e++) dpart += (float)of[e] * (float)dof[ds][e];
   }
@@ -298,7 +314,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
 #pragma unroll
   for (int t = 0; t < D / 32; t++) dq[t] = zero16();
 
-  bf16x8 rk[IO::NL], rv[IO::NL];
+  h16x8 rk[IO::NL], rv[IO::NL];
   IO::load(rk, base, ld, 0, T - 1, H + hd * D);
   IO::load(rv, base, ld, 0, T - 1, 2 * H + hd * D);
   IO::store(Ks, rk);
@@ -310,16 +326,16 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
       IO::load(rk, base, ld, j0 + 64, T - 1, H + hd * D);
       IO::load(rv, base, ld, j0 + 64, T - 1, 2 * H + hd * D);
     }
-    const bf16_t* Kt = Ks + cur * 64 * D;
-    const bf16_t* Vt = Vs + cur * 64 * D;
+    const h16_t* Kt = Ks + cur * 64 * D;
+    const h16_t* Vt = Vs + cur * 64 * D;
     if (!(causal && j0 > qw0 + 31)) {
       f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int ds = 0; ds < D / 16; ds++) {
-          st[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt], 0, 0, 0);
-          dp[jt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Vt, jt * 32 + l32, ds * 2 + hh), dof[ds], dp[jt], 0, 0, 0);
+          st[jt] = KFKB_MFMA_H16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt]);
+          dp[jt] = KFKB_MFMA_H16(IO::frag(Vt, jt * 32 + l32, ds * 2 + hh), dof[ds], dp[jt]);
         }
       if (j0 + 63 >= T || (causal && j0 + 63 > qw0)) {
 #pragma unroll
@@ -341,10 +357,10 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int t16 = 0; t16 < 2; t16++) {
-          const bf16x8 dsb = pack8(st[jt], t16 * 8);
+          const h16x8 dsb = pack8(st[jt], t16 * 8);
 #pragma unroll
           for (int t = 0; t < D / 32; t++)
-            dq[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Kt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dq[t], 0, 0, 0);
+            dq[t] = KFKB_MFMA_H16(IO::frag_tr(Kt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dq[t]);
         }
     }
     if (kb + 1 < nkv) {
@@ -354,15 +370,15 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
     __syncthreads();
   }
   if (i < T) {
-    bf16_t* row = dqkv + ((size_t)bi * T + i) * ld + hd * D;
+    h16_t* row = dqkv + ((size_t)bi * T + i) * ld + hd * D;
 #pragma unroll
     for (int t = 0; t < D / 32; t++)
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        bf16x4 v;
+        h16x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; e++) v[e] = (bf16_t)(dq[t][q * 4 + e] * scale);
-        *reinterpret_cast<bf16x4*>(row + t * 32 + q * 8 + hh * 4) = v;
+        for (int e = 0; e < 4; e++) v[e] = (h16_t)(dq[t][q * 4 + e] * scale);
+        *reinterpret_cast<h16x4*>(row + t * 32 + q * 8 + hh * 4) = v;
       }
   }
 }
@@ -371,14 +387,14 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_bf16_kernel(const bf16_t* __r
 // backward, dK and dV: own rows = keys, streamed rows = queries
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ d_o,
+__global__ void __launch_bounds__(256) attn_bwd_dkv_h16_kernel(const h16_t* __restrict__ qkv, const h16_t* __restrict__ d_o,
                                                                 const float* __restrict__ lse, const float* __restrict__ dsum,
-                                                                bf16_t* __restrict__ dqkv, int T, int H, int heads,
+                                                                h16_t* __restrict__ dqkv, int T, int H, int heads,
                                                                 int causal, float scale, int pair) {
   using IO = TileIO<D>;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  bf16_t* Qs = reinterpret_cast<bf16_t*>(smem);     // [2][64][D]
-  bf16_t* Os = Qs + 2 * 64 * D;                     // [2][64][D]   (dO tiles)
+  h16_t* Qs = reinterpret_cast<h16_t*>(smem);     // [2][64][D]
+  h16_t* Os = Qs + 2 * 64 * D;                     // [2][64][D]   (dO tiles)
   float* Ls = reinterpret_cast<float*>(Os + 2 * 64 * D);   // [2][64] lse * log2(e)
   float* Ss = Ls + 2 * 64;                                 // [2][64] dsum
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -390,8 +406,8 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
   kb = gridDim.x - 1 - kb;                          // for keys the early blocks are the long ones
   const int bi = bh / heads, hd = bh % heads;
   const size_t ld = 3 * (size_t)H;
-  const bf16_t* base = qkv + (size_t)bi * T * ld;
-  const bf16_t* dobase = d_o + (size_t)bi * T * H;
+  const h16_t* base = qkv + (size_t)bi * T * ld;
+  const h16_t* dobase = d_o + (size_t)bi * T * H;
   const float* lbase = lse + ((size_t)bi * heads + hd) * T;
   const float* sbase = dsum + ((size_t)bi * heads + hd) * T;
   const int j0 = kb * 128, jw0 = j0 + wave * 32;
@@ -399,11 +415,11 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
   const int jc = min(j, T - 1);
   const float scale_log2 = scale * kLog2e;
 
-  bf16x8 kf[D / 16], vf[D / 16];
+  h16x8 kf[D / 16], vf[D / 16];
 #pragma unroll
   for (int ds = 0; ds < D / 16; ds++) {
-    kf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)jc * ld + H + hd * D + ds * 16 + hh * 8);
-    vf[ds] = *reinterpret_cast<const bf16x8*>(base + (size_t)jc * ld + 2 * H + hd * D + ds * 16 + hh * 8);
+    kf[ds] = *reinterpret_cast<const h16x8*>(base + (size_t)jc * ld + H + hd * D + ds * 16 + hh * 8);
+    vf[ds] = *reinterpret_cast<const h16x8*>(base + (size_t)jc * ld + 2 * H + hd * D + ds * 16 + hh * 8);
   }
   f32x16 dk[D / 32], dv[D / 32];
 #pragma unroll
@@ -411,7 +427,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
 
   const int nq = (T + 63) / 64;
   const int ib0 = causal ? j0 / 64 : 0;
-  bf16x8 rq[IO::NL], ro[IO::NL];
+  h16x8 rq[IO::NL], ro[IO::NL];
   float rstat = 0.f;
   auto load_stats = [&](int i0) {
     if (threadIdx.x < 64) rstat = lbase[min(i0 + (int)threadIdx.x, T - 1)] * kLog2e;
@@ -437,16 +453,16 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
       IO::load(ro, dobase, (size_t)H, i0 + 64, T - 1, hd * D);
       load_stats(i0 + 64);
     }
-    const bf16_t* Qt = Qs + cur * 64 * D;
-    const bf16_t* Ot = Os + cur * 64 * D;
+    const h16_t* Qt = Qs + cur * 64 * D;
+    const h16_t* Ot = Os + cur * 64 * D;
     if (!(causal && i0 + 63 < jw0)) {               // wave-uniform: some query of the tile sees these keys
       f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
 #pragma unroll
       for (int it = 0; it < 2; it++)
 #pragma unroll
         for (int ds = 0; ds < D / 16; ds++) {
-          st[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Qt, it * 32 + l32, ds * 2 + hh), kf[ds], st[it], 0, 0, 0);
-          dp[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag(Ot, it * 32 + l32, ds * 2 + hh), vf[ds], dp[it], 0, 0, 0);
+          st[it] = KFKB_MFMA_H16(IO::frag(Qt, it * 32 + l32, ds * 2 + hh), kf[ds], st[it]);
+          dp[it] = KFKB_MFMA_H16(IO::frag(Ot, it * 32 + l32, ds * 2 + hh), vf[ds], dp[it]);
         }
       if (i0 + 63 >= T || jw0 + 31 >= T || (causal && jw0 + 31 > i0)) {
 #pragma unroll
@@ -476,12 +492,12 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
       for (int it = 0; it < 2; it++)
 #pragma unroll
         for (int t16 = 0; t16 < 2; t16++) {
-          const bf16x8 pb = pack8(st[it], t16 * 8);
-          const bf16x8 dsb = pack8(dp[it], t16 * 8);
+          const h16x8 pb = pack8(st[it], t16 * 8);
+          const h16x8 dsb = pack8(dp[it], t16 * 8);
 #pragma unroll
           for (int t = 0; t < D / 32; t++) {
-            dv[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, dv[t], 0, 0, 0);
-            dk[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dk[t], 0, 0, 0);
+            dv[t] = KFKB_MFMA_H16(IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, dv[t]);
+            dk[t] = KFKB_MFMA_H16(IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dk[t]);
           }
         }
     }
@@ -493,17 +509,17 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_bf16_kernel(const bf16_t* __
     __syncthreads();
   }
   if (j < T) {
-    bf16_t* krow = dqkv + ((size_t)bi * T + j) * ld + H + hd * D;
-    bf16_t* vrow = dqkv + ((size_t)bi * T + j) * ld + 2 * H + hd * D;
+    h16_t* krow = dqkv + ((size_t)bi * T + j) * ld + H + hd * D;
+    h16_t* vrow = dqkv + ((size_t)bi * T + j) * ld + 2 * H + hd * D;
 #pragma unroll
     for (int t = 0; t < D / 32; t++)
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        bf16x4 a, b;
+        h16x4 a, b;
 #pragma unroll
-        for (int e = 0; e < 4; e++) { a[e] = (bf16_t)(dk[t][q * 4 + e] * scale); b[e] = (bf16_t)dv[t][q * 4 + e]; }
-        *reinterpret_cast<bf16x4*>(krow + t * 32 + q * 8 + hh * 4) = a;
-        *reinterpret_cast<bf16x4*>(vrow + t * 32 + q * 8 + hh * 4) = b;
+        for (int e = 0; e < 4; e++) { a[e] = (h16_t)(dk[t][q * 4 + e] * scale); b[e] = (h16_t)dv[t][q * 4 + e]; }
+        *reinterpret_cast<h16x4*>(krow + t * 32 + q * 8 + hh * 4) = a;
+        *reinterpret_cast<h16x4*>(vrow + t * 32 + q * 8 + hh * 4) = b;
       }
   }
 }
@@ -528,51 +544,71 @@ static int pair_blocks(K kern, size_t smem, int gx, int gy, int causal) {
 }
 
 template <int D>
-static hipError_t fwd_d(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s) {
+static hipError_t fwd_d(const h16_t* qkv, h16_t* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s) {
   static bool attr = false;
-  const size_t smem = (size_t)4 * 64 * D * sizeof(bf16_t);
-  hipError_t e = set_smem(attn_fwd_bf16_kernel<D>, smem, attr);
+  const size_t smem = (size_t)4 * 64 * D * sizeof(h16_t);
+  hipError_t e = set_smem(attn_fwd_h16_kernel<D>, smem, attr);
   if (e != hipSuccess) return e;
   const float scale_log2 = kLog2e / sqrtf((float)D);
   const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
-  klaunch(attn_fwd_bf16_kernel<D>, dim3((T + 127) / 128, b * heads), dim3(256), smem, s, PK_ATTN_FWD + D / 128, 4.0 * pairs * D,
-          qkv, o, lse, T, H, heads, causal, scale_log2, pair_blocks(attn_fwd_bf16_kernel<D>, smem, (T + 127) / 128, b * heads, causal));
+  klaunch(attn_fwd_h16_kernel<D>, dim3((T + 127) / 128, b * heads), dim3(256), smem, s, PK_ATTN_FWD + D / 128, 4.0 * pairs * D,
+          qkv, o, lse, T, H, heads, causal, scale_log2, pair_blocks(attn_fwd_h16_kernel<D>, smem, (T + 127) / 128, b * heads, causal));
   return hipGetLastError();
 }
 
 template <int D>
-static hipError_t bwd_d(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse, float* dsum, bf16_t* dqkv,
+static hipError_t bwd_d(const h16_t* qkv, const h16_t* o, const h16_t* d_o, const float* lse, float* dsum, h16_t* dqkv,
                         int b, int T, int H, int heads, int causal, hipStream_t s) {
   static bool attr1 = false, attr2 = false;
-  const size_t smem1 = (size_t)4 * 64 * D * sizeof(bf16_t);
+  const size_t smem1 = (size_t)4 * 64 * D * sizeof(h16_t);
   const size_t smem2 = smem1 + 4 * 64 * sizeof(float);
-  hipError_t e = set_smem(attn_bwd_dq_bf16_kernel<D>, smem1, attr1);
+  hipError_t e = set_smem(attn_bwd_dq_h16_kernel<D>, smem1, attr1);
   if (e != hipSuccess) return e;
-  e = set_smem(attn_bwd_dkv_bf16_kernel<D>, smem2, attr2);
+  e = set_smem(attn_bwd_dkv_h16_kernel<D>, smem2, attr2);
   if (e != hipSuccess) return e;
   const float scale = 1.0f / sqrtf((float)D);
   const dim3 grid((T + 127) / 128, b * heads);
   const double pairs = (double)b * heads * T * T * (causal ? 0.5 : 1.0);
-  klaunch(attn_bwd_dq_bf16_kernel<D>, grid, dim3(256), smem1, s, PK_ATTN_DQ + D / 128, 6.0 * pairs * D, qkv, o, d_o, lse, dsum, dqkv,
-          T, H, heads, causal, scale, pair_blocks(attn_bwd_dq_bf16_kernel<D>, smem1, (int)grid.x, (int)grid.y, causal));
-  klaunch(attn_bwd_dkv_bf16_kernel<D>, grid, dim3(256), smem2, s, PK_ATTN_DKV + D / 128, 8.0 * pairs * D, qkv, d_o, lse,
-          (const float*)dsum, dqkv, T, H, heads, causal, scale, pair_blocks(attn_bwd_dkv_bf16_kernel<D>, smem2, (int)grid.x, (int)grid.y, causal));
+  klaunch(attn_bwd_dq_h16_kernel<D>, grid, dim3(256), smem1, s, PK_ATTN_DQ + D / 128, 6.0 * pairs * D, qkv, o, d_o, lse, dsum, dqkv,
+          T, H, heads, causal, scale, pair_blocks(attn_bwd_dq_h16_kernel<D>, smem1, (int)grid.x, (int)grid.y, causal));
+  klaunch(attn_bwd_dkv_h16_kernel<D>, grid, dim3(256), smem2, s, PK_ATTN_DKV + D / 128, 8.0 * pairs * D, qkv, d_o, lse,
+          (const float*)dsum, dqkv, T, H, heads, causal, scale, pair_blocks(attn_bwd_dkv_h16_kernel<D>, smem2, (int)grid.x, (int)grid.y, causal));
   return hipGetLastError();
 }
 
-hipError_t launch_attention_fwd_bf16(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads,
+hipError_t launch_attention_fwd_h16(const h16_t* qkv, h16_t* o, float* lse, int b, int T, int H, int heads,
                                      int causal, hipStream_t s) {
   if (b <= 0 || T <= 0) return hipSuccess;
   return (H / heads == 64) ? fwd_d<64>(qkv, o, lse, b, T, H, heads, causal, s)
                            : fwd_d<128>(qkv, o, lse, b, T, H, heads, causal, s);
 }
 
-hipError_t launch_attention_bwd_bf16(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse,
-                                     float* dsum, bf16_t* dqkv, int b, int T, int H, int heads, int causal,
+hipError_t launch_attention_bwd_h16(const h16_t* qkv, const h16_t* o, const h16_t* d_o, const float* lse,
+                                     float* dsum, h16_t* dqkv, int b, int T, int H, int heads, int causal,
                                      hipStream_t s) {
   if (b <= 0 || T <= 0) return hipSuccess;
   return (H / heads == 64) ? bwd_d<64>(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s)
                            : bwd_d<128>(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s);
 }
+
+#ifdef KFKB_H16_IS_F16
+}  // namespace f16k
+hipError_t launch_attention_fwd_f16(const void* qkv, void* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s) {
+  return f16k::launch_attention_fwd_h16((const f16_t*)qkv, (f16_t*)o, lse, b, T, H, heads, causal, s);
+}
+hipError_t launch_attention_bwd_f16(const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum, void* dqkv,
+                                    int b, int T, int H, int heads, int causal, hipStream_t s) {
+  return f16k::launch_attention_bwd_h16((const f16_t*)qkv, (const f16_t*)o, (const f16_t*)d_o, lse, dsum, (f16_t*)dqkv, b, T, H, heads, causal, s);
+}
+#else
+}  // namespace bf16k
+hipError_t launch_attention_fwd_bf16(const void* qkv, void* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s) {
+  return bf16k::launch_attention_fwd_h16((const bf16_t*)qkv, (bf16_t*)o, lse, b, T, H, heads, causal, s);
+}
+hipError_t launch_attention_bwd_bf16(const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum, void* dqkv,
+                                     int b, int T, int H, int heads, int causal, hipStream_t s) {
+  return bf16k::launch_attention_bwd_h16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, dsum, (bf16_t*)dqkv, b, T, H, heads, causal, s);
+}
+#endif
 
 }  // namespace kfkb

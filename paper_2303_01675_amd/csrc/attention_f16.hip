@@ -1,0 +1,3 @@
+// The fused attention kernels built for fp16 storage (the paper's precision): the same source as for bf16.
+#define KFKB_H16_IS_F16 1
+#include "attention_bf16.hip"

@@ -10,6 +10,9 @@ namespace kfkb {
 typedef __bf16 bf16_t;
 typedef bf16_t bf16x8 __attribute__((ext_vector_type(8)));
 typedef bf16_t bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16_t;
+typedef f16_t f16x8 __attribute__((ext_vector_type(8)));
+typedef f16_t f16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -21,9 +24,11 @@ __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)f; }
 template <typename T> __device__ __forceinline__ float to_f(T v);
 template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
 template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return (float)v; }
+template <> __device__ __forceinline__ float to_f<f16_t>(f16_t v) { return (float)v; }
 template <typename T> __device__ __forceinline__ T from_f(float v);
 template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return (bf16_t)v; }
+template <> __device__ __forceinline__ f16_t from_f<f16_t>(float v) { return (f16_t)v; }
 
 // 8 consecutive elements of T <-> 8 floats, vector loads (16 B for bf16, 2 x 16 B for fp32).
 // eight values as they come from memory: loaded now, converted where they are first used (a load whose
@@ -31,6 +36,7 @@ template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return (
 template <typename T> struct Raw8;
 template <> struct Raw8<float> { float4 a, b; };
 template <> struct Raw8<bf16_t> { bf16x8 v; };
+template <> struct Raw8<f16_t> { f16x8 v; };
 template <typename T> struct Vec8;
 template <> struct Vec8<float> {
   static __device__ __forceinline__ Raw8<float> load_raw(const float* p) {
@@ -67,6 +73,26 @@ template <> struct Vec8<bf16_t> {
 #pragma unroll
     for (int i = 0; i < 8; i++) a[i] = (bf16_t)v[i];
     *reinterpret_cast<bf16x8*>(p) = a;
+  }
+};
+template <> struct Vec8<f16_t> {
+  static __device__ __forceinline__ Raw8<f16_t> load_raw(const f16_t* p) {
+    Raw8<f16_t> r; r.v = *reinterpret_cast<const f16x8*>(p); return r;
+  }
+  static __device__ __forceinline__ void unpack(const Raw8<f16_t>& r, float (&v)[8]) {
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (float)r.v[i];
+  }
+  static __device__ __forceinline__ void load(const f16_t* p, float (&v)[8]) {
+    const f16x8 a = *reinterpret_cast<const f16x8*>(p);
+#pragma unroll
+    for (int i = 0; i < 8; i++) v[i] = (float)a[i];
+  }
+  static __device__ __forceinline__ void store(f16_t* p, const float (&v)[8]) {
+    f16x8 a;
+#pragma unroll
+    for (int i = 0; i < 8; i++) a[i] = (f16_t)v[i];
+    *reinterpret_cast<f16x8*>(p) = a;
   }
 };
 
@@ -118,8 +144,9 @@ inline void klaunch(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t smem, 
 }
 
 // ---- launch-side declarations (definitions in the .hip files) ----------------------------------
-enum { DT_F32 = 0, DT_BF16 = 1 };
-static inline size_t dt_bytes(int dt) { return dt == DT_BF16 ? 2 : 4; }
+enum { DT_F32 = 0, DT_BF16 = 1, DT_F16 = 2 };
+static inline size_t dt_bytes(int dt) { return dt == DT_F32 ? 4 : 2; }
+static inline bool dt_is16(int dt) { return dt != DT_F32; }
 
 // Rows of partial column sums that the two-stage column reductions write before their
 // finishing pass (fixed, so results do not depend on the launch).
@@ -155,7 +182,12 @@ struct GemmArgs {
   bool b_tiled = false;      // NT only: B is stored chunk-major, [K/32][N][32] (see launch_tile_weights)
 };
 hipError_t launch_gemm_f32(const GemmArgs& g, hipStream_t s);
-hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);   // NT and TN only
+// 16-bit storage (bf16 or fp16, the same kernels built once per type): NT and TN only
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_f16(const GemmArgs& g, hipStream_t s);
+static inline hipError_t launch_gemm_16(int dt, const GemmArgs& g, hipStream_t s) {
+  return dt == DT_F16 ? launch_gemm_f16(g, s) : launch_gemm_bf16(g, s);
+}
 // The small reductions that belong to the same step as a group of weight-gradient products: column sums over the
 // token axis of up to four bf16 matrices dy[rows, width] (out[i][c] += sum_r dy[i][r][c]) and the finishing pass of
 // up to two LayerNorm backward reductions (partial rows left by launch_ln_bwd called with dgamma == nullptr;
@@ -169,18 +201,36 @@ struct WStepReduce {
 // tiles leave idle when the shapes allow (*red_done = true); otherwise *red_done = false and the caller runs them.
 hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
                                      bool* red_done = nullptr);
+hipError_t launch_gemm_f16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
+                                    bool* red_done = nullptr);
+static inline hipError_t launch_gemm_16_tn_group(int dt, const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
+                                                 bool* red_done = nullptr) {
+  return dt == DT_F16 ? launch_gemm_f16_tn_group(g, n, s, red, red_done) : launch_gemm_bf16_tn_group(g, n, s, red, red_done);
+}
 int ln_bwd_partial_rows(int rows, int H);        // partial rows launch_ln_bwd leaves in its scratch
-const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported
+const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported (either 16-bit type)
 
 hipError_t launch_attention_fwd_f32(const float* qkv, float* o, float* lse, int b, int T, int H, int heads,
                                     int causal, hipStream_t s);
 hipError_t launch_attention_bwd_f32(const float* qkv, const float* o, const float* d_o, const float* lse,
                                     float* dsum, float* dqkv, int b, int T, int H, int heads, int causal,
                                     hipStream_t s);
-hipError_t launch_attention_fwd_bf16(const bf16_t* qkv, bf16_t* o, float* lse, int b, int T, int H, int heads,
-                                     int causal, hipStream_t s);
-hipError_t launch_attention_bwd_bf16(const bf16_t* qkv, const bf16_t* o, const bf16_t* d_o, const float* lse,
-                                     float* dsum, bf16_t* dqkv, int b, int T, int H, int heads, int causal,
-                                     hipStream_t s);
+// 16-bit storage: `dt` is DT_BF16 or DT_F16
+hipError_t launch_attention_fwd_bf16(const void* qkv, void* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s);
+hipError_t launch_attention_bwd_bf16(const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum, void* dqkv,
+                                     int b, int T, int H, int heads, int causal, hipStream_t s);
+hipError_t launch_attention_fwd_f16(const void* qkv, void* o, float* lse, int b, int T, int H, int heads, int causal, hipStream_t s);
+hipError_t launch_attention_bwd_f16(const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum, void* dqkv,
+                                    int b, int T, int H, int heads, int causal, hipStream_t s);
+static inline hipError_t launch_attention_fwd_16(int dt, const void* qkv, void* o, float* lse, int b, int T, int H, int heads,
+                                                 int causal, hipStream_t s) {
+  return dt == DT_F16 ? launch_attention_fwd_f16(qkv, o, lse, b, T, H, heads, causal, s)
+                      : launch_attention_fwd_bf16(qkv, o, lse, b, T, H, heads, causal, s);
+}
+static inline hipError_t launch_attention_bwd_16(int dt, const void* qkv, const void* o, const void* d_o, const float* lse,
+                                                 float* dsum, void* dqkv, int b, int T, int H, int heads, int causal, hipStream_t s) {
+  return dt == DT_F16 ? launch_attention_bwd_f16(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s)
+                      : launch_attention_bwd_bf16(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s);
+}
 
 }  // namespace kfkb

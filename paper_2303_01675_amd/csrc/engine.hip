@@ -24,7 +24,16 @@ std::vector<ProfRec> g_prof_recs;
 std::vector<hipEvent_t> g_prof_pool;      // events created so far, reused run after run
 size_t g_prof_next = 0;
 
+int g_prof_dt = DT_BF16;      // storage type of the stage whose kernels are being timed (names say bf16 or f16)
+
+void prof_key_name_bf16(int key, char* out, size_t cap, int* bound);
 void prof_key_name(int key, char* out, size_t cap, int* bound) {
+  prof_key_name_bf16(key, out, cap, bound);
+  if (g_prof_dt != DT_F16) return;
+  for (char* p = strstr(out, "bf16"); p != nullptr; p = strstr(p, "bf16")) memmove(p, p + 1, strlen(p));   // "bf16" -> "f16"
+}
+
+void prof_key_name_bf16(int key, char* out, size_t cap, int* bound) {
   static const char* epi[] = {"none", "bias", "bias_gelu", "bias_res", "accum", "gelu_bwd"};
   *bound = 1;
   if (key >= PK_GEMM_NT && key < PK_ATTN_FWD) {
@@ -285,7 +294,7 @@ Carve carve_for(const Stage& s, int k_max) {
   const size_t act = align_up(s.n * s.esz);
   size_t off = 0;
   c.wt = off;
-  if (s.dt == DT_BF16) off += align_up((size_t)2 * s.L * ((size_t)4 * s.H * s.H + 2 * (size_t)s.H * s.F) * 2);
+  if (dt_is16(s.dt)) off += align_up((size_t)2 * s.L * ((size_t)4 * s.H * s.H + 2 * (size_t)s.H * s.F) * 2);
   c.stash = off; off += (size_t)c.n_stash * s.L * stash_block_bytes_of(s);
   c.xs = off; off += (size_t)c.n_x * act;
   c.dys = off; off += (size_t)c.n_io * act;
@@ -335,10 +344,10 @@ int gemm(const Stage& s, hipStream_t st, int kind, int epi, int M, int N, int K,
          const void* res, void* C, void* C2, float* Cacc, bool b_tiled = false) {
   GemmArgs a{kind, epi, M, N, K, A, B, bias, res, C, C2, Cacc};
   a.b_tiled = b_tiled;
-  if (s.dt == DT_BF16) {
+  if (dt_is16(s.dt)) {
     const char* why = gemm_bf16_check(a);
     if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
-    HIPCHK(launch_gemm_bf16(a, st));
+    HIPCHK(launch_gemm_16(s.dt, a, st));
   } else {
     HIPCHK(launch_gemm_f32(a, st));
   }
@@ -348,12 +357,12 @@ int gemm(const Stage& s, hipStream_t st, int kind, int epi, int M, int N, int K,
 // forward linear map y = x W + b (+ epilogue): fp32 reads W [in,out] as given, bf16 reads the [out,in] copy
 int linear_fwd(const Stage& s, hipStream_t st, int epi, int in, int out, const void* x, const void* W, const void* Wt, const void* bias,
                const void* res, void* y, void* y2) {
-  if (s.dt == DT_BF16) return gemm(s, st, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr, true);
+  if (dt_is16(s.dt)) return gemm(s, st, KFKB_GEMM_NT, epi, s.m, out, in, x, Wt, bias, res, y, y2, nullptr, true);
   return gemm(s, st, KFKB_GEMM_NN, epi, s.m, out, in, x, W, bias, res, y, y2, nullptr);
 }
 
 int refresh_weights() {
-  if (g.dt != DT_BF16) return 0;
+  if (!dt_is16(g.dt)) return 0;
   hipStream_t st = g.lane[0].s;
   for (int l = 0; l < g.L; l++) {
     WtView w = wt_view(g, l);
@@ -371,13 +380,13 @@ int refresh_weights() {
 }
 
 int attention_fwd(const Stage& s, hipStream_t st, const void* qkv, void* o, float* lse) {
-  if (s.dt == DT_BF16) HIPCHK(launch_attention_fwd_bf16((const bf16_t*)qkv, (bf16_t*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
+  if (dt_is16(s.dt)) HIPCHK(launch_attention_fwd_16(s.dt, qkv, o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   else HIPCHK(launch_attention_fwd_f32((const float*)qkv, (float*)o, lse, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   return 0;
 }
 int attention_bwd(const Stage& s, hipStream_t st, const void* qkv, const void* o, const void* d_o, const float* lse, float* dsum, void* dqkv) {
-  if (s.dt == DT_BF16)
-    HIPCHK(launch_attention_bwd_bf16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, dsum, (bf16_t*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
+  if (dt_is16(s.dt))
+    HIPCHK(launch_attention_bwd_16(s.dt, qkv, o, d_o, lse, dsum, dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   else
     HIPCHK(launch_attention_bwd_f32((const float*)qkv, (const float*)o, (const float*)d_o, lse, dsum, (float*)dqkv, s.b, s.T, s.H, s.heads, s.cfg.causal, st));
   return 0;
@@ -406,7 +415,7 @@ int forward_block(ActiveOp& a) {
   hipStream_t q = s.lane[a.lane].s;
   const int l = a.next;
   StashView v = view(s, st.stash, l);
-  WtView w = s.dt == DT_BF16 ? wt_view(s, l) : WtView{};
+  WtView w = dt_is16(s.dt) ? wt_view(s, l) : WtView{};
   const char* x = a.cur;
   char* y = (l == s.L - 1) ? s.ys.buf[a.out_buf] : v.y;
   if (s.recompute) { const Stage::Lane& ln = s.lane[a.lane]; v.a = ln.f_a; v.c = ln.f_c; v.gact = ln.f_g; }
@@ -438,7 +447,7 @@ int backward_block(ActiveOp& a) {
   char* da = ln.t_n0;            // d_o is dead once dqkv exists
   const char* dy = a.cur;
   StashView v = view(s, st.stash, l);
-  const bool bt = s.dt == DT_BF16;                      // bf16 input-gradient products read the chunk-major copies
+  const bool bt = dt_is16(s.dt);                        // 16-bit input-gradient products read the chunk-major copies
   WtView w = bt ? wt_view(s, l) : WtView{};
   const char* x = (l == 0) ? s.xs.buf[st.x_slot] : (a.x_first != nullptr && l == a.first) ? a.x_first : view(s, st.stash, l - 1).y;
   char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : (a.dx_first != nullptr && l == a.first) ? a.dx_first : ln.t_dxr[seq % 3];
@@ -502,12 +511,12 @@ int backward_block(ActiveOp& a) {
     red.ln_width[0] = red.ln_width[1] = s.H;
   }
   bool red_done = false;
-  if (s.dt == DT_BF16) {
+  if (dt_is16(s.dt)) {
     for (int i = 0; i < 4; i++) {
       const char* why = gemm_bf16_check(wg[i]);
       if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
     }
-    HIPCHK(launch_gemm_bf16_tn_group(wg, 4, qw, s.fuse_w_reductions ? &red : nullptr, &red_done));
+    HIPCHK(launch_gemm_16_tn_group(s.dt, wg, 4, qw, s.fuse_w_reductions ? &red : nullptr, &red_done));
   } else {
     for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], qw));
   }
@@ -1081,13 +1090,13 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   if (weights == nullptr) return fail(KFKB_E_ARG, "stage_init: null weights");
   if (layers < 1 || hidden < 1 || heads < 1 || seq < 1 || c.micro_batch < 1 || c.mlp_ratio < 1 || c.max_microbatches < 1)
     return fail(KFKB_E_ARG, "stage_init: sizes must be positive");
-  if (c.dtype != KFKB_F32 && c.dtype != KFKB_BF16) return fail(KFKB_E_ARG, "stage_init: unknown dtype %d", c.dtype);
+  if (c.dtype != KFKB_F32 && c.dtype != KFKB_BF16 && c.dtype != KFKB_F16) return fail(KFKB_E_ARG, "stage_init: unknown dtype %d", c.dtype);
   if (c.stage_index < 0 || c.stage_index >= c.num_stages) return fail(KFKB_E_ARG, "stage_init: stage_index outside [0, num_stages)");
   if (hidden % heads != 0) return fail(KFKB_E_ARG, "stage_init: hidden %d not divisible by heads %d", hidden, heads);
   const int d = hidden / heads;
-  if (c.dtype == KFKB_BF16) {
-    if (hidden % 128 != 0) return fail(KFKB_E_ARG, "stage_init: bf16 needs hidden %% 128 == 0 (got %d)", hidden);
-    if (d != 64 && d != 128) return fail(KFKB_E_ARG, "stage_init: bf16 needs head size 64 or 128 (got %d)", d);
+  if (c.dtype != KFKB_F32) {
+    if (hidden % 128 != 0) return fail(KFKB_E_ARG, "stage_init: 16-bit storage needs hidden %% 128 == 0 (got %d)", hidden);
+    if (d != 64 && d != 128) return fail(KFKB_E_ARG, "stage_init: 16-bit storage needs head size 64 or 128 (got %d)", d);
   } else {
     if (hidden % 8 != 0) return fail(KFKB_E_ARG, "stage_init: fp32 needs hidden %% 8 == 0 (got %d)", hidden);
     if (d > 128) return fail(KFKB_E_ARG, "stage_init: fp32 needs head size <= 128 (got %d)", d);
@@ -1098,6 +1107,7 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   s.cfg = c; s.dt = c.dtype; s.L = layers; s.H = hidden; s.heads = heads; s.d = d; s.T = seq; s.b = c.micro_batch;
   s.F = c.mlp_ratio * hidden; s.m = s.b * s.T; s.n = (size_t)s.m * s.H; s.esz = dt_bytes(s.dt); s.Mmax = c.max_microbatches;
   s.recompute = c.recompute != 0;
+  g_prof_dt = s.dt;
   if (s.recompute && ((size_t)s.m * s.F) % 8 != 0) return fail(KFKB_E_ARG, "stage_init: recomputation needs tokens * mlp width %% 8 == 0");
   const size_t H = hidden, F = s.F;
   BlockParams& p = s.po;
@@ -1767,7 +1777,7 @@ int kfkb_profile_report(kfkb_kernel_stat_t* out, int cap) {
 }
 
 // ---- per-kernel entry points --------------------------------------------------------------------
-#define CHECK_DT(dt) if ((dt) != KFKB_F32 && (dt) != KFKB_BF16) return fail(KFKB_E_ARG, "unknown dtype %d", (dt))
+#define CHECK_DT(dt) if ((dt) != KFKB_F32 && (dt) != KFKB_BF16 && (dt) != KFKB_F16) return fail(KFKB_E_ARG, "unknown dtype %d", (dt))
 
 int kfkb_op_gemm(int dtype, int kind, int epilogue, int M, int N, int K, const void* A, const void* B, const void* bias,
                  const void* residual, void* C, void* C2, float* Cacc, void* stream) {
@@ -1782,10 +1792,10 @@ int kfkb_op_gemm(int dtype, int kind, int epilogue, int M, int N, int K, const v
     return fail(KFKB_E_ARG, "kfkb_op_gemm: epilogue %d misses an operand", epilogue);
   if (M == 0 || N == 0) return 0;
   GemmArgs a{kind, epilogue, M, N, K, A, B, bias, residual, C, C2, Cacc};
-  if (dtype == KFKB_BF16) {
+  if (dtype != KFKB_F32) {
     const char* why = gemm_bf16_check(a);
     if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, M, N, K);
-    HIPCHK(launch_gemm_bf16(a, (hipStream_t)stream));
+    HIPCHK(launch_gemm_16(dtype, a, (hipStream_t)stream));
   } else {
     HIPCHK(launch_gemm_f32(a, (hipStream_t)stream));
   }
@@ -1868,7 +1878,7 @@ int kfkb_op_gelu_bwd(int dtype, const void* dg, const void* u, void* du, size_t 
 static int check_attn(const char* who, int dtype, int b, int T, int H, int heads) {
   if (b < 0 || T < 0 || H < 1 || heads < 1 || H % heads != 0) return fail(KFKB_E_ARG, "%s: bad shape", who);
   const int d = H / heads;
-  if (dtype == KFKB_BF16 && d != 64 && d != 128) return fail(KFKB_E_ARG, "%s: bf16 needs head size 64 or 128 (got %d)", who, d);
+  if (dtype != KFKB_F32 && d != 64 && d != 128) return fail(KFKB_E_ARG, "%s: 16-bit storage needs head size 64 or 128 (got %d)", who, d);
   if (dtype == KFKB_F32 && (d > 128 || T > 4096)) return fail(KFKB_E_ARG, "%s: fp32 needs head size <= 128 and T <= 4096", who);
   return 0;
 }
@@ -1879,7 +1889,7 @@ int kfkb_op_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int b
   TRY(check_attn("kfkb_op_attention_fwd", dtype, b, T, H, heads));
   if (b == 0 || T == 0) return 0;
   if (!qkv || !o || !lse) return fail(KFKB_E_ARG, "kfkb_op_attention_fwd: null pointer");
-  if (dtype == KFKB_BF16) HIPCHK(launch_attention_fwd_bf16((const bf16_t*)qkv, (bf16_t*)o, lse, b, T, H, heads, causal, (hipStream_t)stream));
+  if (dtype != KFKB_F32) HIPCHK(launch_attention_fwd_16(dtype, qkv, o, lse, b, T, H, heads, causal, (hipStream_t)stream));
   else HIPCHK(launch_attention_fwd_f32((const float*)qkv, (float*)o, lse, b, T, H, heads, causal, (hipStream_t)stream));
   return 0;
 }
@@ -1890,8 +1900,8 @@ int kfkb_op_attention_bwd(int dtype, const void* qkv, const void* o, const void*
   TRY(check_attn("kfkb_op_attention_bwd", dtype, b, T, H, heads));
   if (b == 0 || T == 0) return 0;
   if (!qkv || !o || !d_o || !lse || !dsum || !dqkv) return fail(KFKB_E_ARG, "kfkb_op_attention_bwd: null pointer");
-  if (dtype == KFKB_BF16)
-    HIPCHK(launch_attention_bwd_bf16((const bf16_t*)qkv, (const bf16_t*)o, (const bf16_t*)d_o, lse, dsum, (bf16_t*)dqkv, b, T, H, heads, causal, (hipStream_t)stream));
+  if (dtype != KFKB_F32)
+    HIPCHK(launch_attention_bwd_16(dtype, qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, (hipStream_t)stream));
   else
     HIPCHK(launch_attention_bwd_f32((const float*)qkv, (const float*)o, (const float*)d_o, lse, dsum, (float*)dqkv, b, T, H, heads, causal, (hipStream_t)stream));
   return 0;

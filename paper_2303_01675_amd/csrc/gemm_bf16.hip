@@ -1,4 +1,5 @@
-// bf16 GEMMs of the stage on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16), fp32 accumulation.
+// 16-bit (bf16 or fp16 storage) GEMMs of the stage on the gfx950 matrix cores (v_mfma_f32_32x32x16_bf16 / _f16),
+// fp32 accumulation.
 //
 //   NT:  C[M,N] = A[M,K] . B[N,K]^T     both operands contiguous along the reduction axis
 //        (forward with the weight copy stored [out,in]; input gradients with the weights as given)
@@ -31,6 +32,24 @@
 #include <cstdlib>
 
 namespace kfkb {
+// Built once per 16-bit storage type: this file as it is for bf16, through gemm_f16.hip (which defines
+// KFKB_H16_IS_F16) for fp16.  Everything type-dependent lives in a namespace of its own, so the two builds share no
+// symbol; the launchers the rest of the library calls are defined at the end of the file.
+#ifdef KFKB_H16_IS_F16
+namespace f16k {
+typedef f16_t h16_t;
+typedef f16x8 h16x8;
+typedef f16x4 h16x4;
+#define KFKB_MFMA_H16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0)
+#else
+namespace bf16k {
+typedef bf16_t h16_t;
+typedef bf16x8 h16x8;
+typedef bf16x4 h16x4;
+#define KFKB_MFMA_H16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0)
+#endif
+hipError_t launch_gemm_h16(const GemmArgs& g, hipStream_t s);
+const char* gemm_h16_check(const GemmArgs& g);
 
 constexpr int BK = 64;             // slice depth of the register-staged TN kernel
 
@@ -56,9 +75,9 @@ __device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm,
 }
 
 template <int EPI>
-__device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, int n, int N, const bf16_t* __restrict__ bias,
-                                              const bf16_t* __restrict__ residual, bf16_t* __restrict__ C,
-                                              bf16_t* __restrict__ C2, float* __restrict__ Cacc) {
+__device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, int n, int N, const h16_t* __restrict__ bias,
+                                              const h16_t* __restrict__ residual, h16_t* __restrict__ C,
+                                              h16_t* __restrict__ C2, float* __restrict__ Cacc) {
   float v[4] = {acc[q * 4 + 0], acc[q * 4 + 1], acc[q * 4 + 2], acc[q * 4 + 3]};
   const size_t o = (size_t)m * N + n;
   if (EPI == KFKB_EPI_ACCUM) {
@@ -69,29 +88,29 @@ __device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, i
     return;
   }
   if (EPI == KFKB_EPI_BIAS || EPI == KFKB_EPI_BIAS_GELU || EPI == KFKB_EPI_BIAS_RES) {
-    const bf16x4 b = *reinterpret_cast<const bf16x4*>(bias + n);
+    const h16x4 b = *reinterpret_cast<const h16x4*>(bias + n);
 #pragma unroll
     for (int e = 0; e < 4; e++) v[e] += (float)b[e];
   }
   if (EPI == KFKB_EPI_BIAS_RES) {
-    const bf16x4 r = *reinterpret_cast<const bf16x4*>(residual + o);
+    const h16x4 r = *reinterpret_cast<const h16x4*>(residual + o);
 #pragma unroll
     for (int e = 0; e < 4; e++) v[e] += (float)r[e];
   }
   if (EPI == KFKB_EPI_GELU_BWD) {
-    const bf16x4 r = *reinterpret_cast<const bf16x4*>(residual + o);
+    const h16x4 r = *reinterpret_cast<const h16x4*>(residual + o);
 #pragma unroll
     for (int e = 0; e < 4; e++) v[e] *= gelu_grad_f((float)r[e]);
   }
-  bf16x4 out;
+  h16x4 out;
 #pragma unroll
-  for (int e = 0; e < 4; e++) out[e] = (bf16_t)v[e];
-  *reinterpret_cast<bf16x4*>(C + o) = out;
+  for (int e = 0; e < 4; e++) out[e] = (h16_t)v[e];
+  *reinterpret_cast<h16x4*>(C + o) = out;
   if (EPI == KFKB_EPI_BIAS_GELU) {
-    bf16x4 g;
+    h16x4 g;
 #pragma unroll
-    for (int e = 0; e < 4; e++) g[e] = (bf16_t)gelu_f((float)out[e]);   // gelu of the stored (rounded) pre-activation
-    *reinterpret_cast<bf16x4*>(C2 + o) = g;
+    for (int e = 0; e < 4; e++) g[e] = (h16_t)gelu_f((float)out[e]);   // gelu of the stored (rounded) pre-activation
+    *reinterpret_cast<h16x4*>(C2 + o) = g;
   }
 }
 
@@ -135,7 +154,7 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 // ------------------------------------------------------------------------------------------------
 template <int TM, int TN, typename L>
 __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk) {
-  bf16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
+  h16x8 fa0[TM], fb0[TN], fa1[TM], fb1[TN];
   lay.prologue();
   wait_vmcnt<L::WAIT_PRO>();
   __syncthreads();
@@ -144,7 +163,7 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
 #pragma unroll
   for (int i = 0; i < TM; i++) fa0[i] = lay.rd_a(0, 0, i);
 
-  auto step = [&](bf16x8 (&fa)[TM], bf16x8 (&fb)[TN], bf16x8 (&na)[TM], bf16x8 (&nb)[TN], int npc, int nks, auto&& dma) {
+  auto step = [&](h16x8 (&fa)[TM], h16x8 (&fb)[TN], h16x8 (&na)[TM], h16x8 (&nb)[TN], int npc, int nks, auto&& dma) {
     constexpr int NR = TM + TN;
     constexpr int PER = (NR + TN - 2) / (TN - 1);      // reads per group so that the last group has none
     auto rd = [&](int r) {
@@ -159,7 +178,7 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
         // the next ones): each issues while that MFMA occupies the matrix pipe
 #pragma unroll
         for (int i = 0; i < TM; i++) {
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = KFKB_MFMA_H16(fb[j], fa[i], acc[i][j]);
           __builtin_amdgcn_sched_barrier(0);
           if (i == 0) dma(j);
           else { const int r = j * PER + (i - 1); if (i - 1 < PER && r < NR) rd(r); }
@@ -170,7 +189,7 @@ __device__ __forceinline__ void main_loop(L& lay, f32x16 (&acc)[TM][TN], int nk)
         for (int r = j * PER; r < (j + 1) * PER && r < NR; r++) rd(r);
         dma(j);
 #pragma unroll
-        for (int i = 0; i < TM; i++) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+        for (int i = 0; i < TM; i++) acc[i][j] = KFKB_MFMA_H16(fb[j], fa[i], acc[i][j]);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -203,8 +222,8 @@ struct NtLayout32 {
   static constexpr int PERIOD = RING, WAIT_PRO = 5 * TN, WAIT_MID = 4 * TN;
   static constexpr size_t LDS_BYTES = (size_t)RING * (A_SLOT + B_SLOT) * 2;
   i32x4 ra, rb; unsigned lds0; int wave, nk, sb; int voa[TN], vob[TN];
-  const bf16_t* fa_base[2]; const bf16_t* fb_base[2];
-  __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
+  const h16_t* fa_base[2]; const h16_t* fb_base[2];
+  __device__ __forceinline__ void init(char* smem, const h16_t* A, const h16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
     wave = wave_; nk = K / CK_; sb = BT ? N * CK_ * 2 : CK_ * 2;      // bytes from one chunk of B to the next
     ra = make_rsrc(A, (size_t)M * K * 2); rb = make_rsrc(B, (size_t)N * K * 2);
     lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
@@ -216,8 +235,8 @@ struct NtLayout32 {
     }
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
     const int frow = lane & 31, fhalf = lane >> 5, fsw = (lane >> 2) & 3;
-    const bf16_t* As = reinterpret_cast<const bf16_t*>(smem);
-    const bf16_t* Bs = As + RING * A_SLOT;
+    const h16_t* As = reinterpret_cast<const h16_t*>(smem);
+    const h16_t* Bs = As + RING * A_SLOT;
 #pragma unroll
     for (int ks = 0; ks < 2; ks++) {
       fa_base[ks] = As + (wm0 + frow) * CK_ + (((ks * 2 + fhalf) ^ fsw) << 3);
@@ -240,8 +259,8 @@ struct NtLayout32 {
   }
   __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, kc + 3, (pc + 3) & 3); }
   __device__ __forceinline__ void dma1(int j, int kc, int pc) { dma_a(j, kc + 4, pc); }
-  __device__ __forceinline__ bf16x8 rd_a(int slot, int ks, int i) { return *reinterpret_cast<const bf16x8*>(fa_base[ks] + slot * A_SLOT + i * 32 * CK_); }
-  __device__ __forceinline__ bf16x8 rd_b(int slot, int ks, int j) { return *reinterpret_cast<const bf16x8*>(fb_base[ks] + slot * B_SLOT + j * 32 * CK_); }
+  __device__ __forceinline__ h16x8 rd_a(int slot, int ks, int i) { return *reinterpret_cast<const h16x8*>(fa_base[ks] + slot * A_SLOT + i * 32 * CK_); }
+  __device__ __forceinline__ h16x8 rd_b(int slot, int ks, int j) { return *reinterpret_cast<const h16x8*>(fb_base[ks] + slot * B_SLOT + j * 32 * CK_); }
 };
 
 // NT operands with a chunk-major B (the stage's weight copies) and K % 64 == 0: A is staged in slices of 64
@@ -262,8 +281,8 @@ struct NtLayout64 {
   static constexpr int PERIOD = 12, WAIT_PRO = 5 * TN, WAIT_MID = 4 * TN;
   static constexpr size_t LDS_BYTES = (size_t)(A_RING * A_SLICE + RING * B_SLOT) * 2;
   i32x4 ra, rb; unsigned lds0; int wave, nk, ns, sb; int voa[2 * TN], vob[TN];
-  const bf16_t* fa_base[4]; const bf16_t* fb_base[2];
-  __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
+  const h16_t* fa_base[4]; const h16_t* fb_base[2];
+  __device__ __forceinline__ void init(char* smem, const h16_t* A, const h16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
     wave = wave_; nk = K / CK_; ns = K / 64; sb = N * CK_ * 2;       // bytes from one chunk of B to the next
     ra = make_rsrc(A, (size_t)M * K * 2); rb = make_rsrc(B, (size_t)N * K * 2);
     lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
@@ -276,8 +295,8 @@ struct NtLayout64 {
     for (int i = 0; i < TN; i++) vob[i] = ((n0 + (i * 4 + wave) * 16 + brow) * CK_ + bpiece * 8) * 2;
     const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
     const int frow = lane & 31, fhalf = lane >> 5, fsw_a = (lane >> 1) & 7, fsw_b = (lane >> 2) & 3;
-    const bf16_t* As = reinterpret_cast<const bf16_t*>(smem);
-    const bf16_t* Bs = As + A_RING * A_SLICE;
+    const h16_t* As = reinterpret_cast<const h16_t*>(smem);
+    const h16_t* Bs = As + A_RING * A_SLICE;
 #pragma unroll
     for (int q = 0; q < 4; q++) fa_base[q] = As + (wm0 + frow) * 64 + (((q * 2 + fhalf) ^ fsw_a) << 3);   // q = 2 (chunk & 1) + k-step
 #pragma unroll
@@ -312,10 +331,10 @@ struct NtLayout64 {
     if (pc & 1) dma_a(j, (kc >> 1) + 3, (pc >> 1) % 3);
     else dma_a(TN + j, (kc >> 1) + 2, ((pc >> 1) + 2) % 3);
   }
-  __device__ __forceinline__ bf16x8 rd_a(int pc, int ks, int i) {
-    return *reinterpret_cast<const bf16x8*>(fa_base[(pc & 1) * 2 + ks] + ((pc >> 1) % 3) * A_SLICE + i * 32 * 64);
+  __device__ __forceinline__ h16x8 rd_a(int pc, int ks, int i) {
+    return *reinterpret_cast<const h16x8*>(fa_base[(pc & 1) * 2 + ks] + ((pc >> 1) % 3) * A_SLICE + i * 32 * 64);
   }
-  __device__ __forceinline__ bf16x8 rd_b(int pc, int ks, int j) { return *reinterpret_cast<const bf16x8*>(fb_base[ks] + (pc & 3) * B_SLOT + j * 32 * CK_); }
+  __device__ __forceinline__ h16x8 rd_b(int pc, int ks, int j) { return *reinterpret_cast<const h16x8*>(fb_base[ks] + (pc & 3) * B_SLOT + j * 32 * CK_); }
 };
 
 // TN operands: X[K, cols] row-major, both (K = reduction).  LDS chunk [32 reduction rows][cols] as in memory, the
@@ -330,8 +349,8 @@ struct TnLayout {
   static constexpr int CA = BM / 8, CB = BN / 8;           // 16-byte pieces per row
   static constexpr int RA = 64 / CA, RB = 64 / CB;         // rows one DMA instruction (1 KiB) covers
   i32x4 ra, rb; unsigned lds0; int wave, nk, sa, sb; int voa[TN], vob[TN];
-  const bf16_t* fa_base[TM]; const bf16_t* fb_base[TN];
-  __device__ __forceinline__ void init(char* smem, const bf16_t* A, const bf16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
+  const h16_t* fa_base[TM]; const h16_t* fb_base[TN];
+  __device__ __forceinline__ void init(char* smem, const h16_t* A, const h16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
     wave = wave_; nk = K / CK_;
     ra = make_rsrc(A, (size_t)K * M * 2); rb = make_rsrc(B, (size_t)K * N * 2);
     sa = CK_ * M * 2; sb = CK_ * N * 2;                    // bytes per chunk step
@@ -347,8 +366,8 @@ struct TnLayout {
     const int g16 = lane >> 4, j16 = lane & 15;
     const int tr_row = (g16 >> 1) * 8 + (j16 >> 2), tr_col = (g16 & 1) * 16 + (j16 & 3) * 4;
     const int sw = 4 * (tr_row & 3);
-    const bf16_t* As = reinterpret_cast<const bf16_t*>(smem);
-    const bf16_t* Bs = As + RING * A_SLOT;
+    const h16_t* As = reinterpret_cast<const h16_t*>(smem);
+    const h16_t* Bs = As + RING * A_SLOT;
 #pragma unroll
     for (int i = 0; i < TM; i++) {
       const int col = wm0 + i * 32 + tr_col;
@@ -375,16 +394,16 @@ struct TnLayout {
   }
   __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, kc + 3, (pc + 3) & 3); }
   __device__ __forceinline__ void dma1(int j, int kc, int pc) { dma_a(j, kc + 4, pc); }
-  static __device__ __forceinline__ bf16x8 tr_pair(const bf16_t* p, int second_offset) {
+  static __device__ __forceinline__ h16x8 tr_pair(const h16_t* p, int second_offset) {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + second_offset));
-    union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+    union { struct { s16x4 a, b; } s; h16x8 v; } u;
     u.s.a = lo; u.s.b = hi;
     return u.v;
   }
-  __device__ __forceinline__ bf16x8 rd_a(int slot, int ks, int i) { return tr_pair(fa_base[i] + slot * A_SLOT + ks * 16 * BM, 4 * BM); }
-  __device__ __forceinline__ bf16x8 rd_b(int slot, int ks, int j) { return tr_pair(fb_base[j] + slot * B_SLOT + ks * 16 * BN, 4 * BN); }
+  __device__ __forceinline__ h16x8 rd_a(int slot, int ks, int i) { return tr_pair(fa_base[i] + slot * A_SLOT + ks * 16 * BM, 4 * BM); }
+  __device__ __forceinline__ h16x8 rd_b(int slot, int ks, int j) { return tr_pair(fb_base[j] + slot * B_SLOT + ks * 16 * BN, 4 * BN); }
 };
 
 // ---- epilogues ---------------------------------------------------------------------------------
@@ -395,8 +414,8 @@ struct TnLayout {
 template <int BM, int BN> constexpr size_t epilogue_lds_bytes() { return (size_t)4 * (BM / 2) * (BN + 16); }
 template <int BM, int BN, int EPI>
 __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64], char* smem, int M, int N, int m0, int n0, int lane, int wave,
-                                                const bf16_t* __restrict__ bias, const bf16_t* __restrict__ residual,
-                                                bf16_t* __restrict__ C, bf16_t* __restrict__ C2) {
+                                                const h16_t* __restrict__ bias, const h16_t* __restrict__ residual,
+                                                h16_t* __restrict__ C, h16_t* __restrict__ C2) {
   constexpr int TM = BM / 64, TN = BN / 64, WR = BM / 2, WC = BN / 2;
   constexpr int RS = WC * 2 + 16;                                 // row stride in bytes
   const int wm0 = (wave >> 1) * WR, wn0 = (wave & 1) * WC;
@@ -408,13 +427,13 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
 #pragma unroll
   for (int i = 0; i < TM; i++) {
     const int m = min(m0 + wm0 + i * 32 + frow, M - 1);           // rows past M are computed and dropped
-    bf16x4 rr[TN][4];
+    h16x4 rr[TN][4];
     if constexpr (HAS_RES) {
 #pragma unroll
       for (int j = 0; j < TN; j++)
 #pragma unroll
         for (int q = 0; q < 4; q++)
-          rr[j][q] = *reinterpret_cast<const bf16x4*>(residual + (size_t)m * N + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+          rr[j][q] = *reinterpret_cast<const h16x4*>(residual + (size_t)m * N + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
     }
 #pragma unroll
     for (int j = 0; j < TN; j++)
@@ -422,7 +441,7 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
       for (int q = 0; q < 4; q++) {
         float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
         if constexpr (HAS_BIAS) {
-          const bf16x4 b = *reinterpret_cast<const bf16x4*>(bias + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+          const h16x4 b = *reinterpret_cast<const h16x4*>(bias + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
 #pragma unroll
           for (int e = 0; e < 4; e++) v[e] += (float)b[e];
         }
@@ -434,10 +453,10 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
 #pragma unroll
           for (int e = 0; e < 4; e++) v[e] *= gelu_grad_f((float)rr[j][q][e]);
         }
-        bf16x4 o;
+        h16x4 o;
 #pragma unroll
-        for (int e = 0; e < 4; e++) o[e] = (bf16_t)v[e];
-        *reinterpret_cast<bf16x4*>(ew + (i * 32 + frow) * RS + (j * 32 + q * 8 + fhalf * 4) * 2) = o;
+        for (int e = 0; e < 4; e++) o[e] = (h16_t)v[e];
+        *reinterpret_cast<h16x4*>(ew + (i * 32 + frow) * RS + (j * 32 + q * 8 + fhalf * 4) * 2) = o;
       }
   }
   wait_lgkm0();
@@ -446,24 +465,24 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
 #pragma unroll
   for (int r0 = 0; r0 < WR; r0 += RPI) {
     const int r = r0 + er, m = m0 + wm0 + r;
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(ew + r * RS + ec * 16);
+    const h16x8 v = *reinterpret_cast<const h16x8*>(ew + r * RS + ec * 16);
     if (m < M) {
       const size_t o = (size_t)m * N + n0 + wn0 + ec * 8;
-      *reinterpret_cast<bf16x8*>(C + o) = v;
+      *reinterpret_cast<h16x8*>(C + o) = v;
       if constexpr (EPI == KFKB_EPI_BIAS_GELU) {
-        bf16x8 gl;
+        h16x8 gl;
 #pragma unroll
-        for (int e = 0; e < 8; e++) gl[e] = (bf16_t)gelu_f((float)v[e]);
-        *reinterpret_cast<bf16x8*>(C2 + o) = gl;
+        for (int e = 0; e < 8; e++) gl[e] = (h16_t)gelu_f((float)v[e]);
+        *reinterpret_cast<h16x8*>(C2 + o) = gl;
       }
     }
   }
 }
 
 template <int BM, int BN, int EPI, bool BT>
-__global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                                 const bf16_t* __restrict__ bias, const bf16_t* __restrict__ residual,
-                                                 bf16_t* __restrict__ C, bf16_t* __restrict__ C2, float* __restrict__ Cacc,
+__global__ void __launch_bounds__(256) gemm_h16_nt_kernel(int M, int N, int K, const h16_t* __restrict__ A, const h16_t* __restrict__ B,
+                                                 const h16_t* __restrict__ bias, const h16_t* __restrict__ residual,
+                                                 h16_t* __restrict__ C, h16_t* __restrict__ C2, float* __restrict__ Cacc,
                                                  int tiles_m, int tiles_n) {
   constexpr int TM = BM / 64, TN = BN / 64;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
@@ -503,8 +522,8 @@ __global__ void __launch_bounds__(256) gemm_bf16_nt_kernel(int M, int N, int K, 
 
 // C[M,N] (+)= A[K,M]^T . B[K,N]; EPI NONE (bf16 C) or ACCUM (fp32 Cacc +=)
 template <int BM, int BN, int EPI>
-__device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __restrict__ A, const bf16_t* __restrict__ B,
-                                        bf16_t* __restrict__ C, float* __restrict__ Cacc, int tm, int tn, char* smem) {
+__device__ __forceinline__ void tn_tile(int M, int N, int K, const h16_t* __restrict__ A, const h16_t* __restrict__ B,
+                                        h16_t* __restrict__ C, float* __restrict__ Cacc, int tm, int tn, char* smem) {
   constexpr int TM = BM / 64, TN = BN / 64;
   const int m0 = tm * BM, n0 = tn * BN;
   const int lane = threadIdx.x & 63;
@@ -537,8 +556,8 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const bf16_t* __res
 
 
 template <int BM, int BN, int EPI>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                           const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+__global__ void __launch_bounds__(256) gemm_h16_tn_kernel(int M, int N, int K, const h16_t* __restrict__ A,
+                                                           const h16_t* __restrict__ B, h16_t* __restrict__ C,
                                                            float* __restrict__ Cacc, int tiles_m, int tiles_n) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   int tm, tn; bool valid;
@@ -549,7 +568,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_kernel(int M, int N, int K, 
 
 // Several weight-gradient products that share the reduction length K (the token axis) in one launch:
 // a backward pass of one block has four of them, each too small to fill the chip on its own.
-struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const bf16_t* A; const bf16_t* B; float* Cacc; };
+struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const h16_t* A; const h16_t* B; float* Cacc; };
 struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 
 // The small reductions of the same step, done by extra workgroups of the same launch, on the CUs the tiles leave
@@ -559,29 +578,29 @@ struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 //   partial[parts][2][width] (fp32) that the LayerNorm backward kernels left behind.
 // Work items are strips of 64 columns, dealt round-robin to the reduce workgroups; one workgroup owns a strip from
 // the first row to the last and adds in a fixed order, so the sums do not depend on timing or on the launch shape.
-struct RedColsum { const bf16_t* dy; float* out; int width, first_item; };
+struct RedColsum { const h16_t* dy; float* out; int width, first_item; };
 struct RedLnFinal { const float* partial; float* out0; float* out1; int parts, width, first_item; };
 struct ReduceGroup { int n_colsum, n_ln, rows, total_items; RedColsum c[4]; RedLnFinal ln[2]; };
 
 __device__ __forceinline__ void reduce_colsum_strip(const RedColsum& pr, int strip, int rows, float* red) {
   const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;              // 8 lanes x 16 bytes = one 128-byte row piece
-  const bf16_t* src = pr.dy + strip * 64 + cl * 8;
+  const h16_t* src = pr.dy + strip * 64 + cl * 8;
   const size_t w = pr.width;
   float a[8];
 #pragma unroll
   for (int e = 0; e < 8; e++) a[e] = 0.f;
   int r = rl;
   for (; r + 32 * 15 < rows; r += 32 * 16) {                          // sixteen loads in flight per lane
-    bf16x8 v[16];
+    h16x8 v[16];
 #pragma unroll
-    for (int u = 0; u < 16; u++) v[u] = *reinterpret_cast<const bf16x8*>(src + (size_t)(r + 32 * u) * w);
+    for (int u = 0; u < 16; u++) v[u] = *reinterpret_cast<const h16x8*>(src + (size_t)(r + 32 * u) * w);
 #pragma unroll
     for (int u = 0; u < 16; u++)
 #pragma unroll
       for (int e = 0; e < 8; e++) a[e] += (float)v[u][e];
   }
   for (; r < rows; r += 32) {
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(src + (size_t)r * w);
+    const h16x8 v = *reinterpret_cast<const h16x8*>(src + (size_t)r * w);
 #pragma unroll
     for (int e = 0; e < 8; e++) a[e] += (float)v[e];
   }
@@ -654,7 +673,7 @@ __device__ __forceinline__ void reduce_role(const ReduceGroup& rg, int rb, int n
 }
 
 template <int BM, int BN>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp, ReduceGroup rg, int reduce_blocks) {
+__global__ void __launch_bounds__(256) gemm_h16_tn_grouped_kernel(TnGroup grp, ReduceGroup rg, int reduce_blocks) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   // The first blocks of the grid (a multiple of 8, so the tiles keep their XCDs) reduce: they are on their CUs from
   // the start and finish in the shadow of the tiles, also when the tiles need several rounds.
@@ -677,26 +696,26 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_grouped_kernel(TnGroup grp, 
 // TN kernel, register-staged variant: accepts a ragged reduction length K (zero-fills the tail).
 // Tiles are stored [reduction row][BM + 32].
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ bf16x8 lds_tr_frag(const bf16_t* p, int row_stride) {
+__device__ __forceinline__ h16x8 lds_tr_frag(const h16_t* p, int row_stride) {
   typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * row_stride));
-  union { struct { s16x4 a, b; } s; bf16x8 v; } u;
+  union { struct { s16x4 a, b; } s; h16x8 v; } u;
   u.s.a = lo; u.s.b = hi;
   return u.v;
 }
 
 template <int BM, int BN, int EPI>
-__global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, int K, const bf16_t* __restrict__ A,
-                                                           const bf16_t* __restrict__ B, bf16_t* __restrict__ C,
+__global__ void __launch_bounds__(256) gemm_h16_tn_staged_kernel(int M, int N, int K, const h16_t* __restrict__ A,
+                                                           const h16_t* __restrict__ B, h16_t* __restrict__ C,
                                                            float* __restrict__ Cacc, int tiles_m, int tiles_n) {
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int SA = BM + 32, SB = BN + 32;          // LDS row strides (elements): +64 bytes per row
   constexpr int CA = BM / 8, CB = BN / 8;            // 16-byte chunks per tile row
   constexpr int LA = BM / 32, LB = BN / 32;          // chunks per thread per slice
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  bf16_t* As = reinterpret_cast<bf16_t*>(smem);                       // [2][64][SA]
-  bf16_t* Bs = As + 2 * BK * SA;                                      // [2][64][SB]
+  h16_t* As = reinterpret_cast<h16_t*>(smem);                       // [2][64][SA]
+  h16_t* Bs = As + 2 * BK * SA;                                      // [2][64][SB]
 
   int tm, tn; bool valid;
   tile_of_block(tiles_m, tiles_n, tm, tn, valid);
@@ -705,37 +724,37 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2);
 
-  bf16x8 ra[LA], rb[LB];
+  h16x8 ra[LA], rb[LB];
   auto load_global = [&](int kt) {
 #pragma unroll
     for (int i = 0; i < LA; i++) {
       const int c = tid % CA, r = tid / CA + (256 / CA) * i;
       const int k = kt * BK + r;
-      bf16x8 z;
+      h16x8 z;
 #pragma unroll
-      for (int e = 0; e < 8; e++) z[e] = (bf16_t)0.f;
-      ra[i] = (k < K) ? *reinterpret_cast<const bf16x8*>(A + (size_t)k * M + m0 + c * 8) : z;
+      for (int e = 0; e < 8; e++) z[e] = (h16_t)0.f;
+      ra[i] = (k < K) ? *reinterpret_cast<const h16x8*>(A + (size_t)k * M + m0 + c * 8) : z;
     }
 #pragma unroll
     for (int i = 0; i < LB; i++) {
       const int c = tid % CB, r = tid / CB + (256 / CB) * i;
       const int k = kt * BK + r;
-      bf16x8 z;
+      h16x8 z;
 #pragma unroll
-      for (int e = 0; e < 8; e++) z[e] = (bf16_t)0.f;
-      rb[i] = (k < K) ? *reinterpret_cast<const bf16x8*>(B + (size_t)k * N + n0 + c * 8) : z;
+      for (int e = 0; e < 8; e++) z[e] = (h16_t)0.f;
+      rb[i] = (k < K) ? *reinterpret_cast<const h16x8*>(B + (size_t)k * N + n0 + c * 8) : z;
     }
   };
   auto store_lds = [&](int st) {
 #pragma unroll
     for (int i = 0; i < LA; i++) {
       const int c = tid % CA, r = tid / CA + (256 / CA) * i;
-      *reinterpret_cast<bf16x8*>(As + (st * BK + r) * SA + c * 8) = ra[i];
+      *reinterpret_cast<h16x8*>(As + (st * BK + r) * SA + c * 8) = ra[i];
     }
 #pragma unroll
     for (int i = 0; i < LB; i++) {
       const int c = tid % CB, r = tid / CB + (256 / CB) * i;
-      *reinterpret_cast<bf16x8*>(Bs + (st * BK + r) * SB + c * 8) = rb[i];
+      *reinterpret_cast<h16x8*>(Bs + (st * BK + r) * SB + c * 8) = rb[i];
     }
   };
 
@@ -762,7 +781,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, 
     if (kt + 1 < nk) load_global(kt + 1);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ks++) {
-      bf16x8 fa[TM], fb[TN];
+      h16x8 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; i++)
         fa[i] = lds_tr_frag(As + (cur * BK + ks * 16 + tr_row) * SA + wm0 + i * 32 + tr_col, SA);
@@ -773,7 +792,7 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, 
       for (int i = 0; i < TM; i++)
 #pragma unroll
         for (int j = 0; j < TN; j++)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          acc[i][j] = KFKB_MFMA_H16(fb[j], fa[i], acc[i][j]);
     }
     if (kt + 1 < nk) store_lds(cur ^ 1);
     __syncthreads();
@@ -794,25 +813,25 @@ __global__ void __launch_bounds__(256) gemm_bf16_tn_staged_kernel(int M, int N, 
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-const char* gemm_bf16_check(const GemmArgs& g) {
-  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return "bf16 GEMM: empty shape";
+const char* gemm_h16_check(const GemmArgs& g) {
+  if (g.M <= 0 || g.N <= 0 || g.K <= 0) return "16-bit GEMM: empty shape";
   if (g.kind == KFKB_GEMM_NT) {
-    if (g.N % 128 != 0) return "bf16 NT GEMM needs N % 128 == 0";
-    if (g.K % 32 != 0) return "bf16 NT GEMM needs K % 32 == 0";
-    if (g.b_tiled && g.K % 64 != 0) return "bf16 NT GEMM with a chunk-major B needs K % 64 == 0";
+    if (g.N % 128 != 0) return "16-bit NT GEMM needs N % 128 == 0";
+    if (g.K % 32 != 0) return "16-bit NT GEMM needs K % 32 == 0";
+    if (g.b_tiled && g.K % 64 != 0) return "16-bit NT GEMM with a chunk-major B needs K % 64 == 0";
   } else if (g.kind == KFKB_GEMM_TN) {
-    if (g.M % 128 != 0 || g.N % 128 != 0) return "bf16 TN GEMM needs M % 128 == 0 and N % 128 == 0";
-    if (g.epilogue != KFKB_EPI_ACCUM && g.epilogue != KFKB_EPI_NONE) return "bf16 TN GEMM supports epilogues NONE and ACCUM";
+    if (g.M % 128 != 0 || g.N % 128 != 0) return "16-bit TN GEMM needs M % 128 == 0 and N % 128 == 0";
+    if (g.epilogue != KFKB_EPI_ACCUM && g.epilogue != KFKB_EPI_NONE) return "16-bit TN GEMM supports epilogues NONE and ACCUM";
   } else {
-    return "bf16 GEMM supports the NT and TN forms";
+    return "16-bit GEMM supports the NT and TN forms";
   }
   // the kernels address their operands with 32-bit byte offsets
-  if ((double)g.M * g.K * 2 >= 4294967296.0 || (double)g.N * g.K * 2 >= 4294967296.0) return "bf16 GEMM: an operand of 4 GiB or more";
+  if ((double)g.M * g.K * 2 >= 4294967296.0 || (double)g.N * g.K * 2 >= 4294967296.0) return "16-bit GEMM: an operand of 4 GiB or more";
   return nullptr;
 }
 
 template <int BM, int BN> constexpr size_t tile_lds_bytes() {
-  return std::max((size_t)RING * (BM + BN) * CK_ * sizeof(bf16_t), epilogue_lds_bytes<BM, BN>());
+  return std::max((size_t)RING * (BM + BN) * CK_ * sizeof(h16_t), epilogue_lds_bytes<BM, BN>());
 }
 template <int BM, int BN> constexpr size_t tile64_lds_bytes() { return std::max(NtLayout64<BM, BN>::LDS_BYTES, epilogue_lds_bytes<BM, BN>()); }
 
@@ -821,7 +840,7 @@ static hipError_t launch_nt_bt(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   constexpr size_t smem = BT ? tile64_lds_bytes<BM, BN>() : tile_lds_bytes<BM, BN>();
-  auto kern = gemm_bf16_nt_kernel<BM, BN, EPI, BT>;
+  auto kern = gemm_h16_nt_kernel<BM, BN, EPI, BT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -829,8 +848,8 @@ static hipError_t launch_nt_bt(const GemmArgs& g, hipStream_t s) {
     attr_set = true;
   }
   klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_NT + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
-          (const bf16_t*)g.A, (const bf16_t*)g.B, (const bf16_t*)g.bias, (const bf16_t*)g.residual, (bf16_t*)g.C,
-          (bf16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
+          (const h16_t*)g.A, (const h16_t*)g.B, (const h16_t*)g.bias, (const h16_t*)g.residual, (h16_t*)g.C,
+          (h16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
 }
 template <int BM, int BN, int EPI>
@@ -842,8 +861,8 @@ template <int BM, int BN, int EPI>
 static hipError_t launch_tn_staged(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
-  const size_t smem = (size_t)2 * BK * (BM + 32 + BN + 32) * sizeof(bf16_t);
-  auto kern = gemm_bf16_tn_staged_kernel<BM, BN, EPI>;
+  const size_t smem = (size_t)2 * BK * (BM + 32 + BN + 32) * sizeof(h16_t);
+  auto kern = gemm_h16_tn_staged_kernel<BM, BN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -851,7 +870,7 @@ static hipError_t launch_tn_staged(const GemmArgs& g, hipStream_t s) {
     attr_set = true;
   }
   klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + 200 + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
-          (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, g.Cacc, tiles_m, tiles_n);
+          (const h16_t*)g.A, (const h16_t*)g.B, (h16_t*)g.C, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
@@ -861,7 +880,7 @@ static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
   const int tiles_m = g.M / BM, tiles_n = g.N / BN;
   const int grid = ((tiles_m * tiles_n + 7) / 8) * 8;
   constexpr size_t smem = tile_lds_bytes<BM, BN>();
-  auto kern = gemm_bf16_tn_kernel<BM, BN, EPI>;
+  auto kern = gemm_h16_tn_kernel<BM, BN, EPI>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -869,7 +888,7 @@ static hipError_t launch_tn(const GemmArgs& g, hipStream_t s) {
     attr_set = true;
   }
   klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_TN + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
-          (const bf16_t*)g.A, (const bf16_t*)g.B, (bf16_t*)g.C, g.Cacc, tiles_m, tiles_n);
+          (const h16_t*)g.A, (const h16_t*)g.B, (h16_t*)g.C, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
 }
 
@@ -887,7 +906,7 @@ static hipError_t launch_group(const TnGroup& grp, const ReduceGroup& rg, double
     reduce_blocks = std::min(reduce_blocks, (rg.total_items + 7) / 8 * 8);
   }
   constexpr size_t smem = tile_lds_bytes<BM, BN>();
-  auto kern = gemm_bf16_tn_grouped_kernel<BM, BN>;
+  auto kern = gemm_h16_tn_grouped_kernel<BM, BN>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
@@ -906,16 +925,16 @@ static long big_tile_min() {
   return v;
 }
 
-hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
+hipError_t launch_gemm_h16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
   if (red_done) *red_done = false;
   if (n <= 0) return hipSuccess;
   bool groupable = n <= 4;
   for (int i = 0; i < n; i++)
     groupable = groupable && g[i].kind == KFKB_GEMM_TN && g[i].epilogue == KFKB_EPI_ACCUM && g[i].K == g[0].K &&
-                g[i].K % CK_ == 0 && g[i].M % 128 == 0 && g[i].N % 128 == 0 && gemm_bf16_check(g[i]) == nullptr;
+                g[i].K % CK_ == 0 && g[i].M % 128 == 0 && g[i].N % 128 == 0 && gemm_h16_check(g[i]) == nullptr;
   if (!groupable) {
     for (int i = 0; i < n; i++) {
-      hipError_t e = launch_gemm_bf16(g[i], s);
+      hipError_t e = launch_gemm_h16(g[i], s);
       if (e != hipSuccess) return e;
     }
     return hipSuccess;
@@ -935,7 +954,7 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, co
   for (int i = 0; i < n; i++) {
     TnProblem& p = grp.p[i];
     p.M = g[i].M; p.N = g[i].N; p.tiles_m = g[i].M / BT; p.tiles_n = g[i].N / BT; p.first_tile = grp.total_tiles;
-    p.A = (const bf16_t*)g[i].A; p.B = (const bf16_t*)g[i].B; p.Cacc = g[i].Cacc;
+    p.A = (const h16_t*)g[i].A; p.B = (const h16_t*)g[i].B; p.Cacc = g[i].Cacc;
     grp.total_tiles += p.tiles_m * p.tiles_n;
     flops += 2.0 * g[i].M * g[i].N * g[i].K;
   }
@@ -952,7 +971,7 @@ hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, co
         rg.total_items += red->ln_width[i] / 64;
       }
       for (int i = 0; i < red->n_colsum; i++) {
-        rg.c[i] = RedColsum{(const bf16_t*)red->dy[i], red->out[i], red->width[i], rg.total_items};
+        rg.c[i] = RedColsum{(const h16_t*)red->dy[i], red->out[i], red->width[i], rg.total_items};
         rg.total_items += red->width[i] / 64;
       }
       if (red_done) *red_done = true;
@@ -976,8 +995,8 @@ static hipError_t launch_nt_epi(const GemmArgs& g, hipStream_t s) {
   return launch_nt<128, 128, EPI>(g, s);
 }
 
-hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
-  if (gemm_bf16_check(g) != nullptr) return hipErrorInvalidValue;
+hipError_t launch_gemm_h16(const GemmArgs& g, hipStream_t s) {
+  if (gemm_h16_check(g) != nullptr) return hipErrorInvalidValue;
   if (g.kind == KFKB_GEMM_NT) {
     switch (g.epilogue) {
       case KFKB_EPI_NONE: return launch_nt_epi<KFKB_EPI_NONE>(g, s);
@@ -993,5 +1012,20 @@ hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) {
     return big ? launch_tn<256, 256, KFKB_EPI_ACCUM>(g, s) : launch_tn<128, 128, KFKB_EPI_ACCUM>(g, s);
   return big ? launch_tn<256, 256, KFKB_EPI_NONE>(g, s) : launch_tn<128, 128, KFKB_EPI_NONE>(g, s);
 }
+
+#ifdef KFKB_H16_IS_F16
+}  // namespace f16k
+hipError_t launch_gemm_f16(const GemmArgs& g, hipStream_t s) { return f16k::launch_gemm_h16(g, s); }
+hipError_t launch_gemm_f16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
+  return f16k::launch_gemm_h16_tn_group(g, n, s, red, red_done);
+}
+#else
+}  // namespace bf16k
+hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) { return bf16k::launch_gemm_h16(g, s); }
+hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
+  return bf16k::launch_gemm_h16_tn_group(g, n, s, red, red_done);
+}
+const char* gemm_bf16_check(const GemmArgs& g) { return bf16k::gemm_h16_check(g); }
+#endif
 
 }  // namespace kfkb

@@ -403,6 +403,8 @@ hipError_t launch_colsum_group(int dt, int n, const void* const* dy, float* cons
   }
   if (dt == DT_BF16)
     klaunch(colsum_group_partial_kernel<bf16_t>, dim3(blocks, parts), dim3(256), 0, s, PK_COLSUM + 10, bytes, g, scratch);
+  else if (dt == DT_F16)
+    klaunch(colsum_group_partial_kernel<f16_t>, dim3(blocks, parts), dim3(256), 0, s, PK_COLSUM + 10, bytes, g, scratch);
   else
     klaunch(colsum_group_partial_kernel<float>, dim3(blocks, parts), dim3(256), 0, s, PK_COLSUM + 12, bytes, g, scratch);
   klaunch(colsum_group_final_kernel, dim3((g.total_width + 31) / 32), dim3(256), 0, s, PK_COLSUM_FINAL + 1,
@@ -541,6 +543,8 @@ hipError_t launch_ln_fwd(int dt, const void* x, const void* gamma, const void* b
   if (rows <= 0) return hipSuccess;
   if (dt == DT_BF16)
     return ln_fwd_t<bf16_t>((const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, (bf16_t*)y, mean, rstd, rows, H, eps, s);
+  if (dt == DT_F16)
+    return ln_fwd_t<f16_t>((const f16_t*)x, (const f16_t*)gamma, (const f16_t*)beta, (f16_t*)y, mean, rstd, rows, H, eps, s);
   return ln_fwd_t<float>((const float*)x, (const float*)gamma, (const float*)beta, (float*)y, mean, rstd, rows, H, eps, s);
 }
 
@@ -582,6 +586,9 @@ hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mea
   if (dt == DT_BF16)
     return ln_bwd_t<bf16_t>((const bf16_t*)dy, (const bf16_t*)x, mean, rstd, (const bf16_t*)gamma, (const bf16_t*)dres,
                             (bf16_t*)dx, dgamma, dbeta, scratch, rows, H, s);
+  if (dt == DT_F16)
+    return ln_bwd_t<f16_t>((const f16_t*)dy, (const f16_t*)x, mean, rstd, (const f16_t*)gamma, (const f16_t*)dres,
+                           (f16_t*)dx, dgamma, dbeta, scratch, rows, H, s);
   return ln_bwd_t<float>((const float*)dy, (const float*)x, mean, rstd, (const float*)gamma, (const float*)dres,
                          (float*)dx, dgamma, dbeta, scratch, rows, H, s);
 }
@@ -608,6 +615,8 @@ hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratc
   if (rows <= 0) return hipSuccess;
   if (dt == DT_BF16)
     return colsum_launch<bf16_t, false>((const bf16_t*)dy, nullptr, nullptr, nullptr, out, nullptr, scratch, rows, N, s);
+  if (dt == DT_F16)
+    return colsum_launch<f16_t, false>((const f16_t*)dy, nullptr, nullptr, nullptr, out, nullptr, scratch, rows, N, s);
   return colsum_launch<float, false>((const float*)dy, nullptr, nullptr, nullptr, out, nullptr, scratch, rows, N, s);
 }
 
@@ -617,6 +626,8 @@ hipError_t launch_gelu_bwd(int dt, const void* dg, const void* u, void* du, size
   const int grid = (int)std::min<size_t>((nvec + 255) / 256, 8192);
   if (dt == DT_BF16)
     klaunch(gelu_bwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 2, 3.0 * n * 2, (const bf16_t*)dg, (const bf16_t*)u, (bf16_t*)du, nvec);
+  else if (dt == DT_F16)
+    klaunch(gelu_bwd_kernel<f16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 2, 3.0 * n * 2, (const f16_t*)dg, (const f16_t*)u, (f16_t*)du, nvec);
   else
     klaunch(gelu_bwd_kernel<float>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 4, 3.0 * n * 4, (const float*)dg, (const float*)u, (float*)du, nvec);
   return hipGetLastError();
@@ -628,6 +639,8 @@ hipError_t launch_gelu_fwd(int dt, const void* u, void* g, size_t n, hipStream_t
   const int grid = (int)std::min<size_t>((nvec + 255) / 256, 8192);
   if (dt == DT_BF16)
     klaunch(gelu_fwd_kernel<bf16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 12, 2.0 * n * 2, (const bf16_t*)u, (bf16_t*)g, nvec);
+  else if (dt == DT_F16)
+    klaunch(gelu_fwd_kernel<f16_t>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 12, 2.0 * n * 2, (const f16_t*)u, (f16_t*)g, nvec);
   else
     klaunch(gelu_fwd_kernel<float>, dim3(grid), dim3(256), 0, s, PK_GELU_BWD + 14, 2.0 * n * 4, (const float*)u, (float*)g, nvec);
   return hipGetLastError();
@@ -643,7 +656,7 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t s) {
 hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int cols, hipStream_t s) {
   if (rows <= 0 || cols <= 0) return hipSuccess;
   const dim3 grid((cols + 31) / 32, (rows + 31) / 32);
-  if (dt == DT_BF16)
+  if (dt_is16(dt))
     hipLaunchKernelGGL(transpose_kernel<uint16_t>, grid, dim3(256), 0, s, (const uint16_t*)in, (uint16_t*)out, rows, cols);
   else
     hipLaunchKernelGGL(transpose_kernel<uint32_t>, grid, dim3(256), 0, s, (const uint32_t*)in, (uint32_t*)out, rows, cols);

@@ -5,12 +5,14 @@ import torch
 import kfkb_synth as synth
 import paper_2303_01675_amd as kf
 
-TOL = {kf.F32: 1e-4, kf.BF16: 2e-2}      # relative tolerances the parity bar states
-NAME = {kf.F32: "f32", kf.BF16: "bf16"}
+# relative tolerances: fp32 and bf16 as the parity bar states them; fp16 carries three more mantissa bits than bf16
+# (unit roundoff 2^-11 against 2^-8), its bar is the bf16 one divided by eight
+TOL = {kf.F32: 1e-4, kf.BF16: 2e-2, kf.F16: 2.5e-3}
+NAME = {kf.F32: "f32", kf.BF16: "bf16", kf.F16: "f16"}
 
 
 def tdtype(dt):
-    return torch.bfloat16 if dt == kf.BF16 else torch.float32
+    return torch.bfloat16 if dt == kf.BF16 else torch.float16 if dt == kf.F16 else torch.float32
 
 
 def dev(a, dt):
@@ -26,7 +28,12 @@ def rnd(seed, shape, dt, std=1.0, mean=0.0):
     """Seeded N(mean, std^2) values, conditioned to be exactly representable in dt (float64 array)."""
     n = int(np.prod(shape))
     v = synth.normal(seed, n, mean, std)
-    v = synth.round_to_bf16(v).astype(np.float64) if dt == kf.BF16 else v.astype(np.float32).astype(np.float64)
+    if dt == kf.BF16:
+        v = synth.round_to_bf16(v).astype(np.float64)
+    elif dt == kf.F16:
+        v = v.astype(np.float32).astype(np.float16).astype(np.float64)
+    else:
+        v = v.astype(np.float32).astype(np.float64)
     return v.reshape(shape)
 
 

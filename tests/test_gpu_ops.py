@@ -10,7 +10,8 @@ from oracle import stage_math as sm
 from _util import TOL, assert_close, dev, host, rnd, tdtype
 
 pytestmark = pytest.mark.gpu
-DTS = [kf.F32, kf.BF16]
+DTS = [kf.F32, kf.BF16, kf.F16]
+H16 = [kf.BF16, kf.F16]
 
 
 def _sync():
@@ -132,12 +133,13 @@ def test_gemm_f32(kind, epi):
             assert_close(g, r, kf.F32, "gemm f32 kind %d epi %d %s" % (kind, epi, (M, N, K)))
 
 
+@pytest.mark.parametrize("dt", H16)
 @pytest.mark.parametrize("epi", range(6))
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (300, 384, 192), (4096, 1024, 256), (2048 + 77, 2048, 128), (4096 - 3, 4096, 128)])
-def test_gemm_bf16_nt(epi, M, N, K):
-    got, ref = _gemm_case(kf.BF16, kf.GEMM_NT, epi, M, N, K)
+def test_gemm_bf16_nt(dt, epi, M, N, K):
+    got, ref = _gemm_case(dt, kf.GEMM_NT, epi, M, N, K)
     for g, r in zip(got, ref):
-        assert_close(g, r, kf.BF16 if epi != kf.EPI_ACCUM else kf.F32, "gemm bf16 NT epi %d" % epi,
+        assert_close(g, r, dt if epi != kf.EPI_ACCUM else kf.F32, "gemm 16-bit NT epi %d" % epi,
                      factor=1 if epi != kf.EPI_ACCUM else 10)
 
 
@@ -169,12 +171,13 @@ def test_tile_weights_layout():
         kf.kfkb_op_gemm_nt_tiled(kf.EPI_NONE, 128, 128, 96, dst, dst, None, None, dst, None, None)    # K % 64 != 0
 
 
+@pytest.mark.parametrize("dt", H16)
 @pytest.mark.parametrize("epi", [kf.EPI_ACCUM, kf.EPI_NONE])
 @pytest.mark.parametrize("M,N,K", [(128, 128, 64), (384, 256, 300), (1024, 3072, 1000), (4096, 4096, 130)])
-def test_gemm_bf16_tn(epi, M, N, K):
-    got, ref = _gemm_case(kf.BF16, kf.GEMM_TN, epi, M, N, K)
+def test_gemm_bf16_tn(dt, epi, M, N, K):
+    got, ref = _gemm_case(dt, kf.GEMM_TN, epi, M, N, K)
     for g, r in zip(got, ref):
-        assert_close(g, r, kf.BF16 if epi != kf.EPI_ACCUM else kf.F32, "gemm bf16 TN epi %d" % epi,
+        assert_close(g, r, dt if epi != kf.EPI_ACCUM else kf.F32, "gemm 16-bit TN epi %d" % epi,
                      factor=1 if epi != kf.EPI_ACCUM else 10)
 
 
@@ -234,6 +237,12 @@ def test_attention_f32(b, T, heads, d, causal):
                                          (1, 128, 2, 64), (1, 129, 1, 64)])
 def test_attention_bf16(b, T, heads, d, causal):
     _attention_case(kf.BF16, b, T, heads, d, causal)
+
+
+@pytest.mark.parametrize("causal", [1, 0])
+@pytest.mark.parametrize("b,T,heads,d", [(2, 64, 2, 64), (1, 1, 2, 64), (2, 200, 2, 64), (1, 333, 2, 128), (1, 129, 1, 64)])
+def test_attention_f16(b, T, heads, d, causal):
+    _attention_case(kf.F16, b, T, heads, d, causal)
 
 
 def test_attention_rejects_unsupported_head_size():

@@ -58,6 +58,24 @@ def test_tiny_stage_fp32_matches_oracle_for_k1_and_k2(causal):
     st.close()
 
 
+@pytest.mark.parametrize("H,heads,T,b", [(128, 2, 96, 3), (256, 2, 160, 2)])
+def test_small_stage_fp16_matches_oracle(H, heads, T, b):
+    """fp16 storage (the paper's precision) through the same kernels as bf16: the tighter fp16 bar per tensor, and
+    bit-identical results for every k."""
+    dt, L, M = kf.F16, 2, 4
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=4)
+    ref = None
+    for k in (1, 2, 4):
+        G, Y, dX, order = _run(st, k, M)
+        _check_against_oracle(dt, st, blocks, xs, dys, heads, 1, G, Y, dX, order, k)
+        cur = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+        if ref is None:
+            ref = cur
+        for a, b_ in zip(ref, cur):
+            assert torch.equal(a, b_)
+    st.close()
+
+
 def test_ragged_shapes_fp32():
     dt, L, H, heads, T, b, M = kf.F32, 1, 72, 3, 37, 3, 3
     st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=3)
