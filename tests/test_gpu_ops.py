@@ -261,3 +261,42 @@ def test_delay_kernel_waits_about_as_long_as_asked():
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1)
     assert 2.9 <= ms <= 4.5, ms
+
+
+# ---------------------------------------------------------------- shapes of the larger stages, sampled
+@pytest.mark.parametrize("kind,M,N,K", [(kf.GEMM_NT, 4096, 6144, 2048),      # 1.3B-class stage: qkv forward
+                                        (kf.GEMM_NT, 4096, 2048, 8192),      # 1.3B-class stage: fc2 forward / fc1 input gradient
+                                        (kf.GEMM_NT, 2048, 16384, 4096),     # wide stage: fc1 forward
+                                        (kf.GEMM_TN, 2048, 8192, 4096)])     # 1.3B-class stage: fc1 weight gradient (K = tokens)
+def test_gemm_bf16_at_the_shapes_of_the_larger_stages_on_sampled_rows(kind, M, N, K):
+    """Full-size products of the larger benchmark stages; the oracle side is the textbook product of 64 sampled
+    output rows (all columns), which covers every tile column and a spread of tile rows."""
+    dt = kf.BF16
+    if kind == kf.GEMM_NT:
+        A = rnd(70, (M, K), dt); B = rnd(71, (N, K), dt, 0.05)
+    else:
+        A = rnd(70, (K, M), dt); B = rnd(71, (K, N), dt, 0.05)
+    rows = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, M - 1], synth_rows(72, 57, M)]))
+    ref = (A[rows] @ B.T) if kind == kf.GEMM_NT else (A[:, rows].T @ B)
+    bias = rnd(73, (N,), dt, 0.5)
+    if kind == kf.GEMM_NT:
+        Cout = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
+        kf.kfkb_op_gemm(dt, kind, kf.EPI_BIAS, M, N, K, dev(A, dt), dev(B, dt), dev(bias, dt), None, Cout, None, None)
+        _sync()
+        assert_close(host(Cout[torch.from_numpy(rows).cuda()]), ref + bias, dt, "NT rows")
+    else:
+        Cacc = torch.zeros(M, N, device="cuda")
+        kf.kfkb_op_gemm(dt, kind, kf.EPI_ACCUM, M, N, K, dev(A, dt), dev(B, dt), None, None, None, None, Cacc)
+        _sync()
+        assert_close(host(Cacc[torch.from_numpy(rows).cuda()]), ref, kf.F32, "TN rows", factor=10)
+
+
+def synth_rows(seed, n, M):
+    import kfkb_synth as synth
+    return (synth.uniform(seed, n) * M).astype(np.int64) % M
+
+
+@pytest.mark.parametrize("b,T,heads,d", [(1, 2048, 2, 128),      # 1.3B-class and wide stages
+                                         (1, 4096, 1, 128)])     # very wide stage
+def test_attention_bf16_at_the_sequence_lengths_of_the_larger_stages(b, T, heads, d):
+    _attention_case(kf.BF16, b, T, heads, d, 1)
