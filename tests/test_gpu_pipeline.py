@@ -125,3 +125,34 @@ def test_pipeline_errors():
     with pytest.raises(kf.KfkbError):
         kf.run_pipeline_kFkB(M + 1)
     st.close()
+
+
+def test_pipeline_with_recomputation_in_fp16():
+    """The options compose: fp16 storage, activation recomputation and the pipeline of virtual stages give the bits
+    of the plain single-stage run of the same configuration, within the fp16 bar of the oracle."""
+    dt, L, H, heads, T, b, M, S = kf.F16, 4, 128, 2, 64, 2, 4, 2
+    blocks = synth.stage_weights(L, H, 4 * H, NAME[dt])
+    xs = [synth.microbatch_inputs(mb, b, T, H, NAME[dt]) for mb in range(M)]
+    dys = [synth.microbatch_upstream_grads(mb, b, T, H, NAME[dt]) for mb in range(M)]
+    st = kf.StageBuffers(blocks, dt, heads, T, b, M, k_max=M, recompute=1)
+    st.set_inputs(xs, dys)
+    kf.stage_zero_grads()
+    kf.run_kFkB(2, M, 0)
+    kf.stage_sync()
+    whole = (st.grads.clone(), st.h_out[:M].clone(), st.h_ingrad[:M].clone())
+    keep = _bind(S, M)
+    for k in (1, 2):
+        got, order = _run_pipeline(st, k, M)
+        for a, b_ in zip(whole, got):
+            assert torch.equal(a, b_)
+    Gr, Yr, dXr, _, _ = pl.run_pipeline(S, 2, blocks, xs, dys, heads)
+    Y, dX = st.outputs(M)
+    G = st.gradients()
+    for mb in range(M):
+        assert_close(Y[mb], Yr[mb], dt, "Y[%d]" % mb)
+        assert_close(dX[mb], dXr[mb], dt, "dX[%d]" % mb)
+    for l in range(L):
+        for n in synth.PARAM_ORDER:
+            assert_close(G[l][n], Gr[l][n], dt, "grad block %d %s" % (l, n))
+    del keep
+    st.close()
