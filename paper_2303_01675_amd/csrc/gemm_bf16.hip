@@ -422,28 +422,63 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
   const int frow = lane & 31, fhalf = lane >> 5;
   constexpr bool HAS_BIAS = EPI == KFKB_EPI_BIAS || EPI == KFKB_EPI_BIAS_GELU || EPI == KFKB_EPI_BIAS_RES;
   constexpr bool HAS_RES = EPI == KFKB_EPI_BIAS_RES || EPI == KFKB_EPI_GELU_BWD;
+  constexpr int LPR = WC / 8, RPI = 64 / LPR;                     // lanes per row (16 bytes each), rows per instruction
+  const int er = lane / LPR, ec = lane % LPR;
+  // The residual of the wave's whole quadrant is requested at once, before the barrier (the fragment registers of
+  // the main loop are free by now, and the memory latency is paid once), in the shape of the final store: 16 bytes
+  // per lane along the rows, so that an instruction touches 8 cache lines and not 32.  It reaches the accumulator
+  // layout through the wave's staging rows: every lane later reads exactly the 8 bytes it then overwrites with its
+  // result, and a wave's LDS accesses execute in order.
+  constexpr int NLD = WR / RPI;
+  h16x8 rres[HAS_RES ? NLD : 1];
+  if constexpr (HAS_RES) {
+#pragma unroll
+    for (int t = 0; t < NLD; t++) {
+      const int m = min(m0 + wm0 + t * RPI + er, M - 1);
+      rres[t] = *reinterpret_cast<const h16x8*>(residual + (size_t)m * N + n0 + wn0 + ec * 8);
+    }
+  }
+  h16x4 bb[HAS_BIAS ? TN : 1][4];                                 // the lane's bias values, the same for every row block
+  if constexpr (HAS_BIAS) {
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) bb[j][q] = *reinterpret_cast<const h16x4*>(bias + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+  }
   __syncthreads();                                                // every wave is done with the ring
   char* ew = smem + wave * (WR * RS);
+  if constexpr (HAS_RES) {
+#pragma unroll
+    for (int t = 0; t < NLD; t++) *reinterpret_cast<h16x8*>(ew + (t * RPI + er) * RS + ec * 16) = rres[t];
+  }
 #pragma unroll
   for (int i = 0; i < TM; i++) {
-    const int m = min(m0 + wm0 + i * 32 + frow, M - 1);           // rows past M are computed and dropped
+    __builtin_amdgcn_sched_barrier(0);                            // one 32-row block at a time
     h16x4 rr[TN][4];
     if constexpr (HAS_RES) {
 #pragma unroll
       for (int j = 0; j < TN; j++)
 #pragma unroll
         for (int q = 0; q < 4; q++)
-          rr[j][q] = *reinterpret_cast<const h16x4*>(residual + (size_t)m * N + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+          rr[j][q] = *reinterpret_cast<const h16x4*>(ew + (i * 32 + frow) * RS + (j * 32 + q * 8 + fhalf * 4) * 2);
     }
 #pragma unroll
     for (int j = 0; j < TN; j++)
 #pragma unroll
       for (int q = 0; q < 4; q++) {
-        float v[4] = {acc[i][j][q * 4 + 0], acc[i][j][q * 4 + 1], acc[i][j][q * 4 + 2], acc[i][j][q * 4 + 3]};
-        if constexpr (HAS_BIAS) {
-          const h16x4 b = *reinterpret_cast<const h16x4*>(bias + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
+        float v[4];
+        if constexpr (TM * TN == 16) {
+          // 256 accumulator registers sit in the AGPR half of the file; reading them here, one by one, keeps the
+          // compiler from copying whole tiles into vector registers ahead of time (which spilled the residual)
 #pragma unroll
-          for (int e = 0; e < 4; e++) v[e] += (float)b[e];
+          for (int e = 0; e < 4; e++) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[e]) : "a"(acc[i][j][q * 4 + e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = acc[i][j][q * 4 + e];
+        }
+        if constexpr (HAS_BIAS) {
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] += (float)bb[j][q][e];
         }
         if constexpr (EPI == KFKB_EPI_BIAS_RES) {
 #pragma unroll
@@ -460,8 +495,6 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
       }
   }
   wait_lgkm0();
-  constexpr int LPR = WC / 8, RPI = 64 / LPR;                     // lanes per row (16 bytes each), rows per instruction
-  const int er = lane / LPR, ec = lane % LPR;
 #pragma unroll
   for (int r0 = 0; r0 < WR; r0 += RPI) {
     const int r = r0 + er, m = m0 + wm0 + r;
