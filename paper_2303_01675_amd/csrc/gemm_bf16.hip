@@ -512,6 +512,60 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
   }
 }
 
+// Cacc += acc for a whole tile (fp32, the gradient accumulators).  The accumulator layout would touch 32 rows with
+// 32 bytes each per instruction; through LDS, 32 rows at a time, the wave reads and writes whole rows instead
+// (1 KiB per instruction in 8 full cache lines).  The old values of two 32-row blocks are in flight at any time,
+// the first two requested before the barrier that ends the main loop.  Sum order per element: old + acc, as in
+// epilogue_quad.  Needs 4 * 32 * (BN * 2 + 16) bytes of LDS (less than the ring) and M, N multiples of the tile.
+template <int BM, int BN>
+__device__ __forceinline__ void epilogue_accum_staged(f32x16 (&acc)[BM / 64][BN / 64], char* smem, float* __restrict__ Cacc, int N,
+                                                      int m0, int n0, int lane, int wave) {
+  constexpr int TM = BM / 64, TN = BN / 64, WR = BM / 2, WC = BN / 2;
+  constexpr int RS = WC * 4 + 16;                                 // row stride in bytes
+  constexpr int LPR = WC / 4, RPI = 64 / LPR, NI = 32 / RPI;      // lanes per row, rows per instruction, instructions per block
+  const int wm0 = (wave >> 1) * WR, wn0 = (wave & 1) * WC;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const int er = lane / LPR, ec = lane % LPR;
+  float* cbase = Cacc + (size_t)(m0 + wm0 + er) * N + n0 + wn0 + ec * 4;
+  float4 cin[2][NI];
+  auto request = [&](int i, int slot) {
+#pragma unroll
+    for (int t = 0; t < NI; t++) cin[slot][t] = *reinterpret_cast<const float4*>(cbase + (size_t)(i * 32 + t * RPI) * N);
+  };
+  request(0, 0);
+  request(1, 1);
+  __syncthreads();                                                // every wave is done with the ring
+  char* ew = smem + wave * (32 * RS);
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    __builtin_amdgcn_sched_barrier(0);                            // one 32-row block at a time
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        float v[4];
+        if constexpr (TM * TN == 16) {                            // see epilogue_staged
+#pragma unroll
+          for (int e = 0; e < 4; e++) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[e]) : "a"(acc[i][j][q * 4 + e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = acc[i][j][q * 4 + e];
+        }
+        *reinterpret_cast<float4*>(ew + frow * RS + (j * 32 + q * 8 + fhalf * 4) * 4) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+    // a wave's LDS accesses execute in order: these reads see the block just written, the next block's writes
+    // come after them
+#pragma unroll
+    for (int t = 0; t < NI; t++) {
+      const float4 a = *reinterpret_cast<const float4*>(ew + (t * RPI + er) * RS + ec * 16);
+      float4 c = cin[i & 1][t];
+      c.x += a.x; c.y += a.y; c.z += a.z; c.w += a.w;
+      *reinterpret_cast<float4*>(cbase + (size_t)(i * 32 + t * RPI) * N) = c;
+    }
+    if (i + 2 < TM) request(i + 2, i & 1);
+  }
+}
+
 template <int BM, int BN, int EPI, bool BT>
 __global__ void __launch_bounds__(256) gemm_h16_nt_kernel(int M, int N, int K, const h16_t* __restrict__ A, const h16_t* __restrict__ B,
                                                  const h16_t* __restrict__ bias, const h16_t* __restrict__ residual,
@@ -572,16 +626,7 @@ __device__ __forceinline__ void tn_tile(int M, int N, int K, const h16_t* __rest
       for (int e = 0; e < 16; e++) acc[i][j][e] = 0.f;
   main_loop<TM, TN>(lay, acc, K / CK_);
   if constexpr (EPI == KFKB_EPI_ACCUM) {
-    const int wm0 = (wave >> 1) * (BM / 2), wn0 = (wave & 1) * (BN / 2), frow = lane & 31, fhalf = lane >> 5;
-#pragma unroll
-    for (int i = 0; i < TM; i++) {
-      const int m = m0 + wm0 + i * 32 + frow;
-#pragma unroll
-      for (int j = 0; j < TN; j++)
-#pragma unroll
-        for (int q = 0; q < 4; q++)
-          epilogue_quad<EPI>(acc[i][j], q, m, n0 + wn0 + j * 32 + q * 8 + fhalf * 4, N, nullptr, nullptr, C, nullptr, Cacc);
-    }
+    epilogue_accum_staged<BM, BN>(acc, smem, Cacc, N, m0, n0, lane, wave);
   } else {
     epilogue_staged<BM, BN, KFKB_EPI_NONE>(acc, smem, M, N, m0, n0, lane, wave, nullptr, nullptr, C, nullptr);
   }
