@@ -21,12 +21,15 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
   const int nchunks = H >> 3;
   const T* xr = x + (size_t)row * H;
   float v[NCH][8];
+  Raw8<T> graw[NCH], braw[NCH];                               // requested with the row: they arrive under the two reductions
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
     const int c = lane + 64 * i;
     if (c < nchunks) {
       Vec8<T>::load(xr + c * 8, v[i]);
+      graw[i] = Vec8<T>::load_raw(gamma + c * 8);
+      braw[i] = Vec8<T>::load_raw(beta + c * 8);
 #pragma unroll
       for (int e = 0; e < 8; e++) s += v[i][e];
     }
@@ -49,8 +52,8 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
     const int c = lane + 64 * i;
     if (c < nchunks) {
       float g[8], b[8], o[8];
-      Vec8<T>::load(gamma + c * 8, g);
-      Vec8<T>::load(beta + c * 8, b);
+      Vec8<T>::unpack(graw[i], g);
+      Vec8<T>::unpack(braw[i], b);
 #pragma unroll
       for (int e = 0; e < 8; e++) o[e] = (v[i][e] - mu) * rs * g[e] + b[e];
       Vec8<T>::store(yr + c * 8, o);
