@@ -190,10 +190,15 @@ __global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restri
     if (!(causal && j0 > qw0 + 31)) {               // wave-uniform: some key of the tile is visible
       f32x16 st[2] = {zero16(), zero16()};
 #pragma unroll
-      for (int jt = 0; jt < 2; jt++)
+      for (int jt = 0; jt < 2; jt++) {
+        h16x8 ka[D / 16];                            // requested together, ahead of their MFMAs
 #pragma unroll
-        for (int ds = 0; ds < D / 16; ds++)
-          st[jt] = KFKB_MFMA_H16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt]);
+        for (int ds = 0; ds < D / 16; ds++) ka[ds] = IO::frag(Kt, jt * 32 + l32, ds * 2 + hh);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ds = 0; ds < D / 16; ds++) st[jt] = KFKB_MFMA_H16(ka[ds], qf[ds], st[jt]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
       // masking is needed only where the tile crosses the diagonal or the end of the sequence
       if (j0 + 63 >= T || (causal && j0 + 63 > qw0)) {
 #pragma unroll
@@ -212,32 +217,36 @@ __global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restri
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;      // scale > 0: max commutes with it
       const float mnew = fmaxf(fmaxf(mrun, mx), -1e30f);
       const float alpha = exp2_raw(mrun - mnew);
-      float ps = 0.f;
-#pragma unroll
-      for (int jt = 0; jt < 2; jt++)
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-          const float p = exp2_raw(fmaf(st[jt][r], scale_log2, -mnew));
-          st[jt][r] = p;
-          ps += p;
-        }
-      lsum = lsum * alpha + ps;
-      mrun = mnew;
       if (__any(alpha != 1.0f)) {                    // the running maximum settles after a few tiles
 #pragma unroll
         for (int t = 0; t < D / 32; t++)
 #pragma unroll
           for (int e = 0; e < 16; e++) oacc[t][e] *= alpha;
       }
+      // Sixteen keys at a time: exponentials, then the P.V MFMAs of those keys.  An MFMA runs on after it has been
+      // issued, so the exponentials of the next sixteen keys, next in program order, execute under it.
+      float ps = 0.f;
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int t16 = 0; t16 < 2; t16++) {
-          const h16x8 pb = pack8(st[jt], t16 * 8);
+          h16x8 vt[D / 32];
 #pragma unroll
-          for (int t = 0; t < D / 32; t++)
-            oacc[t] = KFKB_MFMA_H16(IO::frag_tr(Vt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, oacc[t]);
+          for (int t = 0; t < D / 32; t++) vt[t] = IO::frag_tr(Vt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
+#pragma unroll
+          for (int r = t16 * 8; r < t16 * 8 + 8; r++) {
+            const float p = exp2_raw(fmaf(st[jt][r], scale_log2, -mnew));
+            st[jt][r] = p;
+            ps += p;
+          }
+          const h16x8 pb = pack8(st[jt], t16 * 8);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int t = 0; t < D / 32; t++) oacc[t] = KFKB_MFMA_H16(vt[t], pb, oacc[t]);
+          __builtin_amdgcn_sched_barrier(0);
         }
+      lsum = lsum * alpha + ps;
+      mrun = mnew;
     }
     if (kb + 1 < nkv) {
       IO::store(Ks + (cur ^ 1) * 64 * D, rk);
@@ -330,12 +339,25 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_h16_kernel(const h16_t* __res
     const h16_t* Vt = Vs + cur * 64 * D;
     if (!(causal && j0 > qw0 + 31)) {
       f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
+      // fragments are requested eight at a time, ahead of the MFMAs that use them: one LDS latency per eight
+      // MFMAs instead of one per MFMA
 #pragma unroll
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
-        for (int ds = 0; ds < D / 16; ds++) {
-          st[jt] = KFKB_MFMA_H16(IO::frag(Kt, jt * 32 + l32, ds * 2 + hh), qf[ds], st[jt]);
-          dp[jt] = KFKB_MFMA_H16(IO::frag(Vt, jt * 32 + l32, ds * 2 + hh), dof[ds], dp[jt]);
+        for (int d0 = 0; d0 < D / 16; d0 += 4) {
+          h16x8 ka[4], va[4];
+#pragma unroll
+          for (int ds = 0; ds < 4; ds++) {
+            ka[ds] = IO::frag(Kt, jt * 32 + l32, (d0 + ds) * 2 + hh);
+            va[ds] = IO::frag(Vt, jt * 32 + l32, (d0 + ds) * 2 + hh);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int ds = 0; ds < 4; ds++) {
+            st[jt] = KFKB_MFMA_H16(ka[ds], qf[d0 + ds], st[jt]);
+            dp[jt] = KFKB_MFMA_H16(va[ds], dof[d0 + ds], dp[jt]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
       if (j0 + 63 >= T || (causal && j0 + 63 > qw0)) {
 #pragma unroll
@@ -357,10 +379,14 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_h16_kernel(const h16_t* __res
       for (int jt = 0; jt < 2; jt++)
 #pragma unroll
         for (int t16 = 0; t16 < 2; t16++) {
-          const h16x8 dsb = pack8(st[jt], t16 * 8);
+          h16x8 kt[D / 32];
 #pragma unroll
-          for (int t = 0; t < D / 32; t++)
-            dq[t] = KFKB_MFMA_H16(IO::frag_tr(Kt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dq[t]);
+          for (int t = 0; t < D / 32; t++) kt[t] = IO::frag_tr(Kt, jt * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
+          const h16x8 dsb = pack8(st[jt], t16 * 8);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int t = 0; t < D / 32; t++) dq[t] = KFKB_MFMA_H16(kt[t], dsb, dq[t]);
+          __builtin_amdgcn_sched_barrier(0);
         }
     }
     if (kb + 1 < nkv) {
@@ -457,12 +483,25 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_h16_kernel(const h16_t* __re
     const h16_t* Ot = Os + cur * 64 * D;
     if (!(causal && i0 + 63 < jw0)) {               // wave-uniform: some query of the tile sees these keys
       f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
+      // fragments are requested eight at a time, ahead of the MFMAs that use them: one LDS latency per eight
+      // MFMAs instead of one per MFMA
 #pragma unroll
       for (int it = 0; it < 2; it++)
 #pragma unroll
-        for (int ds = 0; ds < D / 16; ds++) {
-          st[it] = KFKB_MFMA_H16(IO::frag(Qt, it * 32 + l32, ds * 2 + hh), kf[ds], st[it]);
-          dp[it] = KFKB_MFMA_H16(IO::frag(Ot, it * 32 + l32, ds * 2 + hh), vf[ds], dp[it]);
+        for (int d0 = 0; d0 < D / 16; d0 += 4) {
+          h16x8 qa[4], oa[4];
+#pragma unroll
+          for (int ds = 0; ds < 4; ds++) {
+            qa[ds] = IO::frag(Qt, it * 32 + l32, (d0 + ds) * 2 + hh);
+            oa[ds] = IO::frag(Ot, it * 32 + l32, (d0 + ds) * 2 + hh);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int ds = 0; ds < 4; ds++) {
+            st[it] = KFKB_MFMA_H16(qa[ds], kf[d0 + ds], st[it]);
+            dp[it] = KFKB_MFMA_H16(oa[ds], vf[d0 + ds], dp[it]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
       if (i0 + 63 >= T || jw0 + 31 >= T || (causal && jw0 + 31 > i0)) {
 #pragma unroll
@@ -492,13 +531,21 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_h16_kernel(const h16_t* __re
       for (int it = 0; it < 2; it++)
 #pragma unroll
         for (int t16 = 0; t16 < 2; t16++) {
-          const h16x8 pb = pack8(st[it], t16 * 8);
-          const h16x8 dsb = pack8(dp[it], t16 * 8);
+          h16x8 ot[D / 32], qt[D / 32];              // again requested together, ahead of their MFMAs
 #pragma unroll
           for (int t = 0; t < D / 32; t++) {
-            dv[t] = KFKB_MFMA_H16(IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), pb, dv[t]);
-            dk[t] = KFKB_MFMA_H16(IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col), dsb, dk[t]);
+            ot[t] = IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
+            qt[t] = IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
           }
+          const h16x8 pb = pack8(st[it], t16 * 8);
+          const h16x8 dsb = pack8(dp[it], t16 * 8);
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int t = 0; t < D / 32; t++) {
+            dv[t] = KFKB_MFMA_H16(ot[t], pb, dv[t]);
+            dk[t] = KFKB_MFMA_H16(qt[t], dsb, dk[t]);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
     }
     if (ib + 1 < nq) {
