@@ -521,6 +521,7 @@ template <int BM, int BN>
 __device__ __forceinline__ void epilogue_accum_staged(f32x16 (&acc)[BM / 64][BN / 64], char* smem, float* __restrict__ Cacc, int N,
                                                       int m0, int n0, int lane, int wave) {
   constexpr int TM = BM / 64, TN = BN / 64, WR = BM / 2, WC = BN / 2;
+  static_assert(TM >= 2, "two 32-row blocks are requested ahead");
   constexpr int RS = WC * 4 + 16;                                 // row stride in bytes
   constexpr int LPR = WC / 4, RPI = 64 / LPR, NI = 32 / RPI;      // lanes per row, rows per instruction, instructions per block
   const int wm0 = (wave >> 1) * WR, wn0 = (wave & 1) * WC;
