@@ -406,6 +406,12 @@ struct TnLayout {
   __device__ __forceinline__ h16x8 rd_b(int slot, int ks, int j) { return tr_pair(fb_base[j] + slot * B_SLOT + ks * 16 * BN, 4 * BN); }
 };
 
+// The staged epilogues read the 256 accumulator registers of the large tiles with v_accvgpr_read_b32 in inline
+// assembly, where the compiler's hazard recogniser does not see an accumulator read: the wait states an MFMA result
+// needs before a vector instruction may read it (at most 18 for the 16-pass forms) are spent here, once, after the
+// last MFMA of the main loop.
+__device__ __forceinline__ void mfma_results_settled() { asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" ::: "memory"); }
+
 // ---- epilogues ---------------------------------------------------------------------------------
 // Accumulator of lane l, register 4 q + e: row (l % 32) of the 32 x 32 tile, column q * 8 + (l / 32) * 4 + e.
 // The finished values (bias, residual or GELU derivative applied in fp32, rounded once) go through LDS so
@@ -446,6 +452,7 @@ __device__ __forceinline__ void epilogue_staged(f32x16 (&acc)[BM / 64][BN / 64],
       for (int q = 0; q < 4; q++) bb[j][q] = *reinterpret_cast<const h16x4*>(bias + n0 + wn0 + j * 32 + q * 8 + fhalf * 4);
   }
   __syncthreads();                                                // every wave is done with the ring
+  if constexpr (TM * TN == 16) mfma_results_settled();
   char* ew = smem + wave * (WR * RS);
   if constexpr (HAS_RES) {
 #pragma unroll
@@ -536,6 +543,7 @@ __device__ __forceinline__ void epilogue_accum_staged(f32x16 (&acc)[BM / 64][BN 
   request(0, 0);
   request(1, 1);
   __syncthreads();                                                // every wave is done with the ring
+  if constexpr (TM * TN == 16) mfma_results_settled();
   char* ew = smem + wave * (32 * RS);
 #pragma unroll
   for (int i = 0; i < TM; i++) {
