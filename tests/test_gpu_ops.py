@@ -173,7 +173,8 @@ def test_tile_weights_layout():
 
 @pytest.mark.parametrize("dt", H16)
 @pytest.mark.parametrize("epi", [kf.EPI_ACCUM, kf.EPI_NONE])
-@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (384, 256, 300), (1024, 3072, 1000), (4096, 4096, 130)])
+@pytest.mark.parametrize("M,N,K", [(128, 128, 64), (384, 256, 300), (1024, 3072, 1000), (4096, 4096, 130),
+                                   (2048, 2048, 96), (4096, 4096, 128)])    # the last two: both tile sizes of the DMA kernel
 def test_gemm_bf16_tn(dt, epi, M, N, K):
     got, ref = _gemm_case(dt, kf.GEMM_TN, epi, M, N, K)
     for g, r in zip(got, ref):
