@@ -97,7 +97,7 @@ size_t kfkb_activation_bytes_per_microbatch_ex(int layers, int micro_batch, int 
 int kfkb_enumerate_candidates(int global_batch, size_t mem_limit, size_t bytes_per_sample, int num_stages,
                               int stage_index, int k_max, int* out_k, int* out_b, int cap);
 
-/* ---- cost model and online choice of k (paper Sections 3.3 "auto tunner", 5.2, 5.4) -------------- *
+/* ---- cost model and online choice of k (paper Sections 3.2.2 "auto tunner", 4.3, 5.2, 5.4) -------- *
  * The pipeline length of a candidate plan is estimated from stage computation times, profiled once *
  * per plan, and from communication times measured end to end and averaged over a moving window;    *
  * at regular intervals the admissible candidate with the shortest estimate is taken (ties: the      *
@@ -141,8 +141,10 @@ int stage_config(const kfkb_config_t* cfg);
  *   ln2_gamma[H] ln2_beta[H] W_1[H,F] b_1[F] W_2[F,H] b_2[H]
  * matrices [in, out]; QKV columns ordered [Q | K | V], head j owning columns j*d..(j+1)*d of
  * each third, d = hidden / heads.  Borrowed until stage_destroy.
- * Errors: KFKB_E_ARG for hidden % heads != 0 or an unsupported shape (bf16 needs hidden % 128 == 0
- * and d in {64, 128}; fp32 needs hidden % 8 == 0 and d <= 128); KFKB_E_STATE if a stage exists. */
+ * Errors: KFKB_E_ARG for a null pointer, a size < 1, hidden % heads != 0, stage_index outside [0, num_stages), or
+ * an unsupported shape: hidden > 8192 (any dtype); 16-bit storage needs hidden % 128 == 0 and d in {64, 128};
+ * fp32 needs hidden % 8 == 0, d <= 128 and seq <= 4096; activation recomputation needs
+ * micro_batch * seq * mlp_width % 8 == 0.  KFKB_E_STATE if a stage exists. */
 int stage_init(const void* weights, int layers, int hidden, int heads, int seq);
 
 /* Number of parameters of the stage (elements of `weights` and of `grad_accum`). */
@@ -216,6 +218,17 @@ int stage_set_compute_lanes(int lanes);
  * stage_get_order is the end of its chain (dX is complete then).  0 keeps them on the op's own stream.
  * Call while no micro-batch is live.  Returns the previous setting. */
 int stage_set_wgrad_stream(int enable);
+/* The small reductions of a W step (bias column sums, finishing pass of the LayerNorm parameter sums) ride in the
+ * grouped weight-gradient launch on the CUs its tiles leave idle (1, the default) or run as launches of their own
+ * (0).  16-bit storage only; the sums are formed in a fixed order either way, but not the same one: results of
+ * the two settings agree to fp32 rounding, each is bit-reproducible.  Call while no micro-batch is live.
+ * Returns the previous setting. */
+int stage_set_fused_w_reductions(int enable);
+/* Tile choice of the 16-bit matrix products: 256 x 256 tiles are used where the product divides into at least
+ * `tiles` of them (default 192: three quarters of the 256 CUs get a tile), 128 x 128 tiles otherwise.  Process-wide,
+ * host-only; returns the previous value.  A product's result does not depend on the tile shape beyond fp32
+ * rounding order.  KFKB_E_ARG for tiles < 1. */
+int kfkb_set_big_tile_min(int tiles);
 int stage_sync(void);                     /* waits for both compute lanes, the send and the receive stream */
 int stage_sync_timeout(double seconds);   /* same, polling; KFKB_E_TIMEOUT if not done in time */
 int stage_destroy(void);

@@ -103,6 +103,39 @@ def stage_weights(L, H, F, dtype="f32", seed=1234, std=0.02):
     return blocks
 
 
+def stage_weights_tiled(L, H, F, dtype="bf16", seed=1234, std=0.02, period=(1 << 22) + 17, out=np.float64):
+    """Weights of the large stages (hundreds of millions of parameters per block) without drawing every value:
+    ONE seeded draw of `period` N(0, std^2) values, repeated cyclically; tensor t of block l starts at offset
+    (12 l + t) * 7919 of the cycle, so that blocks and tensors differ, and the odd period keeps rows of a matrix
+    from repeating.  Same dict layout and conditioning as stage_weights; arrays of type `out` (float64 like
+    stage_weights, or float32, which holds every 16-bit value exactly and halves the host memory)."""
+    base = normal(seed, period, 0.0, std)
+    cond = _condition(base, dtype).astype(out)                 # conditioning is element-wise: condition once, then repeat
+    blocks = []
+    for l in range(L):
+        blk = {}
+        shapes = param_shapes(H, F)
+        for t, name in enumerate(PARAM_ORDER):
+            shp = shapes[name]
+            n = int(np.prod(shp))
+            start = ((12 * l + t) * 7919) % period
+            if name in ("ln1_g", "ln2_g"):                     # 1 + N(0, std^2), conditioned after the shift
+                idx = (start + np.arange(n)) % period
+                blk[name] = _condition(base[idx] + 1.0, dtype).astype(out).reshape(shp)
+                continue
+            v = np.empty(n, dtype=out)
+            first = min(n, period - start)
+            v[:first] = cond[start:start + first]
+            pos = first
+            while pos < n:
+                cnt = min(period, n - pos)
+                v[pos:pos + cnt] = cond[:cnt]
+                pos += cnt
+            blk[name] = v.reshape(shp)
+        blocks.append(blk)
+    return blocks
+
+
 def microbatch_inputs(mb, b, T, H, dtype="f32", seed=1000):
     return _condition(normal(seed + mb, b * T * H), dtype).reshape(b, T, H)
 

@@ -10,7 +10,7 @@ S or k (Section 1: the plans are mathematically equivalent).
 What it leaves open, and the reading taken here:
   * the order in which ONE executor that owns all S stages (a single GPU standing in for S workers)
     issues the ops is not the paper's concern.  `list_schedule` fixes one: imagine every stage on a
-    device of its own, forward 1 time unit, backward 2 (the paper's own assumption, Section 3.3),
+    device of its own, forward 1 time unit, backward 2 (the paper's own assumption, Section 4.1),
     transfers free; repeatedly issue, among the stages whose next op has its producers issued, the
     op that would start earliest on that imaginary pipeline; ties go to the later stage.  Integer
     times, so the rule is exact and the library can be required to issue the same sequence.

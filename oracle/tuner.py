@@ -1,6 +1,6 @@
 """Cost model and online choice of the group size k (the auto tuner of the paper).
 
-What the paper says (Sections 3.3 "auto tunner", 5.2 "profiling", 5.4 "online tuning"):
+What the paper says (Sections 3.2.2 "auto tunner", 4.3 "cost model", 5.2 "profiling", 5.4 "online tuning"):
   * the pipeline length of every candidate plan is ESTIMATED from profiled stage computation
     times and profiled cross-stage communication times, and the shortest plan is taken;
   * stage computation times are stable (the device is not shared) and are profiled once per

@@ -134,6 +134,8 @@ enum ProfClass { PK_GEMM_NT = 1000, PK_GEMM_TN = 2000, PK_ATTN_FWD = 3000, PK_AT
                  PK_ATTN_DSUM = 3300, PK_LN_FWD = 4000, PK_LN_BWD_DX = 4100, PK_COLSUM = 4200, PK_COLSUM_XHAT = 4300,
                  PK_COLSUM_FINAL = 4400, PK_GELU_BWD = 4500, PK_GEMM_F32 = 5000, PK_ATTN_F32 = 5100 };
 bool prof_acquire(int key, double work, hipEvent_t* e0, hipEvent_t* e1);
+// records the calling thread's error message (what kfkb_last_error returns) and hands `code` back
+int set_error(int code, const char* fmt, ...);
 
 template <typename... KArgs, typename... Args>
 inline void klaunch(void (*kern)(KArgs...), dim3 grid, dim3 block, size_t smem, hipStream_t s, int key, double work,
@@ -208,6 +210,10 @@ static inline hipError_t launch_gemm_16_tn_group(int dt, const GemmArgs* g, int 
   return dt == DT_F16 ? launch_gemm_f16_tn_group(g, n, s, red, red_done) : launch_gemm_bf16_tn_group(g, n, s, red, red_done);
 }
 int ln_bwd_partial_rows(int rows, int H);        // partial rows launch_ln_bwd leaves in its scratch
+size_t colsum_scratch_floats(int rows, int N);   // floats of `scratch` that launch_colsum_accum writes and reads
+// fewest 256 x 256 tiles a product must divide into before they are preferred over 128 x 128 tiles
+// (kfkb_set_big_tile_min)
+extern int g_big_tile_min;
 const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported (either 16-bit type)
 
 hipError_t launch_attention_fwd_f32(const float* qkv, float* o, float* lse, int b, int T, int H, int heads,

@@ -65,6 +65,7 @@ void prof_key_name_bf16(int key, char* out, size_t cap, int* bound) {
 }  // namespace
 
 namespace kfkb {
+int g_big_tile_min = 192;
 bool prof_acquire(int key, double work, hipEvent_t* e0, hipEvent_t* e1) {
   if (!g_prof_on) return false;
   while (g_prof_pool.size() < g_prof_next + 2) {
@@ -92,6 +93,22 @@ int fail(int code, const char* fmt, ...) {
   g_err = buf;
   return code;
 }
+
+}  // namespace
+
+namespace kfkb {
+int set_error(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+}  // namespace kfkb
+
+namespace {
 
 #define HIPCHK(expr)                                                                                   \
   do {                                                                                                 \
@@ -218,11 +235,7 @@ struct Stage {
   // cfg.recompute: the LayerNorm outputs a, c and the GELU output g are not stashed; a forward keeps them in
   // per-lane temporaries, a backward forms them again from x, x1 and u (same kernels, same bits)
   bool recompute = false;
-  bool fuse_w_reductions = true;   // KFKB_FUSE_W=0: the W step's small reductions as launches of their own
-  // W steps get a stream of their own when the process has hardware queues to spare (GPU_MAX_HW_QUEUES >= 5:
-  // two lanes, this one, send, receive); otherwise they borrow the other lane's stream while that lane is idle
-  hipStream_t sw = nullptr;
-  hipEvent_t ev_sw_tail = nullptr;
+  bool fuse_w_reductions = true;   // false (stage_set_fused_w_reductions): the W step's small reductions as launches of their own
   hipStream_t ss = nullptr, sr = nullptr;
   std::vector<hipEvent_t> ev_g;                            // per block: last accumulation into its gradients
   std::vector<char> ev_g_set;
@@ -453,7 +466,7 @@ int backward_block(ActiveOp& a) {
   char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : (a.dx_first != nullptr && l == a.first) ? a.dx_first : ln.t_dxr[seq % 3];
   // where the W step of this block goes: the other lane's stream, beside this chain, when that lane has nothing
   // of its own to do; behind the chain otherwise (the other lane's op then fills the chip beside it)
-  hipStream_t qw = !s.wgrad_overlap ? q : s.sw != nullptr ? s.sw : !a.other_busy ? s.lane[1 - a.lane].s : q;
+  hipStream_t qw = !s.wgrad_overlap ? q : !a.other_busy ? s.lane[1 - a.lane].s : q;
   // the buffers about to be overwritten were last read by the W step of two blocks ago
   if (seq >= 2 && ln.w_elsewhere[(seq - 2) % Stage::kRing]) HIPCHK(hipStreamWaitEvent(q, ln.ev_wdone[(seq - 2) % Stage::kRing], 0));
   if (s.recompute) {
@@ -698,10 +711,6 @@ int join_compute_streams(hipStream_t q) {
     HIPCHK(hipEventRecord(g.lane[i].ev_tail, g.lane[i].s));
     HIPCHK(hipStreamWaitEvent(q, g.lane[i].ev_tail, 0));
   }
-  if (g.sw != nullptr) {
-    HIPCHK(hipEventRecord(g.ev_sw_tail, g.sw));
-    HIPCHK(hipStreamWaitEvent(q, g.ev_sw_tail, 0));
-  }
   return 0;
 }
 
@@ -907,7 +916,6 @@ PipeSim gp;
 void pipeline_release() {
   if (gp.bound && g.inited) {
     for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) (void)hipStreamSynchronize(q);
-    if (g.sw != nullptr) (void)hipStreamSynchronize(g.sw);
     for (Pool* p : {&g.xs, &g.dys, &g.ys, &g.dxs}) std::fill(p->release.begin(), p->release.end(), nullptr);
     std::fill(g.stash_release.begin(), g.stash_release.end(), nullptr);
     g.last_done = nullptr;
@@ -1130,11 +1138,6 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   TRY(make_events(g.ev_g, g.L));
   g.ev_g_set.assign(g.L, 0);
   HIPCHK(hipEventCreate(&g.ev_zero));
-  { const char* e = getenv("KFKB_WGRAD_STREAM"); g.wgrad_overlap = !(e && e[0] == '0'); }
-  { const char* e = getenv("KFKB_FUSE_W"); g.fuse_w_reductions = !(e && e[0] == '0'); }
-  { const char* e = getenv("KFKB_LANES"); g.lanes = (e && e[0] == '1') ? 1 : 2; }
-  { const char* e = getenv("GPU_MAX_HW_QUEUES"); if (e && atoi(e) >= 5) HIPCHK(hipStreamCreateWithFlags(&g.sw, hipStreamNonBlocking)); }
-  HIPCHK(hipEventCreate(&g.ev_sw_tail));
   TRY(make_events(g.ev_x, g.Mmax)); TRY(make_events(g.ev_dy, g.Mmax));
   TRY(make_events(g.ev_f0, g.Mmax)); TRY(make_events(g.ev_f1, g.Mmax));
   TRY(make_events(g.ev_b0, g.Mmax)); TRY(make_events(g.ev_b1, g.Mmax));
@@ -1559,7 +1562,6 @@ int run_pipeline_kFkB(int k) {
   TRY(pipeline_list_schedule(S, k, M, sched));
   // nothing of an earlier iteration may still be running: every stream waits for every other
   hipStream_t all[4] = {g.lane[0].s, g.lane[1].s, g.ss, g.sr};
-  if (g.sw != nullptr) { HIPCHK(hipEventRecord(g.ev_sw_tail, g.sw)); for (hipStream_t q : all) HIPCHK(hipStreamWaitEvent(q, g.ev_sw_tail, 0)); }
   for (int i = 0; i < 4; i++) HIPCHK(hipEventRecord(gp.ev_join[i], all[i]));
   for (int i = 0; i < 4; i++)
     for (int j = 0; j < 4; j++) if (i != j) HIPCHK(hipStreamWaitEvent(all[i], gp.ev_join[j], 0));
@@ -1653,7 +1655,6 @@ int stage_zero_grads(void) {
   HIPCHK(launch_fill_zero(g.grad, (size_t)g.L * g.po.total, q0));
   HIPCHK(hipEventRecord(g.ev_zero, q0));
   HIPCHK(hipStreamWaitEvent(g.lane[1].s, g.ev_zero, 0));
-  if (g.sw != nullptr) HIPCHK(hipStreamWaitEvent(g.sw, g.ev_zero, 0));
   std::fill(g.ev_g_set.begin(), g.ev_g_set.end(), 0);
   return 0;
 }
@@ -1662,9 +1663,24 @@ int stage_set_wgrad_stream(int enable) {
   if (!g.inited) return fail(KFKB_E_STATE, "stage_set_wgrad_stream before stage_init");
   if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_wgrad_stream while micro-batches are live");
   for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
-  if (g.sw != nullptr) HIPCHK(hipStreamSynchronize(g.sw));
   const int prev = g.wgrad_overlap ? 1 : 0;
   g.wgrad_overlap = enable != 0;
+  return prev;
+}
+
+int stage_set_fused_w_reductions(int enable) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_set_fused_w_reductions before stage_init");
+  if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_fused_w_reductions while micro-batches are live");
+  for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
+  const int prev = g.fuse_w_reductions ? 1 : 0;
+  g.fuse_w_reductions = enable != 0;
+  return prev;
+}
+
+int kfkb_set_big_tile_min(int tiles) {
+  if (tiles < 1) return fail(KFKB_E_ARG, "kfkb_set_big_tile_min: need tiles >= 1 (got %d)", tiles);
+  const int prev = kfkb::g_big_tile_min;
+  kfkb::g_big_tile_min = tiles;
   return prev;
 }
 
@@ -1673,7 +1689,6 @@ int stage_set_compute_lanes(int lanes) {
   if (lanes != 1 && lanes != 2) return fail(KFKB_E_ARG, "stage_set_compute_lanes: 1 or 2 lanes (got %d)", lanes);
   if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_compute_lanes while micro-batches are live");
   for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
-  if (g.sw != nullptr) HIPCHK(hipStreamSynchronize(g.sw));
   const int prev = g.lanes;
   g.lanes = lanes;
   return prev;
@@ -1682,7 +1697,6 @@ int stage_set_compute_lanes(int lanes) {
 int stage_sync(void) {
   if (!g.inited) return fail(KFKB_E_STATE, "stage_sync before stage_init");
   for (int i = 0; i < 2; i++) HIPCHK(hipStreamSynchronize(g.lane[i].s));
-  if (g.sw != nullptr) HIPCHK(hipStreamSynchronize(g.sw));
   HIPCHK(hipStreamSynchronize(g.sr));
   HIPCHK(hipStreamSynchronize(g.ss));
   return 0;
@@ -1693,8 +1707,7 @@ int stage_sync_timeout(double seconds) {
   const auto t0 = std::chrono::steady_clock::now();
   for (;;) {
     bool done = true;
-    for (hipStream_t s : {g.lane[0].s, g.lane[1].s, g.sw, g.sr, g.ss}) {
-      if (s == nullptr) continue;
+    for (hipStream_t s : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) {
       hipError_t e = hipStreamQuery(s);
       if (e == hipErrorNotReady) done = false;
       else if (e != hipSuccess) return fail(KFKB_E_HIP, "hipStreamQuery failed: %s", hipGetErrorString(e));
@@ -1733,8 +1746,6 @@ int stage_destroy(void) {
   if (!g.inited) return 0;
   for (hipStream_t q : {g.lane[0].s, g.lane[1].s, g.sr, g.ss}) hipStreamSynchronize(q);
   pipeline_release();
-  if (g.sw != nullptr) { hipStreamSynchronize(g.sw); hipStreamDestroy(g.sw); }
-  hipEventDestroy(g.ev_sw_tail);
   for (auto* v : {&g.ev_x, &g.ev_dy, &g.ev_f0, &g.ev_f1, &g.ev_b0, &g.ev_b1, &g.ev_ys, &g.ev_dxs, &g.ev_w, &g.ev_g, &g.ev_t0[0], &g.ev_t0[1], &g.ev_t0[2], &g.ev_t0[3]})
     for (auto e : *v) hipEventDestroy(e);
   for (auto& ln : g.lane) {

@@ -29,7 +29,6 @@
 #include "../../include/kfkb.h"
 #include <algorithm>
 #include <type_traits>
-#include <cstdlib>
 
 namespace kfkb {
 // Built once per 16-bit storage type: this file as it is for bf16, through gemm_f16.hip (which defines
@@ -1005,12 +1004,7 @@ static hipError_t launch_group(const TnGroup& grp, const ReduceGroup& rg, double
 }
 
 // fewest 256 x 256 tiles a launch must have before they are preferred over 128 x 128 tiles
-// (KFKB_BIG_TILE_MIN overrides it for experiments)
-static long big_tile_min() {
-  static long v = -1;
-  if (v < 0) { const char* e = getenv("KFKB_BIG_TILE_MIN"); v = e ? atol(e) : 192; }
-  return v;
-}
+static long big_tile_min() { return g_big_tile_min; }
 
 hipError_t launch_gemm_h16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
   if (red_done) *red_done = false;

@@ -614,6 +614,8 @@ hipError_t launch_ln_bwd_final(const float* scratch, int rows, int H, float* dga
   return hipGetLastError();
 }
 
+size_t colsum_scratch_floats(int rows, int N) { return rows <= 0 ? 0 : (size_t)reduce_parts(rows) * 2 * N; }
+
 hipError_t launch_colsum_accum(int dt, const void* dy, float* out, float* scratch, int rows, int N, hipStream_t s) {
   if (rows <= 0) return hipSuccess;
   if (dt == DT_BF16)

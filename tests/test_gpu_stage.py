@@ -284,3 +284,28 @@ def test_recomputation_keeps_every_bit_and_lets_a_larger_k_in(dt, L, H, heads, T
     for a, b_ in zip(plain, (st.grads, st.h_out, st.h_ingrad)):
         assert torch.equal(a, b_)
     st.close()
+
+
+def test_a_transfer_that_does_not_arrive_in_time_gives_a_timeout_not_a_hang():
+    """Failure detection: an input whose transfer is delayed by 1.5 s makes stage_sync_timeout(0.1 s) give
+    KFKB_E_TIMEOUT (the delay kernel itself is bounded, so every kernel still exits); stage_sync then drains the
+    iteration and the results are those of the undelayed run, bit for bit."""
+    dt, L, H, heads, T, b, M = kf.F32, 1, 64, 2, 16, 1, 2
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=1)
+    _run(st, 1, M)
+    ref = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+    late = np.zeros(M, dtype=np.int64)
+    late[0] = 1_500_000_000
+    kf.stage_set_delays(late, None, None, None)
+    kf.stage_zero_grads()
+    kf.run_kFkB(1, M, 0)
+    with pytest.raises(kf.KfkbError) as e:
+        kf.stage_sync_timeout(0.1)
+    assert e.value.code == -5
+    kf.stage_sync()                                     # the transfer arrives after all: everything completes
+    assert kf.stage_sync_timeout(1.0) == 0
+    assert kf.stage_last_run_ms() >= 1400.0
+    for a, b_ in zip(ref, (st.grads, st.h_out, st.h_ingrad)):
+        assert torch.equal(a, b_)
+    kf.stage_set_delays(None, None, None, None)
+    st.close()

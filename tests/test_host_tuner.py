@@ -103,7 +103,7 @@ def test_tuner_argument_errors(lib):
 
 def test_candidate_enumeration_matches_the_oracle(lib):
     rnd = random.Random(5)
-    assert kf.kfkb_enumerate_candidates(192, 6 * 10, 10, k_max=6) == [(k, 6 // k) for k in range(1, 7)]   # paper, Section 6.3.1
+    assert kf.kfkb_enumerate_candidates(192, 6 * 10, 10, k_max=6) == [(k, 6 // k) for k in range(1, 7)]   # paper, Section 6.2.1
     for _ in range(200):
         G = rnd.choice([6, 12, 16, 30, 64, 192])
         S = rnd.randint(1, 6); s = rnd.randint(0, S - 1)

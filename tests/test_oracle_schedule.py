@@ -132,7 +132,7 @@ def test_iteration_rejects_bad_orders(tiny):
 
 
 def test_candidates_on_the_memory_limit_curve():
-    """Section 4.2 (pruning) and the granularity test of Section 6.3.1: global batch 192, k = 1..6 run with
+    """Section 4.2 (pruning) and the granularity test of Section 6.2.1: global batch 192, k = 1..6 run with
     micro-batch size 6 // k, i.e. a device that holds six samples per warm-up group."""
     for S, s in ((1, 0), (8, 0), (8, 5)):
         w = S - 1 - s

@@ -1,4 +1,4 @@
-"""Pins of the oracle's cost model / tuner (paper Sections 3.3, 5.2, 5.4): closed forms and invariants.
+"""Pins of the oracle's cost model / tuner (paper Sections 3.2.2, 4.3, 5.2, 5.4): closed forms and invariants.
 It is a heuristic: beyond these cases it is "parity unpinned"."""
 import pytest
 
