@@ -360,6 +360,16 @@ int kfkb_op_layernorm_bwd(int dtype, const void* dy, const void* x, const float*
 int kfkb_op_colsum_accum(int dtype, const void* dy, float* out, float* scratch, int rows, int N, void* stream);
 size_t kfkb_op_reduce_scratch_floats(int width);
 
+/* kfkb_op_colsum_accum for callers that cannot allocate device memory: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The same two kernels; the partial sums of the first pass go to a
+ * 16 MiB array built into the library (one copy per GPU, held until the process ends) instead of a buffer of the
+ * caller's.  dy: device, [rows, N] in `dtype`; out: device, fp32 [N], added to.  N % 8 == 0 and N <= 32768,
+ * otherwise KFKB_E_ARG and nothing is launched.  Calls no hipMalloc / hipFree (kfkb_profile must be off: timing
+ * creates events).  Nothing has to be cleared between calls (the first pass rewrites every entry the second
+ * reads), but all calls on one GPU share the one array: two calls whose kernels may overlap on that GPU (different
+ * streams, no ordering between them) race.  Enqueues only. */
+int kfkb_op_colsum_accum_static(int dtype, const void* dy, float* out, int rows, int N, void* stream);
+
 /* du = dg * gelu_tanh'(u), n elements. */
 int kfkb_op_gelu_bwd(int dtype, const void* dg, const void* u, void* du, size_t n, void* stream);
 

@@ -19,6 +19,7 @@ __all__ = [
     "stage_last_k", "stage_side_streams_overlap", "stage_zero_grads", "stage_set_wgrad_stream", "stage_set_compute_lanes", "stage_set_fused_w_reductions", "kfkb_set_big_tile_min", "stage_sync", "stage_sync_timeout", "stage_destroy", "stage_get_order",
     "stage_last_run_ms", "StageBuffers", "kfkb_profile", "kfkb_profile_report",
     "kfkb_op_gemm", "kfkb_op_tile_weights", "kfkb_op_gemm_nt_tiled", "kfkb_op_layernorm_fwd", "kfkb_op_layernorm_bwd", "kfkb_op_colsum_accum",
+    "kfkb_op_colsum_accum_static",
     "kfkb_op_reduce_scratch_floats", "kfkb_op_gelu_bwd", "kfkb_op_attention_fwd", "kfkb_op_attention_bwd",
     "kfkb_op_transpose", "kfkb_op_delay",
 ]
@@ -126,6 +127,7 @@ def load_library():
         "kfkb_op_layernorm_fwd": (i, [i, vp, vp, vp, vp, vp, vp, i, i, C.c_float, vp]),
         "kfkb_op_layernorm_bwd": (i, [i, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, i, i, vp]),
         "kfkb_op_colsum_accum": (i, [i, vp, vp, vp, i, i, vp]),
+        "kfkb_op_colsum_accum_static": (i, [i, vp, vp, i, i, vp]),
         "kfkb_op_reduce_scratch_floats": (sz, [i]),
         "kfkb_op_gelu_bwd": (i, [i, vp, vp, vp, sz, vp]),
         "kfkb_op_attention_fwd": (i, [i, vp, vp, vp, i, i, i, i, i, vp]),
@@ -507,6 +509,10 @@ def kfkb_op_layernorm_bwd(dtype, dy, x, mean, rstd, gamma, dres, dx, dgamma, dbe
 
 def kfkb_op_colsum_accum(dtype, dy, out, scratch, rows, N, stream=None):
     return _check(load_library().kfkb_op_colsum_accum(dtype, _ptr(dy), _ptr(out), _ptr(scratch), rows, N, _stream(stream)))
+
+
+def kfkb_op_colsum_accum_static(dtype, dy, out, rows, N, stream=None):
+    return _check(load_library().kfkb_op_colsum_accum_static(dtype, _ptr(dy), _ptr(out), rows, N, _stream(stream)))
 
 
 def kfkb_op_reduce_scratch_floats(width):

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libkfkb.so")
-SOURCES = ["engine.hip", "rowwise.hip", "f32_path.hip", "gemm_bf16.hip", "attention_bf16.hip", "gemm_f16.hip", "attention_f16.hip"]
+SOURCES = ["engine.hip", "rowwise.hip", "f32_path.hip", "gemm_bf16.hip", "attention_bf16.hip", "gemm_f16.hip", "attention_f16.hip", "noalloc.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-I", os.path.join(ROOT, "include")]
