@@ -89,8 +89,15 @@ class Run:
             self.st.set_inputs_one(mb, *cache[src])
         self.setup_seconds = time.time() - t0
         self.overlap = kf.stage_side_streams_overlap()
-        kf.stage_set_wgrad_stream(args.wgrad_stream)
-        kf.stage_set_compute_lanes(args.lanes)
+        # the library picks lanes and W-step placement from the stage's shape; the flags override it
+        self.lanes = kf.stage_set_compute_lanes(1)
+        self.wgrad_stream = kf.stage_set_wgrad_stream(0)
+        if args.lanes:
+            self.lanes = args.lanes
+        if args.wgrad_stream >= 0:
+            self.wgrad_stream = args.wgrad_stream
+        kf.stage_set_compute_lanes(self.lanes)
+        kf.stage_set_wgrad_stream(self.wgrad_stream)
         self.delay_model = args.delay or w["delay"]
         self.limit = int(w["limit"])
         self.flops_iter = M * stage_flops(L, b, T, H)
@@ -138,8 +145,8 @@ def kernel_pass(run, k, steps, args):
         run.step(k, 0, 1)
     kf.stage_sync()
     kf.kfkb_profile(False)
-    kf.stage_set_wgrad_stream(args.wgrad_stream)
-    kf.stage_set_compute_lanes(args.lanes)
+    kf.stage_set_wgrad_stream(run.wgrad_stream)
+    kf.stage_set_compute_lanes(run.lanes)
     run.delay_model = saved
     stats = kf.kfkb_profile_report()
     tot_ms = sum(s["total_ms"] for s in stats) or 1.0
@@ -208,15 +215,18 @@ def cpu_baseline(run, np):
         one_blocks, one_T, one_L = run.blocks[:1], min(T, 256), 1
     else:
         blk = {n: np.asarray(v, dtype=np.float64) for n, v in run.block0.items()}
-        # tokens so that the sample is about 1.5 TFLOP of float64 work (10 - 30 s on the machine's cores)
-        Ts = int(min(T, max(32, 2 ** int(np.log2(1.5e12 / (3.0 * 24.0 * H * H))))))
-        secs = once([blk], 1, Ts)
-        f_meas = stage_flops(1, 1, Ts, H)
+        # tokens (and, where one sample's whole sequence is not enough, samples) so that the sample is about
+        # 12 TFLOP of float64 work: 10 - 30 s on the machine's cores
+        target = 1.2e13
+        Ts = int(min(T, max(32, 2 ** int(np.log2(target / (3.0 * 24.0 * H * H))))))
+        ns = int(min(8, max(1, target // stage_flops(1, 1, Ts, H))))
+        secs = once([blk], ns, Ts)
+        f_meas = ns * stage_flops(1, 1, Ts, H)
         out = dict(value=(f_meas / secs) / flops_sample, unit="samples/s", cores=cores, kind="oracle", seconds=secs,
                    extrapolated=True, measured_gflops=f_meas / secs / 1e9,
-                   sample="EXTRAPOLATED by model FLOPs from forward+backward of ONE block on ONE sample cut to %d of its %d "
+                   sample="EXTRAPOLATED by model FLOPs from forward+backward of ONE block on %d sample(s) cut to %d of %d "
                           "tokens (%.2f TFLOP of float64 numpy) to the %d-block stage at full sequence length "
-                          "(%.1f TFLOP per sample)" % (Ts, T, f_meas / 1e12, L, flops_sample / 1e12))
+                          "(%.1f TFLOP per sample)" % (ns, Ts, T, f_meas / 1e12, L, flops_sample / 1e12))
         one_blocks, one_T, one_L = [blk], max(16, Ts // 8), 1
     if threadpool_limits is not None:
         with threadpool_limits(limits=1):
@@ -233,6 +243,11 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="very-wide-stage", choices=sorted(WORKLOADS))
+    ap.add_argument("--ks", default=None,
+                    help="comma-separated group sizes to scan instead of the workload's own (e.g. 4 for a short profiling run)")
+    ap.add_argument("--microbatches", type=int, default=0,
+                    help="run the workload with this many micro-batches per iteration instead of its own (same kernels and "
+                         "launch shapes, shorter iteration: for profiling runs)")
     ap.add_argument("--scan-steps", type=int, default=0,
                     help="timed steps per k of the per-k scan (after one warm-up step each); 0 = max(3, steps / 5)")
     ap.add_argument("--profile-steps", type=int, default=0, help="steps of the per-kernel pass; 0 = 2 for the large workloads, else steps")
@@ -243,12 +258,12 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, used to scale "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
-    ap.add_argument("--wgrad-stream", type=int, default=1, choices=[0, 1],
-                    help="1 (the library's default): weight and bias gradients run on the other lane's stream beside the "
-                         "input-gradient chain; 0: everything on the op's own stream")
-    ap.add_argument("--lanes", type=int, default=2, choices=[1, 2],
-                    help="compute lanes (the library's default is 2): ops in flight at once, within the plan's peak of live "
-                         "micro-batches")
+    ap.add_argument("--wgrad-stream", type=int, default=-1, choices=[-1, 0, 1],
+                    help="1: weight and bias gradients run on the other lane's stream beside the input-gradient chain; "
+                         "0: everything on the op's own stream; -1 (default): the library's own choice for the stage's shape")
+    ap.add_argument("--lanes", type=int, default=0, choices=[0, 1, 2],
+                    help="compute lanes: ops in flight at once, within the plan's peak of live micro-batches; 0 (default): "
+                         "the library's own choice for the stage's shape (2 for small blocks, 1 for large ones)")
     ap.add_argument("--adaptive", action="store_true",
                     help="also time the same steps under the tuner (run_kFkB_adaptive: moving averages of the measured "
                          "transfer times, k re-chosen every 2 iterations among the workload's k values)")
@@ -286,6 +301,10 @@ def main():
         w = dict(WORKLOADS[name])
         if args.dtype is not None and w["dtype"] != "f32":
             w["dtype"] = args.dtype
+        if args.ks and name == args.workload:
+            w["ks"] = tuple(int(k) for k in args.ks.split(","))
+        if args.microbatches and name == args.workload:
+            w["M"] = args.microbatches
         return w
 
     def measure(name, steps, warmup, with_extras):
@@ -384,7 +403,7 @@ def main():
         "config": {"workload": args.workload, "layers": L, "hidden": H, "heads": heads, "seq_len": T, "micro_batch": b,
                    "num_microbatches": M, "global_batch": M * b, "k": best_k, "delay": run.delay_model,
                    "activation_limit_bytes": run.limit,
-                   "side_streams_overlap": bool(run.overlap), "wgrad_stream": bool(args.wgrad_stream), "compute_lanes": args.lanes,
+                   "side_streams_overlap": bool(run.overlap), "wgrad_stream": bool(run.wgrad_stream), "compute_lanes": run.lanes,
                    "recompute": bool(args.recompute)},
         "tflops": best["tflops"], "tflops_megatron_convention": best["tflops_megatron"],
         "frac_of_bf16_peak": best["tflops"] / PEAK_BF16_TFLOPS if w["dtype"] != "f32" else None,   # fp16 has the same peak
@@ -407,8 +426,10 @@ def main():
             pair = [(synth.microbatch_inputs(j, cb, T, H, w["dtype"]), synth.microbatch_upstream_grads(j, cb, T, H, w["dtype"])) for j in range(2)]
             for mb in range(cM):
                 cst.set_inputs_one(mb, *pair[mb % 2])
-            kf.stage_set_wgrad_stream(args.wgrad_stream)
-            kf.stage_set_compute_lanes(args.lanes)
+            if args.lanes:
+                kf.stage_set_compute_lanes(args.lanes)
+            if args.wgrad_stream >= 0:
+                kf.stage_set_wgrad_stream(args.wgrad_stream)
 
             def cstep(i):
                 kf.stage_set_delays(*delays_for(synth, run.delay_model, cM, i, args.steps))

@@ -203,7 +203,9 @@ int stage_last_k(void);
  * Measures three 1 ms delay kernels, one per stream; call while the stage is idle. */
 int stage_side_streams_overlap(void);
 int stage_zero_grads(void);               /* enqueues a fill of grad_accum on the compute stream */
-/* Compute lanes (2 by default).  run_kFkB admits ops in schedule order, up to `lanes` at a time and only while
+/* Compute lanes.  Default: 2 where one block's matrix products are small enough to leave the chip partly idle
+ * (24 * tokens * hidden^2 < 6e11 flops per block forward), 1 above that, where kernels of two streams only take
+ * each other's CUs.  run_kFkB admits ops in schedule order, up to `lanes` at a time and only while
  * an activation slot is free, so the plan's peak of live micro-batches (paper sections 3.1, 4.2: larger k holds
  * more activations) is never exceeded; the blocks of the ops in flight are enqueued in turn on one stream per
  * lane.  Independent micro-batches of a group then fill each other's idle phases; k = 1 on the last stage
@@ -211,7 +213,7 @@ int stage_zero_grads(void);               /* enqueues a fill of grad_accum on th
  * accumulation into a block's gradients stays in micro-batch order.  With 2 lanes ops overlap in time in
  * stage_get_order.  Call while no micro-batch is live.  Returns the previous setting. */
 int stage_set_compute_lanes(int lanes);
-/* W steps (on by default): the weight, bias and LayerNorm parameter gradients of a block (the
+/* W steps (beside the chain by default exactly where the default number of lanes is 2): the weight, bias and LayerNorm parameter gradients of a block (the
  * gradient-accumulation task nodes of paper section 2.4) are enqueued on the other lane's stream while that
  * lane has no op of its own, and run beside the chain of input gradients of the following blocks and of the
  * next op; the accumulation order, hence every result bit, is unchanged.  An op's end time in

@@ -49,8 +49,9 @@ void prof_key_name_bf16(int key, char* out, size_t cap, int* bound) {
     *bound = 0;
     snprintf(out, cap, "%s<%d>", cls == 0 ? "attn_fwd_bf16_kernel" : cls == 1 ? "attn_bwd_dq_bf16_kernel" : "attn_bwd_dkv_bf16_kernel", (key - PK_ATTN_FWD) % 100 ? 128 : 64);
   } else if (key >= PK_ATTN_DSUM && key < PK_LN_FWD) snprintf(out, cap, "attn_dsum_kernel");
-  else if (key >= PK_LN_FWD && key < PK_LN_BWD_DX) snprintf(out, cap, "ln_fwd_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_FWD) / 4);
-  else if (key >= PK_LN_BWD_DX && key < PK_LN_BWD_DX + 80) snprintf(out, cap, "ln_bwd_dx_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_BWD_DX) / 4);
+  // forward and dx kernels: key = class + 20 log2(waves per row) + 4 log2(chunks per lane) + (float ? 1 : 0)
+  else if (key >= PK_LN_FWD && key < PK_LN_BWD_DX) snprintf(out, cap, "ln_fwd_kernel<%s,%d,%d>", (key & 3) == 1 ? "float" : "bf16", 1 << ((key - PK_LN_FWD) % 20 / 4), 1 << ((key - PK_LN_FWD) / 20));
+  else if (key >= PK_LN_BWD_DX && key < PK_LN_BWD_DX + 80) snprintf(out, cap, "ln_bwd_dx_kernel<%s,%d,%d>", (key & 3) == 1 ? "float" : "bf16", 1 << ((key - PK_LN_BWD_DX) % 20 / 4), 1 << ((key - PK_LN_BWD_DX) / 20));
   else if (key >= PK_LN_BWD_DX + 80 && key < PK_COLSUM) snprintf(out, cap, "ln_bwd_fused_kernel<%s,%d>", (key & 3) == 1 ? "float" : "bf16", (key - PK_LN_BWD_DX - 80) / 4);
   else if (key == PK_COLSUM + 10 || key == PK_COLSUM + 12) snprintf(out, cap, "colsum_group_partial_kernel<%s>", key == PK_COLSUM + 12 ? "float" : "bf16");
   else if (key == PK_COLSUM_FINAL + 1) snprintf(out, cap, "colsum_group_final_kernel");
@@ -1145,6 +1146,16 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   for (auto& v : g.ev_t0) TRY(make_events(v, g.Mmax));
   HIPCHK(hipEventCreate(&g.ev_epoch));
   HIPCHK(hipEventCreate(&g.ev_run_end));
+  // How much of the chip one op's kernels fill decides how ops are best run.  A block whose matrix products are a
+  // few hundred GFLOP leaves gaps (launch latency, partly filled rounds of tiles, memory-bound row kernels) that a
+  // second micro-batch in flight and W steps beside the chain fill: two lanes.  From about 0.6 TFLOP per block
+  // forward on, every kernel runs many rounds of tiles on all CUs, kernels of two streams only take each other's
+  // CUs and cache, and one op at a time with its W steps behind its chain is faster (measured: hidden 2048 with
+  // 4096 tokens 298 against 316 ms per iteration for two lanes, hidden 4096 with 2048 tokens 366 against 357,
+  // hidden 8192 with 4096 tokens 2430 against 2290).  stage_set_compute_lanes / stage_set_wgrad_stream override.
+  const bool big_ops = 24.0 * (double)g.m * (double)g.H * (double)g.H >= 6.0e11;
+  g.lanes = big_ops ? 1 : 2;
+  g.wgrad_overlap = !big_ops;
   g.inited = true;
   return 0;
 }

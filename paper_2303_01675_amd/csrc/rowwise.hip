@@ -7,17 +7,36 @@
 namespace kfkb {
 
 // ------------------------------------------------------------------------------------------------
-// LayerNorm forward: one wave per row, the row lives in registers between the two passes.
-// Lane l owns the 8-element chunks l, l+64, l+128, ...  (H % 8 == 0, H <= 512 * NCH).
+// LayerNorm forward.  A row is shared by WPR waves of a 256-thread block (1, 2 or 4; the block holds 4 / WPR rows)
+// and lives in registers between the passes: lane l of the row's wave w owns the 8-element chunks
+// (i * WPR + w) * 64 + l, i < NCH  (H % 8 == 0, H <= 512 * NCH * WPR).  Wide rows are split over waves so that a
+// lane holds a few chunks only: many waves fit a CU and enough loads are in flight to keep HBM busy; the waves of
+// a row meet in LDS, partial sums added in wave order.
 // ------------------------------------------------------------------------------------------------
-template <typename T, int NCH>
+template <int WPR>
+__device__ __forceinline__ float row_sum(float v, float* red, int wave, int lane) {
+  v = wave_sum(v);
+  if constexpr (WPR == 1) return v;
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  const int w0 = wave / WPR * WPR;
+  float t = red[w0];
+#pragma unroll
+  for (int j = 1; j < WPR; j++) t += red[w0 + j];
+  return t;
+}
+
+template <typename T, int NCH, int WPR>
 __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, const T* __restrict__ gamma,
                                                      const T* __restrict__ beta, T* __restrict__ y,
                                                      float* __restrict__ mean, float* __restrict__ rstd,
                                                      int rows, int H, float eps) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
+  __shared__ float red[2][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = min(blockIdx.x * (4 / WPR) + wave / WPR, rows - 1);      // waves past the end redo the last row
+  const bool owner = blockIdx.x * (4 / WPR) + wave / WPR < rows;
+  if (WPR == 1 && !owner) return;
+  const int wr = wave % WPR;
   const int nchunks = H >> 3;
   const T* xr = x + (size_t)row * H;
   float v[NCH][8];
@@ -25,7 +44,7 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
-    const int c = lane + 64 * i;
+    const int c = (i * WPR + wr) * 64 + lane;
     if (c < nchunks) {
       Vec8<T>::load(xr + c * 8, v[i]);
       graw[i] = Vec8<T>::load_raw(gamma + c * 8);
@@ -34,22 +53,23 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
       for (int e = 0; e < 8; e++) s += v[i][e];
     }
   }
-  const float mu = wave_sum(s) / (float)H;
+  const float mu = row_sum<WPR>(s, red[0], wave, lane) / (float)H;
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
-    const int c = lane + 64 * i;
+    const int c = (i * WPR + wr) * 64 + lane;
     if (c < nchunks) {
 #pragma unroll
       for (int e = 0; e < 8; e++) { const float d = v[i][e] - mu; q += d * d; }
     }
   }
-  const float rs = 1.0f / sqrtf(wave_sum(q) / (float)H + eps);
-  if (lane == 0) { mean[row] = mu; rstd[row] = rs; }
+  const float rs = 1.0f / sqrtf(row_sum<WPR>(q, red[1], wave, lane) / (float)H + eps);
+  if (!owner) return;
+  if (lane == 0 && wr == 0) { mean[row] = mu; rstd[row] = rs; }
   T* yr = y + (size_t)row * H;
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
-    const int c = lane + 64 * i;
+    const int c = (i * WPR + wr) * 64 + lane;
     if (c < nchunks) {
       float g[8], b[8], o[8];
       Vec8<T>::unpack(graw[i], g);
@@ -62,28 +82,42 @@ __global__ void __launch_bounds__(256) ln_fwd_kernel(const T* __restrict__ x, co
 }
 
 // LayerNorm backward, input gradient:  g = dy*gamma;  dx = rstd (g - mean(g) - xhat mean(g xhat)) [+ dres]
-template <typename T, int NCH>
+// Rows are shared by WPR waves as in the forward kernel.
+template <typename T, int NCH, int WPR>
 __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy, const T* __restrict__ x,
                                                         const float* __restrict__ mean, const float* __restrict__ rstd,
                                                         const T* __restrict__ gamma, const T* __restrict__ dres,
                                                         T* __restrict__ dx, int rows, int H) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (row >= rows) return;
+  __shared__ float red[2][4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = min(blockIdx.x * (4 / WPR) + wave / WPR, rows - 1);
+  const bool owner = blockIdx.x * (4 / WPR) + wave / WPR < rows;
+  if (WPR == 1 && !owner) return;
+  const int wr = wave % WPR;
   const int nchunks = H >> 3;
   const float mu = mean[row], rs = rstd[row];
   const T* xr = x + (size_t)row * H;
   const T* dyr = dy + (size_t)row * H;
+  const T* rr = dres != nullptr ? dres + (size_t)row * H : xr;          // no residual: x again (in bounds, unused)
+  Raw8<T> xraw[NCH], graw[NCH], mraw[NCH], rraw[NCH];
+#pragma unroll
+  for (int i = 0; i < NCH; i++) {                                        // every load of the row in flight at once
+    const int c = min((i * WPR + wr) * 64 + lane, nchunks - 1);
+    xraw[i] = Vec8<T>::load_raw(xr + c * 8);
+    graw[i] = Vec8<T>::load_raw(dyr + c * 8);
+    mraw[i] = Vec8<T>::load_raw(gamma + c * 8);
+    rraw[i] = Vec8<T>::load_raw(rr + c * 8);
+  }
   float xh[NCH][8], g[NCH][8];
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
-    const int c = lane + 64 * i;
+    const int c = (i * WPR + wr) * 64 + lane;
     if (c < nchunks) {
       float gm[8];
-      Vec8<T>::load(xr + c * 8, xh[i]);
-      Vec8<T>::load(dyr + c * 8, g[i]);
-      Vec8<T>::load(gamma + c * 8, gm);
+      Vec8<T>::unpack(xraw[i], xh[i]);
+      Vec8<T>::unpack(graw[i], g[i]);
+      Vec8<T>::unpack(mraw[i], gm);
 #pragma unroll
       for (int e = 0; e < 8; e++) {
         xh[i][e] = (xh[i][e] - mu) * rs;
@@ -93,19 +127,20 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
       }
     }
   }
-  const float m1 = wave_sum(s1) / (float)H;
-  const float m2 = wave_sum(s2) / (float)H;
+  const float m1 = row_sum<WPR>(s1, red[0], wave, lane) / (float)H;
+  const float m2 = row_sum<WPR>(s2, red[1], wave, lane) / (float)H;
+  if (!owner) return;
   T* dxr = dx + (size_t)row * H;
 #pragma unroll
   for (int i = 0; i < NCH; i++) {
-    const int c = lane + 64 * i;
+    const int c = (i * WPR + wr) * 64 + lane;
     if (c < nchunks) {
       float o[8];
 #pragma unroll
       for (int e = 0; e < 8; e++) o[e] = rs * (g[i][e] - m1 - xh[i][e] * m2);
       if (dres != nullptr) {
         float r[8];
-        Vec8<T>::load(dres + (size_t)row * H + c * 8, r);
+        Vec8<T>::unpack(rraw[i], r);
 #pragma unroll
         for (int e = 0; e < 8; e++) o[e] += r[e];
       }
@@ -523,21 +558,35 @@ __global__ void delay_since_kernel(const long long* stamp, long long ticks) {
 // ------------------------------------------------------------------------------------------------
 static inline int nch_for(int H) { const int n = (H + 511) / 512; return n <= 1 ? 1 : n <= 2 ? 2 : n <= 4 ? 4 : n <= 8 ? 8 : 16; }
 
-#define KFKB_NCH_SWITCH(NCHV, ...)                                                     \
-  switch (NCHV) {                                                                      \
-    case 1: { constexpr int NCH = 1; __VA_ARGS__; break; }                             \
-    case 2: { constexpr int NCH = 2; __VA_ARGS__; break; }                             \
-    case 4: { constexpr int NCH = 4; __VA_ARGS__; break; }                             \
-    case 8: { constexpr int NCH = 8; __VA_ARGS__; break; }                             \
-    default: { constexpr int NCH = 16; __VA_ARGS__; break; }                           \
+// How a row is dealt to the lanes of the forward and dx kernels: WPR waves per row, NCH chunks of 8 per lane,
+// 512 * NCH * WPR >= H.  At most 4 chunks per lane: wide rows go over more waves, not into more registers.
+struct RowShape { int nch, wpr, code; };
+static inline RowShape row_shape(int H) {
+  const int per_wave = (H + 511) / 512;                        // chunks per lane if one wave took the row
+  int wpr = per_wave <= 2 ? 1 : per_wave <= 4 ? 2 : 4;
+  int nch = (per_wave + wpr - 1) / wpr;
+  nch = nch <= 1 ? 1 : nch <= 2 ? 2 : 4;
+  const int wcode = wpr == 1 ? 0 : wpr == 2 ? 1 : 2, ncode = nch == 1 ? 0 : nch == 2 ? 1 : 2;
+  return RowShape{nch, wpr, wcode * 20 + ncode * 4};
+}
+
+#define KFKB_ROW_SWITCH(RS, ...)                                                                       \
+  switch ((RS).wpr * 8 + (RS).nch) {                                                                   \
+    case 1 * 8 + 1: { constexpr int WPR = 1, NCH = 1; __VA_ARGS__; break; }                            \
+    case 1 * 8 + 2: { constexpr int WPR = 1, NCH = 2; __VA_ARGS__; break; }                            \
+    case 2 * 8 + 2: { constexpr int WPR = 2, NCH = 2; __VA_ARGS__; break; }                            \
+    case 4 * 8 + 2: { constexpr int WPR = 4, NCH = 2; __VA_ARGS__; break; }                            \
+    default: { constexpr int WPR = 4, NCH = 4; __VA_ARGS__; break; }                                   \
   }
 
 template <typename T>
 static hipError_t ln_fwd_t(const T* x, const T* g, const T* b, T* y, float* mean, float* rstd, int rows, int H,
                            float eps, hipStream_t s) {
-  const dim3 grid((rows + 3) / 4);
+  const RowShape rs = row_shape(H);
+  const int rpb = 4 / rs.wpr;
+  const dim3 grid((rows + rpb - 1) / rpb);
   const double bytes = 2.0 * rows * H * sizeof(T);
-  KFKB_NCH_SWITCH(nch_for(H), klaunch(ln_fwd_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_FWD + NCH * 4 + (int)sizeof(T) / 4, bytes, x, g, b, y, mean, rstd, rows, H, eps));
+  KFKB_ROW_SWITCH(rs, klaunch(ln_fwd_kernel<T, NCH, WPR>, grid, dim3(256), 0, s, PK_LN_FWD + rs.code + (int)sizeof(T) / 4, bytes, x, g, b, y, mean, rstd, rows, H, eps));
   return hipGetLastError();
 }
 
@@ -574,9 +623,11 @@ static hipError_t ln_bwd_t(const T* dy, const T* x, const float* mean, const flo
   if (nch == 1) return ln_bwd_fused_launch<T, 1>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
   if (nch == 2) return ln_bwd_fused_launch<T, 2>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
   if (nch == 4) return ln_bwd_fused_launch<T, 4>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
-  const dim3 grid((rows + 3) / 4);
+  const RowShape rs = row_shape(H);
+  const int rpb = 4 / rs.wpr;
+  const dim3 grid((rows + rpb - 1) / rpb);
   const double bytes = (dres ? 4.0 : 3.0) * rows * H * sizeof(T);
-  KFKB_NCH_SWITCH(nch, klaunch(ln_bwd_dx_kernel<T, NCH>, grid, dim3(256), 0, s, PK_LN_BWD_DX + NCH * 4 + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, rows, H));
+  KFKB_ROW_SWITCH(rs, klaunch(ln_bwd_dx_kernel<T, NCH, WPR>, grid, dim3(256), 0, s, PK_LN_BWD_DX + rs.code + (int)sizeof(T) / 4, bytes, dy, x, mean, rstd, gamma, dres, dx, rows, H));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   return colsum_launch<T, true>(dy, x, mean, rstd, dgamma != nullptr ? dbeta : (float*)nullptr, dgamma, scratch, rows, H, s);

@@ -2,8 +2,13 @@
 16 heads, seq 1024, micro-batch 4, 16 micro-batches, bf16), in the launch configuration bench.py times.
 The oracle computes what it can in reasonable time: two whole micro-batches (outputs, input gradients and the
 accumulated gradient of a two-micro-batch iteration); the full 16-micro-batch iteration is then checked by
-properties that hold at any size: sampled micro-batches equal the oracle's, every k gives bit-identical
-results, and the 16-micro-batch gradient contains the 2-micro-batch one in its running sum order."""
+properties that hold at any size (sampled micro-batches equal the oracle's, every k gives bit-identical results)
+and its accumulated gradient G against the oracle's record of the same iteration: per parameter tensor the L2 norm
+and 48 seeded entries, stored in tests/golden/gpt2medium_stage_G.json by tests/golden/make_fullsize_golden.py,
+which calls the oracle only."""
+import json
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -76,7 +81,23 @@ def test_full_iteration_is_identical_for_every_k_and_consistent_with_the_sampled
     dxr, _ = sm.stage_bwd(dys[mb], blocks, caches, HEADS)
     assert_close(y_full[mb].float().numpy(), yr, kf.BF16, "Y[%d] of the 16-micro-batch run" % mb)
     assert_close(dx_full[mb].float().numpy(), dxr, kf.BF16, "dX[%d] of the 16-micro-batch run" % mb)
-    # the accumulated gradient is a sum of per-micro-batch terms of similar size: its norm grows roughly like
-    # sqrt(M) and every entry is finite
+    # the accumulated gradient of all 16 micro-batches against the oracle's record of the same iteration
     g = ref[0]
     assert torch.isfinite(g).all()
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "gpt2medium_stage_G.json")) as f:
+        gold = json.load(f)
+    c = gold["case"]
+    assert (c["L"], c["H"], c["heads"], c["T"], c["b"], c["M"]) == (L, H, HEADS, T, B, M)
+    offs, per = kf.param_offsets(H, 4 * H)
+    gh = g.cpu().numpy().astype(np.float64)
+    for l in range(L):
+        for n in synth.PARAM_ORDER:
+            rec = gold["tensors"]["%d.%s" % (l, n)]
+            o, shp = offs[n]
+            t = gh[l * per + o: l * per + o + int(np.prod(shp))]
+            # the sampled entries, on the scale of the tensor's typical entry (single entries of a sum of 65536
+            # token terms may cancel to nearly nothing; the tolerance is a per-tensor one)
+            scale = rec["l2"] / np.sqrt(t.size)
+            assert_close(t[np.asarray(rec["positions"])], np.asarray(rec["values"]), kf.BF16, "G block %d %s, sampled" % (l, n),
+                         floor=scale)
+            assert abs(np.linalg.norm(t) - rec["l2"]) <= 2e-2 * rec["l2"], ("G block %d %s: norm" % (l, n), np.linalg.norm(t), rec["l2"])
