@@ -60,6 +60,9 @@ def delays_for(synth, model, M, step_index, n_steps, seed0=4242):
         return tuple(synth.delays_lognormal(M, 2.0, 0.5, seed=seed0 + 4 * step_index + i) for i in range(4))
     if model == "bimodal":
         return tuple(synth.delays_bimodal(M, 0.5, 10.0, 0.7, seed=seed0 + 4 * step_index + i) for i in range(4))
+    if model.startswith("fixed:"):                              # every transfer delayed by the same time, in ms
+        import numpy as np
+        return (np.full(M, int(float(model[6:]) * 1e6), dtype=np.int64),) * 4
     return (synth.delays_drift(M, step_index, n_steps, 20.0),) * 4
 
 
@@ -277,9 +280,10 @@ def main():
                     help="activation recomputation: LayerNorm and GELU outputs are formed again in the backward pass")
     ap.add_argument("--dtype", default=None, choices=["bf16", "f16"],
                     help="storage type of a 16-bit workload (default bf16; f16 is the paper's precision, same kernels)")
-    ap.add_argument("--delay", default=None, choices=["none", "lognormal", "bimodal", "drift"],
-                    help="per-transfer injected delay; default: the workload's own (lognormal: mean 2 ms, sigma 0.5; "
-                         "bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms over the timed steps)")
+    ap.add_argument("--delay", default=None,
+                    help="per-transfer injected delay: none | lognormal | bimodal | drift | fixed:MS; default: the workload's "
+                         "own (lognormal: mean 2 ms, sigma 0.5; bimodal: 0.5 ms w.p. 0.7 / 10 ms w.p. 0.3; drift: 0 -> 20 ms "
+                         "over the timed steps; fixed:MS: every transfer MS milliseconds)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build drives one pipeline stage on ONE GPU; --gpus %d is not supported "
