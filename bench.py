@@ -101,6 +101,8 @@ class Run:
             self.wgrad_stream = args.wgrad_stream
         kf.stage_set_compute_lanes(self.lanes)
         kf.stage_set_wgrad_stream(self.wgrad_stream)
+        if args.wstep_window > 0:
+            kf.stage_set_wstep_window(args.wstep_window)
         self.delay_model = args.delay or w["delay"]
         self.limit = int(w["limit"])
         self.flops_iter = M * stage_flops(L, b, T, H)
@@ -258,6 +260,9 @@ def main():
                     help="a second workload timed after the first, reported under \"secondary\" (default: gpt2-medium-stage "
                          "when the first is the default workload, else none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wstep-window", type=int, default=0,
+                    help="most micro-batches whose gradient accumulation goes into one W step (stage_set_wstep_window); "
+                         "1: every backward accumulates by itself; 0 (default): the library's default, 8")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic, used to scale "
                          "the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")

@@ -155,8 +155,9 @@ size_t stage_param_count(void);
 size_t stage_activation_bytes(int k, int num_microbatches);
 
 /* Device bytes the caller must provide to stage_bind for plans up to group size k_max
- * (activation stash for the peak live count, transfer slots, backward scratch, and the
- * re-laid-out weight copy the bf16 kernels read). */
+ * (activation stash for the peak live count, transfer slots, backward scratch, the
+ * re-laid-out weight copy the bf16 kernels read, and, for k_max >= 2, the operands of a
+ * W-step window: min(k_max, 8) * layers * 9 b*T*H output-gradient elements). */
 size_t stage_workspace_bytes(int k_max);
 
 /* Hands the library its memory.  workspace: device, >= stage_workspace_bytes(k_max) bytes,
@@ -226,6 +227,16 @@ int stage_set_wgrad_stream(int enable);
  * the two settings agree to fp32 rounding, each is bit-reproducible.  Call while no micro-batch is live.
  * Returns the previous setting. */
 int stage_set_fused_w_reductions(int enable);
+/* W-step windows.  The backwards of one kFkB schedule unit run back to back, so a 16-bit stage whose shapes allow it
+ * (hidden % 128 == 0, tokens per micro-batch % 32 == 0) accumulates the gradients of a block ONCE for up to
+ * `max_microbatches` of them (at most 8, the default; never more than the k_max the workspace was sized for): the
+ * fp32 gradients are then read and written once per window instead of once per micro-batch, which is what a larger k
+ * buys on the compute side.  Every gradient keeps its bits: a weight-gradient tile starts from the accumulator and
+ * adds the products of every token on top in token order, whatever the window.  The micro-batches of a window give
+ * their activation and input slots back when the window's last W step has been enqueued, not one by one.  1 switches
+ * the windows off; a stage with activation recomputation has none (the recomputed tensors would have to be kept for
+ * the whole window).  Call while no micro-batch is live.  Returns the previous setting. */
+int stage_set_wstep_window(int max_microbatches);
 /* Tile choice of the 16-bit matrix products: 256 x 256 tiles are used where the product divides into at least
  * `tiles` of them (default 192: three quarters of the 256 CUs get a tile), 128 x 128 tiles otherwise.  Process-wide,
  * host-only; returns the previous value.  A product's result does not depend on the tile shape beyond fp32

@@ -190,24 +190,27 @@ hipError_t launch_gemm_f16(const GemmArgs& g, hipStream_t s);
 static inline hipError_t launch_gemm_16(int dt, const GemmArgs& g, hipStream_t s) {
   return dt == DT_F16 ? launch_gemm_f16(g, s) : launch_gemm_bf16(g, s);
 }
-// The small reductions that belong to the same step as a group of weight-gradient products: column sums over the
-// token axis of up to four bf16 matrices dy[rows, width] (out[i][c] += sum_r dy[i][r][c]) and the finishing pass of
-// up to two LayerNorm backward reductions (partial rows left by launch_ln_bwd called with dgamma == nullptr;
-// ln_parts[i] = ln_bwd_partial_rows(rows, width); out0 += the first half of every partial row, out1 += the second).
+// A W step: every accumulation into the gradients of one block, for a window of up to kWSeg micro-batches
+// (segments), in one launch.  Weight gradients: G[M,N] (fp32) += sum over segments A_s[K,M]^T . B_s[K,N], K = tokens
+// per micro-batch; the tile starts from G and the products of every token are added on top in token order, so the
+// result does not depend on how many micro-batches a launch covers.  The small reductions ride along in the same
+// launch: column sums over the token axis of up to four 16-bit matrices dy_s[rows, width] (out[c] += sum_r dy_s[r][c],
+// one segment after the other) and the finishing pass of up to two LayerNorm backward reductions (partial rows left
+// by launch_ln_bwd called with dgamma == nullptr; ln_parts = ln_bwd_partial_rows(rows, width); out0 += the first
+// half of every partial row, out1 += the second).
+constexpr int kWSeg = 8;
+struct WGrad { int M, N; float* Cacc; const void* A[kWSeg]; const void* B[kWSeg]; };
 struct WStepReduce {
   int rows, n_colsum, n_ln;
-  const void* dy[4]; float* out[4]; int width[4];
-  const float* ln_partial[2]; float* ln_out0[2]; float* ln_out1[2]; int ln_parts[2]; int ln_width[2];
+  const void* dy[4][kWSeg]; float* out[4]; int width[4];
+  const float* ln_partial[2][kWSeg]; float* ln_out0[2]; float* ln_out1[2]; int ln_parts[2]; int ln_width[2];
 };
-// Up to 4 wgrads in one launch.  With `red`, workgroups of the same launch also do those reductions on the CUs the
-// tiles leave idle when the shapes allow (*red_done = true); otherwise *red_done = false and the caller runs them.
-hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
-                                     bool* red_done = nullptr);
-hipError_t launch_gemm_f16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
-                                    bool* red_done = nullptr);
-static inline hipError_t launch_gemm_16_tn_group(int dt, const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red = nullptr,
-                                                 bool* red_done = nullptr) {
-  return dt == DT_F16 ? launch_gemm_f16_tn_group(g, n, s, red, red_done) : launch_gemm_bf16_tn_group(g, n, s, red, red_done);
+// shapes one grouped launch takes: M, N multiples of 128, K a multiple of 32, reduction widths multiples of 64
+bool wstep_groupable(const WGrad* g, int n, int K, const WStepReduce* red);
+hipError_t launch_wstep_bf16(const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red);
+hipError_t launch_wstep_f16(const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red);
+static inline hipError_t launch_wstep_16(int dt, const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red) {
+  return dt == DT_F16 ? launch_wstep_f16(g, n, K, nseg, s, red) : launch_wstep_bf16(g, n, K, nseg, s, red);
 }
 int ln_bwd_partial_rows(int rows, int H);        // partial rows launch_ln_bwd leaves in its scratch
 size_t colsum_scratch_floats(int rows, int N);   // floats of `scratch` that launch_colsum_accum writes and reads

@@ -231,6 +231,27 @@ struct Stage {
     hipEvent_t ev_tail = nullptr;
   };
   Lane lane[2];
+  // W-step windows (16-bit stages whose shapes take the grouped launch): the backwards of one schedule unit run
+  // back to back, so the gradient accumulation of a block is done ONCE for up to kWSeg of them: their operands are
+  // kept in a pool [window position][block] and the W step of block l is launched when the last of them has passed
+  // block l.  The fp32 gradients are then read and written once per window instead of once per micro-batch, and
+  // the matrix pipes work through a k times longer token axis per tile.  The result is the same bit for bit
+  // whatever the window (see launch_wstep_16).  Activation slots and input slots of a window's micro-batches go
+  // back to their pools when its last W step has been enqueued.  Not with activation recomputation: the recomputed
+  // LayerNorm and GELU outputs would have to be kept for the whole window, which is the memory that mode is there to
+  // save; every backward then accumulates by itself.
+  struct WOps { char *du = nullptr, *dqkv = nullptr, *dx1 = nullptr, *dx = nullptr; float* ln[2] = {nullptr, nullptr}; };
+  struct Deferred { int stash, x_slot, dy_slot; };
+  bool wstep_grouped = false;                                // the stage's W steps take the grouped launch
+  int wwin_cap = 1;                                          // window positions the bound workspace holds
+  int wwin_max = kWSeg;                                      // stage_set_wstep_window
+  std::vector<WOps> wpool;                                   // [position * L + block]
+  std::vector<hipEvent_t> ev_wops;                           // [position * L + block]: that chain has written its operands
+  std::vector<int> w_arrived;                                // per block: chains of the open window enqueued so far
+  std::vector<Deferred> w_deferred;                          // slots of the open window's finished micro-batches
+  bool w_open = false;                                       // a window has been opened and its last W step is not enqueued yet
+  int w_size = 0, w_mbs[kWSeg] = {};                         // the open window: its micro-batches in backward order
+  hipEvent_t ev_wlast = nullptr;                             // the most recent W step (they are chained, so: all of them)
   int lanes = 2;
   bool wgrad_overlap = true;
   // cfg.recompute: the LayerNorm outputs a, c and the GELU output g are not stashed; a forward keeps them in
@@ -299,7 +320,22 @@ LaneCarve lane_carve(const Stage& s) {
   return c;
 }
 
-struct Carve { size_t wt, stash, xs, dys, ys, dxs, lanes, total; int n_stash, n_x, n_io; };
+struct Carve { size_t wt, stash, xs, dys, ys, dxs, lanes, wpool, total; int n_stash, n_x, n_io, wwin; };
+
+// bytes of one (window position, block) entry of the W-step operand pool
+struct WOpsCarve { size_t du, dqkv, dx1, dx, ln, total; };
+WOpsCarve wops_carve(const Stage& s) {
+  WOpsCarve c{};
+  const size_t act = align_up(s.n * s.esz);
+  size_t off = 0;
+  c.du = off; off += align_up((size_t)s.m * s.F * s.esz);
+  c.dqkv = off; off += align_up(3 * s.n * s.esz);
+  c.dx1 = off; off += act;
+  c.dx = off; off += act;
+  c.ln = off; off += 2 * align_up(red_ln_floats(s) * 4);
+  c.total = off;
+  return c;
+}
 
 Carve carve_for(const Stage& s, int k_max) {
   Carve c{};
@@ -315,6 +351,9 @@ Carve carve_for(const Stage& s, int k_max) {
   c.ys = off; off += (size_t)c.n_io * act;
   c.dxs = off; off += (size_t)c.n_io * act;
   c.lanes = off; off += 2 * lane_carve(s).total;
+  c.wwin = (s.wstep_grouped && !s.recompute && k_max >= 2) ? std::min(k_max, kWSeg) : 1;
+  c.wpool = off;
+  if (c.wwin >= 2) off += (size_t)c.wwin * s.L * wops_carve(s).total;
   c.total = off;
   return c;
 }
@@ -421,6 +460,8 @@ struct ActiveOp {
   int first = 0;
   const char* x_first = nullptr;
   char* dx_first = nullptr;
+  // backward op that belongs to a W-step window of wsize >= 2 micro-batches, at position wpos (0: none)
+  int wpos = 0, wsize = 0;
 };
 
 int forward_block(ActiveOp& a) {
@@ -445,17 +486,87 @@ int forward_block(ActiveOp& a) {
   return 0;
 }
 
+// The W step of block l for `nseg` micro-batches (their operands in ops[0 .. nseg-1], in backward order) on stream
+// qw: weight gradients, bias column sums and the LayerNorm-parameter finishing pass.  Grouped stages do it in one
+// launch; otherwise (fp32, shapes the grouped launch does not take) one micro-batch at a time with the plain kernels.
+struct WOperands { const void *a, *c, *o, *gact, *dqkv, *du, *dx1, *dy; const float* ln1; const float* ln2; float* red_w; };
+
+int launch_w_step(Stage& s, int l, const WOperands* ops, int nseg, hipStream_t qw) {
+  const int widths[4] = {3 * s.H, s.F, s.H, s.H};
+  float* bias_out[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
+  if (s.wstep_grouped) {
+    WGrad wg[4] = {};
+    // order of the group: qkv, fc1, fc2, proj (as the chain produces their operands last to first)
+    const int wm[4] = {s.H, s.H, s.F, s.H}, wn[4] = {3 * s.H, s.F, s.H, s.H};
+    float* wacc[4] = {gptr(s, l, s.po.w_qkv), gptr(s, l, s.po.w_1), gptr(s, l, s.po.w_2), gptr(s, l, s.po.w_o)};
+    WStepReduce red{};
+    red.rows = s.m; red.n_colsum = 4; red.n_ln = 2;
+    for (int i = 0; i < 4; i++) { wg[i].M = wm[i]; wg[i].N = wn[i]; wg[i].Cacc = wacc[i]; red.out[i] = bias_out[i]; red.width[i] = widths[i]; }
+    for (int sg = 0; sg < nseg; sg++) {
+      const WOperands& o = ops[sg];
+      wg[0].A[sg] = o.a; wg[0].B[sg] = o.dqkv;
+      wg[1].A[sg] = o.c; wg[1].B[sg] = o.du;
+      wg[2].A[sg] = o.gact; wg[2].B[sg] = o.dy;
+      wg[3].A[sg] = o.o; wg[3].B[sg] = o.dx1;
+      red.dy[0][sg] = o.dqkv; red.dy[1][sg] = o.du; red.dy[2][sg] = o.dy; red.dy[3][sg] = o.dx1;
+      red.ln_partial[0][sg] = o.ln2; red.ln_partial[1][sg] = o.ln1;     // partial rows: [sum dy | sum dy * xhat] -> beta, gamma
+    }
+    red.ln_out0[0] = gptr(s, l, s.po.ln2_b); red.ln_out1[0] = gptr(s, l, s.po.ln2_g);
+    red.ln_out0[1] = gptr(s, l, s.po.ln1_b); red.ln_out1[1] = gptr(s, l, s.po.ln1_g);
+    red.ln_parts[0] = red.ln_parts[1] = ln_bwd_partial_rows(s.m, s.H);
+    red.ln_width[0] = red.ln_width[1] = s.H;
+    HIPCHK(launch_wstep_16(s.dt, wg, 4, s.m, nseg, qw, s.fuse_w_reductions ? &red : nullptr));
+    if (!s.fuse_w_reductions) {
+      for (int sg = 0; sg < nseg; sg++) {                          // the same sums, one micro-batch after the other
+        const WOperands& o = ops[sg];
+        const void* srcs[4] = {o.dqkv, o.du, o.dy, o.dx1};
+        HIPCHK(launch_ln_bwd_final(o.ln2, s.m, s.H, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), qw));
+        HIPCHK(launch_ln_bwd_final(o.ln1, s.m, s.H, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), qw));
+        HIPCHK(launch_colsum_group(s.dt, 4, srcs, bias_out, widths, o.red_w, s.m, qw));
+      }
+    }
+    return 0;
+  }
+  for (int sg = 0; sg < nseg; sg++) {
+    const WOperands& o = ops[sg];
+    const GemmArgs wg[4] = {
+        GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, 3 * s.H, s.m, o.a, o.dqkv, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_qkv)},
+        GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, s.F, s.m, o.c, o.du, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_1)},
+        GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.F, s.H, s.m, o.gact, o.dy, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_2)},
+        GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, s.H, s.H, s.m, o.o, o.dx1, nullptr, nullptr, nullptr, nullptr, gptr(s, l, s.po.w_o)}};
+    for (int i = 0; i < 4; i++) {
+      if (dt_is16(s.dt)) {
+        const char* why = gemm_bf16_check(wg[i]);
+        if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
+        HIPCHK(launch_gemm_16(s.dt, wg[i], qw));
+      } else {
+        HIPCHK(launch_gemm_f32(wg[i], qw));
+      }
+    }
+    const void* srcs[4] = {o.dqkv, o.du, o.dy, o.dx1};
+    HIPCHK(launch_ln_bwd_final(o.ln2, s.m, s.H, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), qw));
+    HIPCHK(launch_ln_bwd_final(o.ln1, s.m, s.H, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), qw));
+    HIPCHK(launch_colsum_group(s.dt, 4, srcs, bias_out, widths, o.red_w, s.m, qw));
+  }
+  return 0;
+}
+
 int backward_block(ActiveOp& a) {
   Stage& s = g;
   const MbState& st = s.mb[a.mb];
   Stage::Lane& ln = s.lane[a.lane];
   hipStream_t q = ln.s;
   const int l = a.next;
+  const bool windowed = a.wsize >= 2;
   const uint64_t seq = ln.seq++;
   const int par = (int)(seq & 1), ring = (int)(seq % Stage::kRing);
-  char* du = ln.t_mf[par];
-  char* dqkv = ln.t_3n[par];
-  char* dx1 = ln.t_dx1[par];
+  // where this block's W-step operands go: the window's pool entry, or the lane's alternating buffers
+  Stage::WOps* wp = windowed ? &s.wpool[(size_t)a.wpos * s.L + l] : nullptr;
+  char* du = windowed ? wp->du : ln.t_mf[par];
+  char* dqkv = windowed ? wp->dqkv : ln.t_3n[par];
+  char* dx1 = windowed ? wp->dx1 : ln.t_dx1[par];
+  float* red_ln2 = windowed ? wp->ln[1] : ln.red_ln[par][1];
+  float* red_ln1 = windowed ? wp->ln[0] : ln.red_ln[par][0];
   char* dc = ln.t_n0;
   char* d_o = ln.t_n0;           // dc is dead once dx1 exists
   char* da = ln.t_n0;            // d_o is dead once dqkv exists
@@ -464,83 +575,71 @@ int backward_block(ActiveOp& a) {
   const bool bt = dt_is16(s.dt);                        // 16-bit input-gradient products read the chunk-major copies
   WtView w = bt ? wt_view(s, l) : WtView{};
   const char* x = (l == 0) ? s.xs.buf[st.x_slot] : (a.x_first != nullptr && l == a.first) ? a.x_first : view(s, st.stash, l - 1).y;
-  char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : (a.dx_first != nullptr && l == a.first) ? a.dx_first : ln.t_dxr[seq % 3];
+  char* dx = (l == 0) ? s.dxs.buf[a.out_buf] : (a.dx_first != nullptr && l == a.first) ? a.dx_first : windowed ? wp->dx : ln.t_dxr[seq % 3];
   // where the W step of this block goes: the other lane's stream, beside this chain, when that lane has nothing
-  // of its own to do; behind the chain otherwise (the other lane's op then fills the chip beside it)
-  hipStream_t qw = !s.wgrad_overlap ? q : !a.other_busy ? s.lane[1 - a.lane].s : q;
+  // of its own to do; behind the chain otherwise (the other lane's op then fills the chip beside it).  A window's
+  // W step follows the chain of whichever of its micro-batches passes the block last.
+  hipStream_t qw = (windowed || !s.wgrad_overlap) ? q : !a.other_busy ? s.lane[1 - a.lane].s : q;
   // the buffers about to be overwritten were last read by the W step of two blocks ago
-  if (seq >= 2 && ln.w_elsewhere[(seq - 2) % Stage::kRing]) HIPCHK(hipStreamWaitEvent(q, ln.ev_wdone[(seq - 2) % Stage::kRing], 0));
+  if (!windowed && seq >= 2 && ln.w_elsewhere[(seq - 2) % Stage::kRing]) HIPCHK(hipStreamWaitEvent(q, ln.ev_wdone[(seq - 2) % Stage::kRing], 0));
   if (s.recompute) {
     // what the forward did not keep: LayerNorm outputs from the kept inputs (the statistics come out as they were),
     // GELU output from the kept pre-activation
-    v.a = ln.r_a[par]; v.c = ln.r_c[par]; v.gact = ln.r_g[par];
+    v.a = ln.r_a[par]; v.c = ln.r_c[par]; v.gact = ln.r_g[par];        // (no windows with recomputation)
     HIPCHK(launch_ln_fwd(s.dt, x, wptr(s, l, s.po.ln1_g), wptr(s, l, s.po.ln1_b), v.a, v.mean1, v.rstd1, s.m, s.H, s.cfg.ln_eps, q));
     HIPCHK(launch_ln_fwd(s.dt, v.x1, wptr(s, l, s.po.ln2_g), wptr(s, l, s.po.ln2_b), v.c, v.mean2, v.rstd2, s.m, s.H, s.cfg.ln_eps, q));
     HIPCHK(launch_gelu_fwd(s.dt, v.u, v.gact, (size_t)s.m * s.F, q));
   }
-  // the four weight-gradient products of a block are issued together: one launch fills the chip where each
-  // alone would not
-  GemmArgs wg[4];
-  auto wgrad = [&](int i, int in, int out, const void* xin, const void* dyv, float* acc) {
-    wg[i] = GemmArgs{KFKB_GEMM_TN, KFKB_EPI_ACCUM, in, out, s.m, xin, dyv, nullptr, nullptr, nullptr, nullptr, acc};
-  };
   // y = x1 + g W2 + b2
-  wgrad(2, s.F, s.H, v.gact, dy, gptr(s, l, s.po.w_2));
   TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_GELU_BWD, s.m, s.F, s.H, dy, bt ? w.w2_d : wptr(s, l, s.po.w_2), nullptr, v.u, du, nullptr, nullptr, bt));
   // u = c W1 + b1
-  wgrad(1, s.H, s.F, v.c, du, gptr(s, l, s.po.w_1));
   TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.F, du, bt ? w.w1_d : wptr(s, l, s.po.w_1), nullptr, nullptr, dc, nullptr, nullptr, bt));
   // c = LN2(x1), plus the residual path; the parameter gradients are finished in the W step
-  HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, nullptr, nullptr, ln.red_ln[par][1], s.m, s.H, q));
+  HIPCHK(launch_ln_bwd(s.dt, dc, v.x1, v.mean2, v.rstd2, wptr(s, l, s.po.ln2_g), dy, dx1, nullptr, nullptr, red_ln2, s.m, s.H, q));
   // x1 = x + o Wo + bo
-  wgrad(3, s.H, s.H, v.o, dx1, gptr(s, l, s.po.w_o));
   TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, s.H, dx1, bt ? w.o_d : wptr(s, l, s.po.w_o), nullptr, nullptr, d_o, nullptr, nullptr, bt));
   // o = attention(qkv)
   TRY(attention_bwd(s, q, v.qkv, v.o, d_o, v.lse, ln.dsum, dqkv));
   // qkv = a Wqkv + bqkv
-  wgrad(0, s.H, 3 * s.H, v.a, dqkv, gptr(s, l, s.po.w_qkv));
   TRY(gemm(s, q, KFKB_GEMM_NT, KFKB_EPI_NONE, s.m, s.H, 3 * s.H, dqkv, bt ? w.qkv_d : wptr(s, l, s.po.w_qkv), nullptr, nullptr, da, nullptr, nullptr, bt));
   // a = LN1(x), plus the residual path
-  HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, nullptr, nullptr, ln.red_ln[par][0], s.m, s.H, q));
+  HIPCHK(launch_ln_bwd(s.dt, da, x, v.mean1, v.rstd1, wptr(s, l, s.po.ln1_g), dx1, dx, nullptr, nullptr, red_ln1, s.m, s.H, q));
 
   // ---- W step: every accumulation into the gradients of block l, in micro-batch order -----------------
+  if (windowed) {
+    HIPCHK(hipEventRecord(s.ev_wops[(size_t)a.wpos * s.L + l], q));
+    if (++s.w_arrived[l] == s.w_size) {                   // the window's last chain through this block: its W step
+      for (int p = 0; p < s.w_size; p++)
+        if (p != a.wpos) HIPCHK(hipStreamWaitEvent(q, s.ev_wops[(size_t)p * s.L + l], 0));
+      if (s.ev_wlast != nullptr) HIPCHK(hipStreamWaitEvent(q, s.ev_wlast, 0));   // W steps follow one another
+      WOperands ops[kWSeg];
+      for (int p = 0; p < s.w_size; p++) {
+        const MbState& mp = s.mb[s.w_mbs[p]];
+        StashView vp = view(s, mp.stash, l);
+        const Stage::WOps& o = s.wpool[(size_t)p * s.L + l];
+        const char* dyp = (l == s.L - 1) ? s.dys.buf[mp.dy_slot] : s.wpool[(size_t)p * s.L + l + 1].dx;
+        ops[p] = WOperands{vp.a, vp.c, vp.o, vp.gact, o.dqkv, o.du, o.dx1, dyp, o.ln[0], o.ln[1], ln.red_w[par]};
+      }
+      TRY(launch_w_step(s, l, ops, s.w_size, q));
+      HIPCHK(hipEventRecord(s.ev_g[l], q));
+      s.ev_g_set[l] = 1;
+      s.ev_wlast = s.ev_g[l];
+      s.w_arrived[l] = 0;
+    }
+    a.cur = dx;
+    a.next--; a.left--;
+    return 0;
+  }
   if (qw != q) {
     HIPCHK(hipEventRecord(ln.ev_chain[ring], q));
     HIPCHK(hipStreamWaitEvent(qw, ln.ev_chain[ring], 0));
   }
   if (s.ev_g_set[l]) HIPCHK(hipStreamWaitEvent(qw, s.ev_g[l], 0));     // the previous micro-batch's W step of this block
-  // the weight-gradient products in one launch; the bias-gradient column sums and the finishing pass of the two
-  // LayerNorm-parameter reductions ride along in it (bf16), or run as launches of their own
-  WStepReduce red{};
-  red.rows = s.m; red.n_colsum = 4; red.n_ln = 2;
-  {
-    const void* srcs[4] = {dqkv, du, dy, dx1};
-    float* outs[4] = {gptr(s, l, s.po.b_qkv), gptr(s, l, s.po.b_1), gptr(s, l, s.po.b_2), gptr(s, l, s.po.b_o)};
-    const int widths[4] = {3 * s.H, s.F, s.H, s.H};
-    for (int i = 0; i < 4; i++) { red.dy[i] = srcs[i]; red.out[i] = outs[i]; red.width[i] = widths[i]; }
-    // partial rows: [sum dy | sum dy * xhat] -> beta, gamma
-    red.ln_partial[0] = ln.red_ln[par][1]; red.ln_out0[0] = gptr(s, l, s.po.ln2_b); red.ln_out1[0] = gptr(s, l, s.po.ln2_g);
-    red.ln_partial[1] = ln.red_ln[par][0]; red.ln_out0[1] = gptr(s, l, s.po.ln1_b); red.ln_out1[1] = gptr(s, l, s.po.ln1_g);
-    red.ln_parts[0] = red.ln_parts[1] = ln_bwd_partial_rows(s.m, s.H);
-    red.ln_width[0] = red.ln_width[1] = s.H;
-  }
-  bool red_done = false;
-  if (dt_is16(s.dt)) {
-    for (int i = 0; i < 4; i++) {
-      const char* why = gemm_bf16_check(wg[i]);
-      if (why) return fail(KFKB_E_ARG, "%s (M=%d N=%d K=%d)", why, wg[i].M, wg[i].N, wg[i].K);
-    }
-    HIPCHK(launch_gemm_16_tn_group(s.dt, wg, 4, qw, s.fuse_w_reductions ? &red : nullptr, &red_done));
-  } else {
-    for (int i = 0; i < 4; i++) HIPCHK(launch_gemm_f32(wg[i], qw));
-  }
-  if (!red_done) {
-    HIPCHK(launch_ln_bwd_final(ln.red_ln[par][1], s.m, s.H, gptr(s, l, s.po.ln2_g), gptr(s, l, s.po.ln2_b), qw));
-    HIPCHK(launch_ln_bwd_final(ln.red_ln[par][0], s.m, s.H, gptr(s, l, s.po.ln1_g), gptr(s, l, s.po.ln1_b), qw));
-    HIPCHK(launch_colsum_group(s.dt, 4, red.dy, red.out, red.width, ln.red_w[par], s.m, qw));
-  }
+  const WOperands ops{v.a, v.c, v.o, v.gact, dqkv, du, dx1, dy, red_ln1, red_ln2, ln.red_w[par]};
+  TRY(launch_w_step(s, l, &ops, 1, qw));
   HIPCHK(hipEventRecord(s.ev_g[l], qw));
   s.ev_g_set[l] = 1;
+  s.ev_wlast = s.ev_g[l];
   ln.w_elsewhere[ring] = qw != q;
   if (qw != q) { HIPCHK(hipEventRecord(ln.ev_wdone[ring], qw)); a.w_stream = qw; }
   a.cur = dx;
@@ -640,8 +739,11 @@ int end_forward(ActiveOp& a) {
   return 0;
 }
 
-int begin_backward(int mbi, int lane, bool wait_ok, ActiveOp& a) {
+// wpos / wsize: position and size of the op's W-step window (wsize < 2: the op accumulates its gradients itself)
+int begin_backward(int mbi, int lane, bool wait_ok, ActiveOp& a, int wpos = 0, int wsize = 0) {
   MbState& st = g.mb[mbi];
+  // a window opens with its first micro-batch, once the previous one has enqueued all its W steps
+  if (wsize >= 2 && wpos == 0 && g.w_open) return wait_ok ? 1 : fail(KFKB_E_STATE, "backward of micro-batch %d: the previous W-step window is still open", mbi);
   if (st.bwd_done || st.bwd_begun) return fail(KFKB_E_STATE, "backward of micro-batch %d without a live forward", mbi);
   if (!st.fwd_done) {
     if (wait_ok && st.fwd_begun) return 1;            // its forward is still being enqueued
@@ -656,6 +758,12 @@ int begin_backward(int mbi, int lane, bool wait_ok, ActiveOp& a) {
   const int dxbuf = g.dxs.take();
   st.bwd_begun = true;
   hipStream_t q = g.lane[lane].s;
+  if (wsize >= 2) {
+    if (wpos == 0) { g.w_open = true; g.w_size = wsize; std::fill(g.w_arrived.begin(), g.w_arrived.end(), 0); g.w_deferred.clear(); }
+    g.w_mbs[wpos] = mbi;
+    // the pool entries were last read by the W steps of the previous window (chained: the last one stands for all)
+    if (g.ev_wlast != nullptr) HIPCHK(hipStreamWaitEvent(q, g.ev_wlast, 0));
+  }
   HIPCHK(hipStreamWaitEvent(q, g.ev_dy[mbi], 0));
   HIPCHK(hipStreamWaitEvent(q, g.ev_f1[mbi], 0));    // the forward may have run on the other lane
   if (g.dxs.release[dxbuf]) HIPCHK(hipStreamWaitEvent(q, g.dxs.release[dxbuf], 0));
@@ -663,6 +771,25 @@ int begin_backward(int mbi, int lane, bool wait_ok, ActiveOp& a) {
   g.log.push_back({KFKB_OP_B, mbi});
   a = ActiveOp{};
   a.op = KFKB_OP_B; a.mb = mbi; a.lane = lane; a.next = g.L - 1; a.left = g.L; a.out_buf = dxbuf; a.cur = g.dys.buf[st.dy_slot];
+  a.wpos = wpos; a.wsize = wsize;
+  return 0;
+}
+
+// The open window's last W step (block 0) has just been enqueued on stream q of lane `lane`: everything its
+// micro-batches held may be reused once that step is done.
+int close_window_on(hipStream_t q) {
+  const int last = g.w_mbs[g.w_size - 1];
+  HIPCHK(hipEventRecord(g.ev_w[last], q));
+  for (const auto& d : g.w_deferred) {
+    g.stash_release[d.stash] = g.ev_w[last];
+    g.stash_free.push_back(d.stash);
+    g.xs.give(d.x_slot, g.ev_w[last]);
+    g.dys.give(d.dy_slot, g.ev_w[last]);
+  }
+  g.w_deferred.clear();
+  for (int p = 0; p < g.w_size; p++) { MbState& m = g.mb[g.w_mbs[p]]; m.stash = m.x_slot = m.dy_slot = -1; }
+  g.w_open = false;
+  g.last_done = g.ev_w[last];
   return 0;
 }
 
@@ -686,6 +813,14 @@ int end_backward(ActiveOp& a) {
   HIPCHK(hipMemcpyAsync(g.h_ingrad + (size_t)mbi * bytes, g.dxs.buf[a.out_buf], bytes, hipMemcpyDeviceToHost, g.ss));
   HIPCHK(hipEventRecord(g.ev_dxs[mbi], g.ss));
   g.dxs.give(a.out_buf, g.ev_dxs[mbi]);
+  if (a.wsize >= 2) {
+    // the window's W steps still read this micro-batch's activations and gradients: its slots go back when the
+    // last of them has been enqueued (by the window's last micro-batch, which ends after all the others)
+    g.w_deferred.push_back(Stage::Deferred{st.stash, st.x_slot, st.dy_slot});
+    st.bwd_done = true;
+    if (a.wpos == a.wsize - 1) TRY(close_window_on(q));
+    return 0;
+  }
   // early release: the micro-batch's activations and its input slots return to their pools
   g.stash_release[st.stash] = ev_done;
   g.stash_free.push_back(st.stash);
@@ -1125,6 +1260,18 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   p.w_o = o; o += H * H; p.b_o = o; o += H; p.ln2_g = o; o += H; p.ln2_b = o; o += H;
   p.w_1 = o; o += H * F; p.b_1 = o; o += F; p.w_2 = o; o += F * H; p.b_2 = o; o += H; p.total = o;
   s.weights = (const char*)weights;
+  if (dt_is16(s.dt)) {
+    WGrad wg[4] = {};
+    const int wm[4] = {s.H, s.H, s.F, s.H}, wn[4] = {3 * s.H, s.F, s.H, s.H};
+    for (int i = 0; i < 4; i++) { wg[i].M = wm[i]; wg[i].N = wn[i]; }
+    WStepReduce red{};
+    red.rows = s.m; red.n_colsum = 4; red.n_ln = 2;
+    const int widths[4] = {3 * s.H, s.F, s.H, s.H};
+    for (int i = 0; i < 4; i++) red.width[i] = widths[i];
+    red.ln_width[0] = red.ln_width[1] = s.H;
+    red.ln_parts[0] = red.ln_parts[1] = ln_bwd_partial_rows(s.m, s.H);
+    s.wstep_grouped = wstep_groupable(wg, 4, s.m, &red);
+  }
   s.stash_block_bytes = stash_block_bytes_of(s);
   s.mb.assign(s.Mmax, MbState{});
   s.dl_x.assign(s.Mmax, 0); s.dl_dy.assign(s.Mmax, 0); s.dl_y.assign(s.Mmax, 0); s.dl_dx.assign(s.Mmax, 0);
@@ -1220,6 +1367,25 @@ int stage_bind(void* workspace, size_t workspace_bytes, float* grad_accum, const
       for (int j = 0; j < 2; j++) { char* q = r + (size_t)(1 + j) * set; ln.r_a[j] = q; ln.r_c[j] = q + act; ln.r_g[j] = q + 2 * act; }
     }
   }
+  g.wwin_cap = c.wwin;
+  g.wpool.clear();
+  for (auto e : g.ev_wops) (void)hipEventDestroy(e);
+  g.ev_wops.clear();
+  if (c.wwin >= 2) {
+    const WOpsCarve wc = wops_carve(g);
+    g.wpool.resize((size_t)c.wwin * g.L);
+    for (size_t i = 0; i < g.wpool.size(); i++) {
+      char* base = g.ws + c.wpool + i * wc.total;
+      Stage::WOps& w = g.wpool[i];
+      w.du = base + wc.du; w.dqkv = base + wc.dqkv; w.dx1 = base + wc.dx1; w.dx = base + wc.dx;
+      w.ln[0] = reinterpret_cast<float*>(base + wc.ln);
+      w.ln[1] = reinterpret_cast<float*>(base + wc.ln + align_up(red_ln_floats(g) * 4));
+    }
+    TRY(make_events(g.ev_wops, (int)g.wpool.size()));
+  }
+  g.w_arrived.assign(g.L, 0);
+  g.w_deferred.clear();
+  g.w_open = false; g.w_size = 0; g.ev_wlast = nullptr;
   g.stash_release.assign(c.n_stash, nullptr);
   reset_iteration_state();
   g.epoch_valid = false; g.run_timed = false; g.log.clear();
@@ -1294,6 +1460,22 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
   // Ops are admitted in schedule order, as many as there are lanes at a time and only while an activation
   // slot is free (the plan's peak of live micro-batches is never exceeded: k = 1 on the last stage runs one op
   // at a time); the blocks of the ops in flight are enqueued in turn.
+  // W-step windows: the backwards of a schedule unit, in runs of at most `wcap`; a run of one accumulates by itself
+  const int wcap = g.wstep_grouped ? std::min(g.wwin_cap, g.wwin_max) : 1;
+  std::vector<int> wpos(order.size(), 0), wsize(order.size(), 0);
+  if (wcap >= 2) {
+    for (size_t i = 0; i < order.size();) {
+      if (order[i].op != KFKB_OP_B) { i++; continue; }
+      size_t j = i;
+      while (j < order.size() && order[j].op == KFKB_OP_B) j++;          // the unit [i, j)
+      for (size_t b0 = i; b0 < j; b0 += wcap) {
+        const int n = (int)std::min<size_t>(wcap, j - b0);
+        for (int p2 = 0; p2 < n; p2++) { wpos[b0 + p2] = p2; wsize[b0 + p2] = n; }
+      }
+      i = j;
+    }
+  }
+  g.w_open = false;
   size_t rp = 0, next = 0;
   std::vector<ActiveOp> act;
   while (next < order.size() || !act.empty()) {
@@ -1308,7 +1490,8 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
       for (const auto& a : act) if (a.lane == lane) lane = 1 - lane;
       ActiveOp a;
       const bool wait_ok = !act.empty();
-      const int rc = order[next].op == KFKB_OP_F ? begin_forward(order[next].mb, lane, wait_ok, a) : begin_backward(order[next].mb, lane, wait_ok, a);
+      const int rc = order[next].op == KFKB_OP_F ? begin_forward(order[next].mb, lane, wait_ok, a)
+                                                 : begin_backward(order[next].mb, lane, wait_ok, a, wpos[next], wsize[next]);
       if (rc < 0) return rc;
       if (rc == 1) break;                             // needs something an op in flight still holds
       act.push_back(a);
@@ -1688,6 +1871,15 @@ int stage_set_fused_w_reductions(int enable) {
   return prev;
 }
 
+int stage_set_wstep_window(int max_microbatches) {
+  if (!g.inited) return fail(KFKB_E_STATE, "stage_set_wstep_window before stage_init");
+  if (max_microbatches < 1) return fail(KFKB_E_ARG, "stage_set_wstep_window: need a window of at least 1 micro-batch (got %d)", max_microbatches);
+  if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_wstep_window while micro-batches are live");
+  const int prev = g.wwin_max;
+  g.wwin_max = std::min(max_microbatches, kWSeg);
+  return prev;
+}
+
 int kfkb_set_big_tile_min(int tiles) {
   if (tiles < 1) return fail(KFKB_E_ARG, "kfkb_set_big_tile_min: need tiles >= 1 (got %d)", tiles);
   const int prev = kfkb::g_big_tile_min;
@@ -1763,6 +1955,7 @@ int stage_destroy(void) {
     for (int i = 0; i < Stage::kRing; i++) { hipEventDestroy(ln.ev_chain[i]); hipEventDestroy(ln.ev_wdone[i]); }
     hipEventDestroy(ln.ev_tail);
   }
+  for (auto e : g.ev_wops) hipEventDestroy(e);
   hipEventDestroy(g.ev_epoch); hipEventDestroy(g.ev_run_end); hipEventDestroy(g.ev_zero);
   g = Stage{};
   g_cfg_set = false;

@@ -49,6 +49,8 @@ typedef bf16x4 h16x4;
 #endif
 hipError_t launch_gemm_h16(const GemmArgs& g, hipStream_t s);
 const char* gemm_h16_check(const GemmArgs& g);
+bool wstep_groupable_h16(const WGrad* g, int n, int K, const WStepReduce* red);
+hipError_t launch_wstep_h16(const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red);
 
 constexpr int BK = 64;             // slice depth of the register-staged TN kernel
 
@@ -574,6 +576,97 @@ __device__ __forceinline__ void epilogue_accum_staged(f32x16 (&acc)[BM / 64][BN 
   }
 }
 
+// The W step's tiles start from the gradient accumulator itself: acc <- Cacc tile, the matrix instructions add the
+// products of every token on top in token order, the tile is stored once.  However many micro-batches one launch
+// covers, every element sees the same sequence of fp32 additions (storing and re-loading an fp32 value changes
+// nothing), so the gradients do not depend on how the W steps were batched.
+// Both directions go through LDS, 32 rows at a time (the wave's own staging rows, whole rows per instruction).
+// acc <- Cacc tile.  Every wave brings its own quadrant in, 32 rows at a time, with loads that write LDS directly
+// (no staging registers: the accumulators alone fill half the register file), two 32-row blocks in flight, and reads
+// each block back in accumulator layout.  A staged row is WC floats, its 16-byte pieces XOR-ed with (row & 15):
+// an accumulator-layout read touches one piece column of 16 rows per clock, which then lie in 16 different banks.
+template <int BM, int BN>
+__device__ __forceinline__ void load_accum_dma(f32x16 (&acc)[BM / 64][BN / 64], char* smem, const float* __restrict__ Cacc, int N,
+                                               int m0, int n0, int lane, int wave) {
+  constexpr int TM = BM / 64, TN = BN / 64, WR = BM / 2, WC = BN / 2;
+  constexpr int ROWB = WC * 4;                                    // bytes of a staged row
+  constexpr int LPR = ROWB / 16, RPI = 64 / LPR, NI = 32 / RPI;   // lanes per row, rows per load instruction, instructions per block
+  constexpr int BLKB = 32 * ROWB;                                 // bytes of a 32-row block
+  static_assert((size_t)2 * 4 * BLKB <= (size_t)RING * (BM + BN) * CK_ * 2, "two blocks per wave fit the ring's LDS");
+  static_assert(LPR >= 16, "the swizzle flips the low four bits of the piece index");
+  const int wm0 = (wave >> 1) * WR, wn0 = (wave & 1) * WC;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const i32x4 rc = make_rsrc(Cacc + (size_t)(m0 + wm0) * N + n0 + wn0, (size_t)WR * N * 4);
+  const unsigned lds_w = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem + wave * (2 * BLKB);
+  int voff[NI];
+#pragma unroll
+  for (int g = 0; g < NI; g++) {
+    const int row = g * RPI + lane / LPR, piece = (lane % LPR) ^ (row & 15);
+    voff[g] = (row * N + piece * 4) * 4;
+  }
+  auto issue = [&](int blk, int slot) {
+#pragma unroll
+    for (int g = 0; g < NI; g++) dma16b(rc, voff[g], blk * 32 * N * 4, lds_w + slot * BLKB + g * 1024);
+  };
+  issue(0, 0);
+  issue(1, 1);
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    if (i + 1 < TM) wait_vmcnt<NI>(); else wait_vmcnt<0>();       // loads retire in order: block i has landed
+    asm volatile("" ::: "memory");
+    const char* eb = smem + wave * (2 * BLKB) + (i & 1) * BLKB;
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        const float4 v = *reinterpret_cast<const float4*>(eb + frow * ROWB + (((j * 8 + q * 2 + fhalf) ^ (frow & 15)) << 4));
+        acc[i][j][q * 4 + 0] = v.x; acc[i][j][q * 4 + 1] = v.y; acc[i][j][q * 4 + 2] = v.z; acc[i][j][q * 4 + 3] = v.w;
+      }
+    wait_lgkm0();                                                 // read out before the slot is filled again
+    asm volatile("" ::: "memory");
+    if (i + 2 < TM) issue(i + 2, i & 1);
+  }
+  __syncthreads();                                                // the staging blocks become ring slots again
+}
+
+template <int BM, int BN>
+__device__ __forceinline__ void store_accum_staged(f32x16 (&acc)[BM / 64][BN / 64], char* smem, float* __restrict__ Cacc, int N,
+                                                   int m0, int n0, int lane, int wave) {
+  constexpr int TM = BM / 64, TN = BN / 64, WR = BM / 2, WC = BN / 2;
+  constexpr int RS = WC * 4 + 16;
+  constexpr int LPR = WC / 4, RPI = 64 / LPR, NI = 32 / RPI;
+  const int wm0 = (wave >> 1) * WR, wn0 = (wave & 1) * WC;
+  const int frow = lane & 31, fhalf = lane >> 5;
+  const int er = lane / LPR, ec = lane % LPR;
+  float* cbase = Cacc + (size_t)(m0 + wm0 + er) * N + n0 + wn0 + ec * 4;
+  __syncthreads();                                                // every wave is done with the ring
+  if constexpr (TM * TN == 16) mfma_results_settled();
+  char* ew = smem + wave * (32 * RS);
+#pragma unroll
+  for (int i = 0; i < TM; i++) {
+    __builtin_amdgcn_sched_barrier(0);                            // one 32-row block at a time
+#pragma unroll
+    for (int j = 0; j < TN; j++)
+#pragma unroll
+      for (int q = 0; q < 4; q++) {
+        float v[4];
+        if constexpr (TM * TN == 16) {                            // see epilogue_staged
+#pragma unroll
+          for (int e = 0; e < 4; e++) asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(v[e]) : "a"(acc[i][j][q * 4 + e]));
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; e++) v[e] = acc[i][j][q * 4 + e];
+        }
+        *reinterpret_cast<float4*>(ew + frow * RS + (j * 32 + q * 8 + fhalf * 4) * 4) = make_float4(v[0], v[1], v[2], v[3]);
+      }
+#pragma unroll
+    for (int t = 0; t < NI; t++) {
+      const float4 a = *reinterpret_cast<const float4*>(ew + (t * RPI + er) * RS + ec * 16);
+      *reinterpret_cast<float4*>(cbase + (size_t)(i * 32 + t * RPI) * N) = a;
+    }
+  }
+}
+
 template <int BM, int BN, int EPI, bool BT>
 __global__ void __launch_bounds__(256) gemm_h16_nt_kernel(int M, int N, int K, const h16_t* __restrict__ A, const h16_t* __restrict__ B,
                                                  const h16_t* __restrict__ bias, const h16_t* __restrict__ residual,
@@ -654,8 +747,10 @@ __global__ void __launch_bounds__(256) gemm_h16_tn_kernel(int M, int N, int K, c
 
 // Several weight-gradient products that share the reduction length K (the token axis) in one launch:
 // a backward pass of one block has four of them, each too small to fill the chip on its own.
-struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; const h16_t* A; const h16_t* B; float* Cacc; };
-struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
+// Every product covers `nseg` segments of the token axis (one per micro-batch of the W step's window), each with
+// operands of its own: Cacc[M,N] += sum_s A_s[K,M]^T . B_s[K,N], K tokens per segment.
+struct TnProblem { int M, N, tiles_m, tiles_n, first_tile; float* Cacc; const h16_t* A[kWSeg]; const h16_t* B[kWSeg]; };
+struct TnGroup { int count, K, total_tiles, nseg; TnProblem p[4]; };
 
 // The small reductions of the same step, done by extra workgroups of the same launch, on the CUs the tiles leave
 // idle (192 tiles of 256 x 256 on 256 CUs for a GPT-2-medium block), instead of by launches of their own:
@@ -664,14 +759,14 @@ struct TnGroup { int count, K, total_tiles; TnProblem p[4]; };
 //   partial[parts][2][width] (fp32) that the LayerNorm backward kernels left behind.
 // Work items are strips of 64 columns, dealt round-robin to the reduce workgroups; one workgroup owns a strip from
 // the first row to the last and adds in a fixed order, so the sums do not depend on timing or on the launch shape.
-struct RedColsum { const h16_t* dy; float* out; int width, first_item; };
-struct RedLnFinal { const float* partial; float* out0; float* out1; int parts, width, first_item; };
-struct ReduceGroup { int n_colsum, n_ln, rows, total_items; RedColsum c[4]; RedLnFinal ln[2]; };
+struct RedColsum { const h16_t* dy[kWSeg]; float* out; int width, first_item; };
+struct RedLnFinal { const float* partial[kWSeg]; float* out0; float* out1; int parts, width, first_item; };
+struct ReduceGroup { int n_colsum, n_ln, rows, total_items, nseg; RedColsum c[4]; RedLnFinal ln[2]; };
 
-__device__ __forceinline__ void reduce_colsum_strip(const RedColsum& pr, int strip, int rows, float* red) {
+__device__ __forceinline__ void reduce_colsum_strip(const h16_t* dy, float* out, int width, int strip, int rows, float* red) {
   const int cl = threadIdx.x & 7, rl = threadIdx.x >> 3;              // 8 lanes x 16 bytes = one 128-byte row piece
-  const h16_t* src = pr.dy + strip * 64 + cl * 8;
-  const size_t w = pr.width;
+  const h16_t* src = dy + strip * 64 + cl * 8;
+  const size_t w = width;
   float a[8];
 #pragma unroll
   for (int e = 0; e < 8; e++) a[e] = 0.f;
@@ -697,18 +792,18 @@ __device__ __forceinline__ void reduce_colsum_strip(const RedColsum& pr, int str
     float t = 0.f;
 #pragma unroll
     for (int j = 0; j < 32; j++) t += red[j * 65 + threadIdx.x];
-    pr.out[strip * 64 + threadIdx.x] += t;
+    out[strip * 64 + threadIdx.x] += t;
   }
   __syncthreads();
 }
 
-__device__ __forceinline__ void reduce_ln_strip(const RedLnFinal& pr, int strip, float* red) {
+__device__ __forceinline__ void reduce_ln_strip(const float* partial, float* out0, float* out1, int parts, int width, int strip, float* red) {
   const int c4 = threadIdx.x & 15, pl = threadIdx.x >> 4;             // 16 lanes x float4 = 64 columns, 16 part lanes
-  const size_t w = pr.width;
-  const float* src = pr.partial + strip * 64 + c4 * 4;
+  const size_t w = width;
+  const float* src = partial + strip * 64 + c4 * 4;
   float4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = s0;
   int p = pl;
-  for (; p + 16 * 3 < pr.parts; p += 16 * 4) {
+  for (; p + 16 * 3 < parts; p += 16 * 4) {
     float4 v0[4], v1[4];
 #pragma unroll
     for (int u = 0; u < 4; u++) {
@@ -721,7 +816,7 @@ __device__ __forceinline__ void reduce_ln_strip(const RedLnFinal& pr, int strip,
       s1.x += v1[u].x; s1.y += v1[u].y; s1.z += v1[u].z; s1.w += v1[u].w;
     }
   }
-  for (; p < pr.parts; p += 16) {
+  for (; p < parts; p += 16) {
     const float4 v0 = *reinterpret_cast<const float4*>(src + (size_t)p * 2 * w);
     const float4 v1 = *reinterpret_cast<const float4*>(src + (size_t)p * 2 * w + w);
     s0.x += v0.x; s0.y += v0.y; s0.z += v0.z; s0.w += v0.w;
@@ -737,45 +832,117 @@ __device__ __forceinline__ void reduce_ln_strip(const RedLnFinal& pr, int strip,
     float t = 0.f;
 #pragma unroll
     for (int j = 0; j < 16; j++) t += red[half * 16 * 65 + j * 65 + c];
-    float* out = half ? pr.out1 : pr.out0;
+    float* out = half ? out1 : out0;
     out[strip * 64 + c] += t;
   }
   __syncthreads();
 }
 
-__device__ __forceinline__ void reduce_role(const ReduceGroup& rg, int rb, int nrb, char* smem) {
+// The kernel's by-value arguments, read in place: indexing a copy of them with a run-time index (problem, segment)
+// would put the copy into scratch memory; through the kernel-argument segment they are scalar loads.
+typedef const __attribute__((address_space(4))) TnGroup* tn_group_args;
+typedef const __attribute__((address_space(4))) ReduceGroup* reduce_group_args;
+
+__device__ __forceinline__ void reduce_role(reduce_group_args rg, int rb, int nrb, char* smem) {
   float* red = reinterpret_cast<float*>(smem);                        // 32 x 65 floats
-  for (int item = rb; item < rg.total_items; item += nrb) {
-    bool done = false;                              // items are numbered LayerNorm strips first, then column-sum strips
-#pragma unroll
-    for (int q = 3; q >= 0; q--) {
-      if (!done && q < rg.n_colsum && item >= rg.c[q].first_item) { reduce_colsum_strip(rg.c[q], item - rg.c[q].first_item, rg.rows, red); done = true; }
-    }
-#pragma unroll
-    for (int q = 1; q >= 0; q--) {
-      if (!done && q < rg.n_ln && item >= rg.ln[q].first_item) { reduce_ln_strip(rg.ln[q], item - rg.ln[q].first_item, red); done = true; }
+  const int total = rg->total_items, nseg = rg->nseg, rows = rg->rows, n_colsum = rg->n_colsum, n_ln = rg->n_ln;
+  for (int item = rb; item < total; item += nrb) {
+    // items are numbered LayerNorm strips first, then column-sum strips
+    int kind = 0, q = 0;                                              // 0: LayerNorm finishing pass q, 1: column sum q
+    for (int c = n_colsum - 1; c >= 0 && kind == 0; c--)
+      if (item >= rg->c[c].first_item) { kind = 1; q = c; }
+    if (kind == 0)
+      for (int c = n_ln - 1; c >= 0; c--)
+        if (item >= rg->ln[c].first_item) { q = c; break; }
+    // a strip's segments (micro-batches) are summed one after the other and added in that order: the bits of one
+    // launch per micro-batch
+    if (kind == 1) {
+      float* out = rg->c[q].out; const int width = rg->c[q].width, strip = item - rg->c[q].first_item;
+      for (int seg = 0; seg < nseg; seg++) reduce_colsum_strip(rg->c[q].dy[seg], out, width, strip, rows, red);
+    } else {
+      float* out0 = rg->ln[q].out0; float* out1 = rg->ln[q].out1;
+      const int parts = rg->ln[q].parts, width = rg->ln[q].width, strip = item - rg->ln[q].first_item;
+      for (int seg = 0; seg < nseg; seg++) reduce_ln_strip(rg->ln[q].partial[seg], out0, out1, parts, width, strip, red);
     }
   }
 }
 
+// TnLayout for a token axis made of several segments (micro-batches) with operands of their own: the ring runs on
+// across segment boundaries.  Two cursors, one per operand, name the chunk the next load instructions fetch
+// (segment, chunk inside it); a cursor steps once per chunk, after the chunk's last instruction, and takes the next
+// segment's base pointer from the kernel arguments when it crosses a boundary.  Past the end it stays on the last
+// chunk (those loads land in slots nobody reads any more).
 template <int BM, int BN>
-__global__ void __launch_bounds__(256) gemm_h16_tn_grouped_kernel(TnGroup grp, ReduceGroup rg, int reduce_blocks) {
+struct TnLayoutSeg : TnLayout<BM, BN> {
+  using Base = TnLayout<BM, BN>;
+  using Base::TM; using Base::TN;
+  tn_group_args grp; int prob, nseg, nks, M_, N_, K_;
+  int seg_a, ka, seg_b, kb;
+  __device__ __forceinline__ void init_seg(char* smem, tn_group_args g_, int prob_, int M, int N, int K, int nseg_, int m0, int n0, int lane, int wave_) {
+    grp = g_; prob = prob_; nseg = nseg_; nks = K / CK_; M_ = M; N_ = N; K_ = K;
+    Base::init(smem, grp->p[prob].A[0], grp->p[prob].B[0], M, N, K, m0, n0, lane, wave_);
+    seg_a = ka = seg_b = kb = 0;
+  }
+  __device__ __forceinline__ void step_a() {
+    if (ka + 1 < nks) { ka++; return; }
+    if (seg_a + 1 < nseg) { seg_a++; ka = 0; this->ra = make_rsrc(grp->p[prob].A[seg_a], (size_t)K_ * M_ * 2); }
+  }
+  __device__ __forceinline__ void step_b() {
+    if (kb + 1 < nks) { kb++; return; }
+    if (seg_b + 1 < nseg) { seg_b++; kb = 0; this->rb = make_rsrc(grp->p[prob].B[seg_b], (size_t)K_ * N_ * 2); }
+  }
+  __device__ __forceinline__ void dma_a(int i, int slot) { dma16b(this->ra, this->voa[i], ka * this->sa, this->lds0 + (slot * Base::A_SLOT + (i * 4 + this->wave) * 512) * 2); }
+  __device__ __forceinline__ void dma_b(int i, int slot) { dma16b(this->rb, this->vob[i], kb * this->sb, this->lds0 + (RING * Base::A_SLOT + slot * Base::B_SLOT + (i * 4 + this->wave) * 512) * 2); }
+  __device__ __forceinline__ void prologue() {
+#pragma unroll
+    for (int c = 0; c < RING; c++) {
+#pragma unroll
+      for (int i = 0; i < TN; i++) dma_a(i, c);
+      step_a();
+      if (c < RING - 1) {
+#pragma unroll
+        for (int i = 0; i < TN; i++) dma_b(i, c);
+        step_b();
+      }
+    }
+  }
+  __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, (pc + 3) & 3); if (j == TN - 1) step_b(); }
+  __device__ __forceinline__ void dma1(int j, int kc, int pc) { dma_a(j, pc); if (j == TN - 1) step_a(); }
+};
+
+template <int BM, int BN>
+__global__ void __launch_bounds__(256) gemm_h16_tn_grouped_kernel(TnGroup grp_arg, ReduceGroup rg_arg, int reduce_blocks) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
+  static_assert(sizeof(TnGroup) % 8 == 0 && alignof(ReduceGroup) == 8, "the second argument follows the first without padding");
+  const __attribute__((address_space(4))) char* kargs = (const __attribute__((address_space(4))) char*)__builtin_amdgcn_kernarg_segment_ptr();
+  tn_group_args grp = (tn_group_args)kargs;
+  reduce_group_args rg = (reduce_group_args)(kargs + sizeof(TnGroup));
   // The first blocks of the grid (a multiple of 8, so the tiles keep their XCDs) reduce: they are on their CUs from
   // the start and finish in the shadow of the tiles, also when the tiles need several rounds.
   if ((int)blockIdx.x < reduce_blocks) {
     reduce_role(rg, blockIdx.x, reduce_blocks, smem);
     return;
   }
-  const int t = linear_of_block(grp.total_tiles, blockIdx.x - reduce_blocks);
-  if (t >= grp.total_tiles) return;
+  const int total_tiles = grp->total_tiles, count = grp->count, K = grp->K, nseg = grp->nseg;
+  const int t = linear_of_block(total_tiles, blockIdx.x - reduce_blocks);
+  if (t >= total_tiles) return;
   int i = 0;
-#pragma unroll
-  for (int q = 1; q < 4; q++) if (q < grp.count && t >= grp.p[q].first_tile) i = q;
-  const TnProblem pr = grp.p[i];
+  for (int q = 1; q < count; q++) if (t >= grp->p[q].first_tile) i = q;
+  const int M = grp->p[i].M, N = grp->p[i].N;
+  float* Cacc = grp->p[i].Cacc;
   int tm, tn;
-  tile_from_linear(t - pr.first_tile, pr.tiles_m, pr.tiles_n, tm, tn);
-  tn_tile<BM, BN, KFKB_EPI_ACCUM>(pr.M, pr.N, grp.K, pr.A, pr.B, nullptr, pr.Cacc, tm, tn, smem);
+  tile_from_linear(t - grp->p[i].first_tile, grp->p[i].tiles_m, grp->p[i].tiles_n, tm, tn);
+  constexpr int TM = BM / 64, TN = BN / 64;
+  const int m0 = tm * BM, n0 = tn * BN;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  f32x16 acc[TM][TN];
+  load_accum_dma<BM, BN>(acc, smem, Cacc, N, m0, n0, lane, wave);
+  TnLayoutSeg<BM, BN> lay;
+  lay.init_seg(smem, grp, i, M, N, K, nseg, m0, n0, lane, wave);
+  main_loop<TM, TN>(lay, acc, nseg * (K / CK_));                  // one token axis, segment after segment
+  store_accum_staged<BM, BN>(acc, smem, Cacc, N, m0, n0, lane, wave);
+  (void)grp_arg; (void)rg_arg;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1006,20 +1173,24 @@ static hipError_t launch_group(const TnGroup& grp, const ReduceGroup& rg, double
 // fewest 256 x 256 tiles a launch must have before they are preferred over 128 x 128 tiles
 static long big_tile_min() { return g_big_tile_min; }
 
-hipError_t launch_gemm_h16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
-  if (red_done) *red_done = false;
-  if (n <= 0) return hipSuccess;
-  bool groupable = n <= 4;
-  for (int i = 0; i < n; i++)
-    groupable = groupable && g[i].kind == KFKB_GEMM_TN && g[i].epilogue == KFKB_EPI_ACCUM && g[i].K == g[0].K &&
-                g[i].K % CK_ == 0 && g[i].M % 128 == 0 && g[i].N % 128 == 0 && gemm_h16_check(g[i]) == nullptr;
-  if (!groupable) {
-    for (int i = 0; i < n; i++) {
-      hipError_t e = launch_gemm_h16(g[i], s);
-      if (e != hipSuccess) return e;
-    }
-    return hipSuccess;
+// Can these weight gradients (and, if given, the reductions of the same W step) go into one grouped launch?
+bool wstep_groupable_h16(const WGrad* g, int n, int K, const WStepReduce* red) {
+  if (n <= 0 || n > 4 || K <= 0 || K % CK_ != 0) return false;
+  for (int i = 0; i < n; i++) {
+    if (g[i].M <= 0 || g[i].N <= 0 || g[i].M % 128 != 0 || g[i].N % 128 != 0) return false;
+    // the kernels address their operands with 32-bit byte offsets
+    if ((double)g[i].M * K * 2 >= 4294967296.0 || (double)g[i].N * K * 2 >= 4294967296.0) return false;
   }
+  if (red != nullptr) {
+    if (red->rows != K || red->n_colsum > 4 || red->n_ln > 2) return false;
+    for (int i = 0; i < red->n_colsum; i++) if (red->width[i] <= 0 || red->width[i] % 64 != 0) return false;
+    for (int i = 0; i < red->n_ln; i++) if (red->ln_width[i] <= 0 || red->ln_width[i] % 64 != 0 || red->ln_parts[i] <= 0) return false;
+  }
+  return true;
+}
+
+hipError_t launch_wstep_h16(const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red) {
+  if (nseg < 1 || nseg > kWSeg || !wstep_groupable_h16(g, n, K, red)) return hipErrorInvalidValue;
   // 256 x 256 tiles when every problem divides into them and the group still gives most CUs a tile
   long big_tiles = 0;
   bool big = true;
@@ -1030,32 +1201,29 @@ hipError_t launch_gemm_h16_tn_group(const GemmArgs* g, int n, hipStream_t s, con
   big = big && big_tiles >= big_tile_min();
   const int BT = big ? 256 : 128;
   TnGroup grp{};
-  grp.count = n; grp.K = g[0].K;
+  grp.count = n; grp.K = K; grp.nseg = nseg;
   double flops = 0;
   for (int i = 0; i < n; i++) {
     TnProblem& p = grp.p[i];
     p.M = g[i].M; p.N = g[i].N; p.tiles_m = g[i].M / BT; p.tiles_n = g[i].N / BT; p.first_tile = grp.total_tiles;
-    p.A = (const h16_t*)g[i].A; p.B = (const h16_t*)g[i].B; p.Cacc = g[i].Cacc;
+    p.Cacc = g[i].Cacc;
+    for (int sg = 0; sg < nseg; sg++) { p.A[sg] = (const h16_t*)g[i].A[sg]; p.B[sg] = (const h16_t*)g[i].B[sg]; }
     grp.total_tiles += p.tiles_m * p.tiles_n;
-    flops += 2.0 * g[i].M * g[i].N * g[i].K;
+    flops += 2.0 * g[i].M * g[i].N * K * nseg;
   }
-  // the reductions ride along when they divide into strips of 64 columns
+  // the reductions ride along (strips of 64 columns)
   ReduceGroup rg{};
-  if (red != nullptr && red->rows > 0 && red->n_colsum <= 4 && red->n_ln <= 2) {
-    bool ok = true;
-    for (int i = 0; i < red->n_colsum; i++) ok = ok && red->width[i] > 0 && red->width[i] % 64 == 0;
-    for (int i = 0; i < red->n_ln; i++) ok = ok && red->ln_width[i] > 0 && red->ln_width[i] % 64 == 0 && red->ln_parts[i] > 0;
-    if (ok) {
-      rg.n_colsum = red->n_colsum; rg.n_ln = red->n_ln; rg.rows = red->rows;
-      for (int i = 0; i < red->n_ln; i++) {
-        rg.ln[i] = RedLnFinal{red->ln_partial[i], red->ln_out0[i], red->ln_out1[i], red->ln_parts[i], red->ln_width[i], rg.total_items};
-        rg.total_items += red->ln_width[i] / 64;
-      }
-      for (int i = 0; i < red->n_colsum; i++) {
-        rg.c[i] = RedColsum{(const h16_t*)red->dy[i], red->out[i], red->width[i], rg.total_items};
-        rg.total_items += red->width[i] / 64;
-      }
-      if (red_done) *red_done = true;
+  if (red != nullptr) {
+    rg.n_colsum = red->n_colsum; rg.n_ln = red->n_ln; rg.rows = red->rows; rg.nseg = nseg;
+    for (int i = 0; i < red->n_ln; i++) {
+      rg.ln[i] = RedLnFinal{{}, red->ln_out0[i], red->ln_out1[i], red->ln_parts[i], red->ln_width[i], rg.total_items};
+      for (int sg = 0; sg < nseg; sg++) rg.ln[i].partial[sg] = red->ln_partial[i][sg];
+      rg.total_items += red->ln_width[i] / 64;
+    }
+    for (int i = 0; i < red->n_colsum; i++) {
+      rg.c[i] = RedColsum{{}, red->out[i], red->width[i], rg.total_items};
+      for (int sg = 0; sg < nseg; sg++) rg.c[i].dy[sg] = (const h16_t*)red->dy[i][sg];
+      rg.total_items += red->width[i] / 64;
     }
   }
   if (big) return launch_group<256, 256>(grp, rg, flops, s);
@@ -1097,15 +1265,16 @@ hipError_t launch_gemm_h16(const GemmArgs& g, hipStream_t s) {
 #ifdef KFKB_H16_IS_F16
 }  // namespace f16k
 hipError_t launch_gemm_f16(const GemmArgs& g, hipStream_t s) { return f16k::launch_gemm_h16(g, s); }
-hipError_t launch_gemm_f16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
-  return f16k::launch_gemm_h16_tn_group(g, n, s, red, red_done);
+hipError_t launch_wstep_f16(const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red) {
+  return f16k::launch_wstep_h16(g, n, K, nseg, s, red);
 }
 #else
 }  // namespace bf16k
 hipError_t launch_gemm_bf16(const GemmArgs& g, hipStream_t s) { return bf16k::launch_gemm_h16(g, s); }
-hipError_t launch_gemm_bf16_tn_group(const GemmArgs* g, int n, hipStream_t s, const WStepReduce* red, bool* red_done) {
-  return bf16k::launch_gemm_h16_tn_group(g, n, s, red, red_done);
+hipError_t launch_wstep_bf16(const WGrad* g, int n, int K, int nseg, hipStream_t s, const WStepReduce* red) {
+  return bf16k::launch_wstep_h16(g, n, K, nseg, s, red);
 }
+bool wstep_groupable(const WGrad* g, int n, int K, const WStepReduce* red) { return bf16k::wstep_groupable_h16(g, n, K, red); }
 const char* gemm_bf16_check(const GemmArgs& g) { return bf16k::gemm_h16_check(g); }
 #endif
 

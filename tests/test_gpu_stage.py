@@ -309,3 +309,32 @@ def test_a_transfer_that_does_not_arrive_in_time_gives_a_timeout_not_a_hang():
         assert torch.equal(a, b_)
     kf.stage_set_delays(None, None, None, None)
     st.close()
+
+
+@pytest.mark.parametrize("S,s", [(1, 0), (2, 0)])
+def test_w_step_windows_keep_every_bit(S, s):
+    """The gradient accumulation of a block is done once per window of up to 8 backwards of a schedule unit (16-bit
+    stages).  Whatever the window (off, 2, 3, 8), the group size (also above 8 and not dividing the number of
+    micro-batches: windows of 8 + a rest, a last short unit), the number of lanes and the warm-up depth, every
+    gradient, output and input gradient keeps its bits, and the result matches the oracle."""
+    dt, L, H, heads, T, b, M = kf.BF16, 2, 128, 2, 64, 2, 19
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=M, S=S, s=s)
+    ref = None
+    for lanes in (1, 2):
+        kf.stage_set_compute_lanes(lanes)
+        for window in (1, 2, 3, 8):
+            assert kf.stage_set_wstep_window(window) in (1, 2, 3, 8)
+            for k in (1, 2, 5, 9, 19):
+                G, Y, dX, order = _run(st, k, M)
+                w = min(S - 1 - s, (M + k - 1) // k)
+                assert order == sch.kfkb_order(k, M, w)
+                got = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+                if ref is None:
+                    ref = got
+                    _check_against_oracle(dt, st, blocks, xs, dys, heads, 1, G, Y, dX, order, k, w=w)
+                for a, b_ in zip(ref, got):
+                    assert torch.equal(a, b_), (lanes, window, k)
+    with pytest.raises(kf.KfkbError) as e:
+        kf.stage_set_wstep_window(0)
+    assert e.value.code == -1
+    st.close()
