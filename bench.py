@@ -177,9 +177,12 @@ def kernel_pass(run, k, steps, args):
             tj = json.load(f)
         hit = tj["kernels"].get(dom["name"])
         if hit:
-            roofline["traffic"] = hit["read_bytes"] + hit["write_bytes"]
+            # per launch of THIS run: a W-step launch covers as many micro-batches as the group size allows, so the
+            # measured bytes are scaled by the algorithmic work of a launch here over that of a launch in the counter run
+            scale = dom["work_per_launch"] / hit["work_per_launch"] if hit.get("work_per_launch") else 1.0
+            roofline["traffic"] = (hit["read_bytes"] + hit["write_bytes"]) * scale
             roofline["traffic_source"] = ("profiles/stage_%s_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
-                                          "scaled by a 1 GiB copy)" % tag)
+                                          "scaled by a 1 GiB copy; x %.2f for the work of a launch in this run)" % (tag, scale))
     except (OSError, ValueError, KeyError):
         pass
     gemm = [s for s in stats if s["name"].startswith("gemm_")]
