@@ -101,6 +101,8 @@ class Run:
             self.wgrad_stream = args.wgrad_stream
         kf.stage_set_compute_lanes(self.lanes)
         kf.stage_set_wgrad_stream(self.wgrad_stream)
+        if args.inputs_ahead >= 0:
+            kf.kfkb_set_inputs_ahead(args.inputs_ahead)
         if args.wstep_window > 0:
             kf.stage_set_wstep_window(args.wstep_window)
         self.delay_model = args.delay or w["delay"]
@@ -263,6 +265,7 @@ def main():
                     help="a second workload timed after the first, reported under \"secondary\" (default: gpt2-medium-stage "
                          "when the first is the default workload, else none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--inputs-ahead", type=int, default=-1, help="receive order (kfkb_set_inputs_ahead): 0 consumption order, 1 stage inputs one schedule unit ahead, 2 by k; -1 keeps the library default")
     ap.add_argument("--wstep-window", type=int, default=0,
                     help="most micro-batches whose gradient accumulation goes into one W step (stage_set_wstep_window); "
                          "1: every backward accumulates by itself; 0 (default): the library's default, 8")

@@ -106,8 +106,8 @@ int kfkb_enumerate_candidates(int global_batch, size_t mem_limit, size_t bytes_p
 
 /* Estimated iteration time of plan (k, M, w) on one stage whose neighbours do no compute: a discrete-event
  * run of the transfer rules (three FIFO resources compute / receive / send; send Y_mb after F(mb), send dX_mb
- * after B(mb), dY_mb arrives only after Y_mb has been sent, inputs are sent ahead as far as the slot pools
- * allow, a slot returns to its pool when the backward that read it ends).  Every op takes t_fwd / t_bwd and
+ * after B(mb), dY_mb arrives only after Y_mb has been sent, receives are issued in the order
+ * kfkb_set_inputs_ahead describes as far ahead as the slot pools allow, a slot returns to its pool when the backward that read it ends).  Every op takes t_fwd / t_bwd and
  * every transfer of a direction its t_*.  x_slots / dy_slots: pool sizes, 0 = peak live + k and 2k.
  * Returns a negative error code for an invalid plan. */
 double kfkb_predict_iteration_ms(int k, int num_microbatches, int warmup_groups, double t_fwd, double t_bwd,
@@ -237,6 +237,14 @@ int stage_set_fused_w_reductions(int enable);
  * the windows off; a stage with activation recomputation has none (the recomputed tensors would have to be kept for
  * the whole window).  Call while no micro-batch is live.  Returns the previous setting. */
 int stage_set_wstep_window(int max_microbatches);
+/* Order in which the receive stream is fed (paper Section 5.3: receives of one stream complete one after the other,
+ * so the order decides which transfer waits behind which; Section 4.4: inputs sent ahead wait in a queue).
+ * 0: the plan's consumption order: the upstream gradients of a schedule unit, then the inputs of the next forward
+ * unit.  1: every forward unit's inputs ahead of the upstream gradients of the backward unit before it.  2 (the
+ * default): 1 for k = 1, 0 for k >= 2.  Changes timing, never a result.  Process-wide, host-only, also read by
+ * kfkb_predict_iteration_ms and the tuner; takes effect at the next run_kFkB.  Returns the previous mode, or
+ * KFKB_E_ARG for a mode outside 0 .. 2. */
+int kfkb_set_inputs_ahead(int mode);
 /* Tile choice of the 16-bit matrix products: 256 x 256 tiles are used where the product divides into at least
  * `tiles` of them (default 192: three quarters of the 256 CUs get a tile), 128 x 128 tiles otherwise.  Process-wide,
  * host-only; returns the previous value.  A product's result does not depend on the tile shape beyond fp32

@@ -9,10 +9,15 @@ argument of Section 4.4, reduced to one device whose neighbours do no compute):
   * send Y_mb starts when F(mb) ends; send dX_mb starts when B(mb) ends;
   * "echo neighbour": the upstream gradient dY_mb can start arriving only after Y_mb has
     been fully sent;
-  * stage inputs X are sent ahead: the receive list is the schedule's consumption order
-    with every forward group's receives moved one schedule unit earlier, bounded by a
-    pool of input slots (live + k) and of gradient slots (2k); a slot returns to its
-    pool when the backward that read it ends;
+  * the receive stream is fed in a fixed list order, each receive issued as early as the
+    list and the pools allow: a pool of input slots (live + k) and of gradient slots (2k);
+    a slot returns to its pool when the backward that read it ends.  The list is the
+    schedule's consumption order (the upstream gradients of a unit, then the inputs of the
+    next forward unit, which so arrive while the unit's backwards run), or, "inputs
+    ahead", that order with every forward unit's receives moved one schedule unit earlier;
+    the default takes inputs ahead for k = 1 only (there a unit is one micro-batch and the
+    next input can only hide behind the current forward), since for k >= 2 a backward unit
+    would wait behind k input transfers;
   * an op starts when the previous op has ended and its input has arrived.
 Output buffers are modelled as unbounded.
 
@@ -24,8 +29,11 @@ from . import schedule
 F, B = schedule.F, schedule.B
 
 
-def receive_plan(order):
-    """Consumption order with each forward unit moved ahead of the backward unit before it."""
+def receive_plan(order, inputs_ahead=True):
+    """The receive list: the consumption order itself, or (inputs_ahead) that order with each forward unit moved
+    ahead of the backward unit before it."""
+    if not inputs_ahead:
+        return list(order)
     units = []
     for op, mb in order:
         if units and units[-1][0] == op:
@@ -43,9 +51,10 @@ def receive_plan(order):
 
 
 def simulate(order, k, t_fwd, t_bwd, delay_recv_x, delay_recv_dy, delay_send_y, delay_send_dx,
-             t_copy=0.0, x_slots=None, dy_slots=None):
+             t_copy=0.0, x_slots=None, dy_slots=None, inputs_ahead=None):
     """All times in one unit (say ms).  t_fwd / t_bwd: scalars or per-micro-batch lists.
     x_slots / dy_slots override the pool sizes (defaults: peak live + k, and 2k).
+    inputs_ahead: the receive list (see receive_plan); None = ahead exactly for k == 1.
     Returns dict(total=..., start=[...], end=[...], stall=...) with per-op compute times."""
     M = len(order) // 2
     tf = t_fwd if hasattr(t_fwd, "__len__") else [t_fwd] * M
@@ -53,7 +62,7 @@ def simulate(order, k, t_fwd, t_bwd, delay_recv_x, delay_recv_dy, delay_send_y, 
     live_peak = schedule.peak_live(order)
     x_free = [0.0] * (x_slots or live_peak + k)     # times at which input slots become free
     dy_free = [0.0] * (dy_slots or 2 * k)
-    plan = receive_plan(order)
+    plan = receive_plan(order, k == 1 if inputs_ahead is None else inputs_ahead)
     arrive, slot_of = {}, {}
     end_of, sent_y = {}, {}
     start, end = [], []

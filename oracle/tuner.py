@@ -47,11 +47,12 @@ class Window:
         return sum(self.samples) / len(self.samples) if self.samples else 0.0
 
 
-def predict(k, M, w, t_fwd, t_bwd, comm, x_slots=None, dy_slots=None):
-    """Estimated iteration time of plan (k, M, w).  comm: dict direction -> time of one transfer."""
+def predict(k, M, w, t_fwd, t_bwd, comm, x_slots=None, dy_slots=None, inputs_ahead=None):
+    """Estimated iteration time of plan (k, M, w).  comm: dict direction -> time of one transfer.
+    inputs_ahead: the receive list of transfer_sim.receive_plan; None = its default by k."""
     order = schedule.kfkb_order(k, M, w)
     c = [[comm[d]] * M for d in DIRECTIONS]
-    return transfer_sim.simulate(order, k, t_fwd, t_bwd, c[0], c[1], c[2], c[3], 0.0, x_slots, dy_slots)["total"]
+    return transfer_sim.simulate(order, k, t_fwd, t_bwd, c[0], c[1], c[2], c[3], 0.0, x_slots, dy_slots, inputs_ahead)["total"]
 
 
 def choose(candidates, M, w, compute_profile, comm, mem_limit=0, per_mb_bytes=0):

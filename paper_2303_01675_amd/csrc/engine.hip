@@ -152,9 +152,23 @@ int peak_live_of(const std::vector<kfkb_op_t>& order) {
   return peak;
 }
 
-// Receive list: the order's units with every forward unit moved ahead of the backward unit before it
-// (stage inputs are sent one schedule unit ahead by the upstream neighbour).
-void build_receive_plan(const std::vector<kfkb_op_t>& order, std::vector<kfkb_op_t>& plan) {
+// Receive list of a plan: the order the receive stream is fed in (it is FIFO, so this fixes which transfer waits
+// behind which).  Two orders:
+//   consumption order   the plan's own op order: the upstream gradients of a schedule unit come before the inputs of
+//                       the next forward unit, which then arrive while the unit's backwards run.  With k >= 2 this is
+//                       the better one under delay: a backward unit never waits behind k input transfers, and the
+//                       inputs are still early (measured: very wide stage, 15 ms per transfer, k = 8: 2.36 s against
+//                       2.96 s per iteration).
+//   inputs ahead        every forward unit moved ahead of the backward unit before it (the upstream neighbour sends
+//                       one schedule unit ahead).  With k = 1 a unit is one micro-batch, and the next input then
+//                       arrives while the current forward runs and its output travels, so that on two compute lanes
+//                       F(mb+1) can run beside B(mb).
+// mode: 0 consumption order, 1 inputs ahead, 2 (default) inputs ahead exactly for k = 1.
+int g_inputs_ahead_mode = 2;
+bool inputs_ahead_for(int k) { return g_inputs_ahead_mode == 2 ? k == 1 : g_inputs_ahead_mode != 0; }
+
+void build_receive_plan(const std::vector<kfkb_op_t>& order, int k, std::vector<kfkb_op_t>& plan) {
+  if (!inputs_ahead_for(k)) { plan = order; return; }
   std::vector<std::vector<kfkb_op_t>> units;
   for (const auto& o : order) {
     if (!units.empty() && units.back().back().op == o.op) units.back().push_back(o);
@@ -918,7 +932,7 @@ int pick_streams() {
 double predict_iteration(int k, int M, int w, double tf, double tb, const double (&tc)[4], int x_slots, int dy_slots) {
   std::vector<kfkb_op_t> order, plan;
   build_order(k, M, w, order);
-  build_receive_plan(order, plan);
+  build_receive_plan(order, k, plan);
   const int live = peak_live_of(order);
   constexpr double kBusy = -1.0;
   std::vector<double> pool[2];
@@ -1451,7 +1465,7 @@ int run_kFkB(int k, int num_microbatches, size_t mem_limit) {
   }
   std::vector<kfkb_op_t> order, plan;
   build_order(k, M, warmup_for(g, k, M), order);
-  build_receive_plan(order, plan);
+  build_receive_plan(order, k, plan);
   reset_iteration_state();
   g.last_k = k;
   TRY(begin_log_epoch());
@@ -1877,6 +1891,13 @@ int stage_set_wstep_window(int max_microbatches) {
   if (g.bound && live_count() != 0) return fail(KFKB_E_STATE, "stage_set_wstep_window while micro-batches are live");
   const int prev = g.wwin_max;
   g.wwin_max = std::min(max_microbatches, kWSeg);
+  return prev;
+}
+
+int kfkb_set_inputs_ahead(int mode) {
+  if (mode < 0 || mode > 2) return fail(KFKB_E_ARG, "kfkb_set_inputs_ahead: mode is 0, 1 or 2 (by k) (got %d)", mode);
+  const int prev = g_inputs_ahead_mode;
+  g_inputs_ahead_mode = mode;
   return prev;
 }
 

@@ -197,19 +197,24 @@ def test_delays_change_timing_not_results():
     d = np.full(M, int(delay_ms * 1e6), dtype=np.int64)
     kf.stage_set_delays(d, d, d, d)
     times = {}
-    for k in (1, 2, 4):
-        G, Y, dX, order = _run(st, k, M)
-        assert order == sch.kfkb_order(k, M, 0)
-        for a, b_ in zip(ref, (st.grads, st.h_out, st.h_ingrad)):
-            assert torch.equal(a, b_)
-        times[k] = kf.stage_last_run_ms()
-        log = kf.stage_get_order()
-        assert all(t1 >= t0 for _, _, t0, t1 in log)
-        assert all(log[i + 1][2] >= log[i][3] - 1e-3 for i in range(len(log) - 1))   # ops do not overlap
-        dl = [delay_ms] * M
-        pred = ts.simulate(sch.kfkb_order(k, M, 0), k, t_f, t_b, dl, dl, dl, dl, t_copy=0.02, x_slots=8, dy_slots=8)["total"]
-        if overlap:
-            assert abs(times[k] - pred) <= 0.15 * pred + 1.0, (k, times[k], pred)
+    # receive list: by k (the default), consumption order, inputs ahead: each changes timing only, and the measured
+    # time follows the model run with the same list
+    for mode, ahead in ((0, False), (1, True), (2, None)):
+        kf.kfkb_set_inputs_ahead(mode)
+        for k in (1, 2, 4):
+            G, Y, dX, order = _run(st, k, M)
+            assert order == sch.kfkb_order(k, M, 0)
+            for a, b_ in zip(ref, (st.grads, st.h_out, st.h_ingrad)):
+                assert torch.equal(a, b_)
+            times[k] = kf.stage_last_run_ms()
+            log = kf.stage_get_order()
+            assert all(t1 >= t0 for _, _, t0, t1 in log)
+            assert all(log[i + 1][2] >= log[i][3] - 1e-3 for i in range(len(log) - 1))   # ops do not overlap
+            dl = [delay_ms] * M
+            pred = ts.simulate(sch.kfkb_order(k, M, 0), k, t_f, t_b, dl, dl, dl, dl, t_copy=0.02, x_slots=8, dy_slots=8,
+                               inputs_ahead=ahead)["total"]
+            if overlap:
+                assert abs(times[k] - pred) <= 0.15 * pred + 1.0, (mode, k, times[k], pred)
     assert times[1] > base_ms + M * 2 * delay_ms * 0.9
     if overlap:
         assert times[4] < times[1] and times[2] < times[1]

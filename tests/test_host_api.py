@@ -64,3 +64,14 @@ def test_calls_before_init_fail_cleanly(lib):
             fn(*args)
         assert e.value.code == -2
     assert kf.stage_param_count() == 0 and kf.stage_workspace_bytes(1) == 0
+
+
+def test_receive_list_mode_is_checked_and_returned(lib):
+    assert kf.kfkb_set_inputs_ahead(0) == 2          # the default is "by k"
+    assert kf.kfkb_set_inputs_ahead(1) == 0
+    assert kf.kfkb_set_inputs_ahead(2) == 1
+    for bad in (-1, 3):
+        with pytest.raises(kf.KfkbError) as e:
+            kf.kfkb_set_inputs_ahead(bad)
+        assert e.value.code == -1
+    assert kf.kfkb_set_inputs_ahead(2) == 2

@@ -21,7 +21,10 @@ def lib():
 def test_estimate_matches_the_oracle_on_random_plans(lib):
     rnd = random.Random(7)
     n = 0
-    for _ in range(400):
+    for it in range(600):
+        mode = (2, 0, 1)[it % 3]                      # receive list: by k (the default), consumption order, inputs ahead
+        ahead = {2: None, 0: False, 1: True}[mode]
+        kf.kfkb_set_inputs_ahead(mode)
         M = rnd.randint(1, 24)
         k = rnd.randint(1, M)
         w = rnd.randint(0, 3)
@@ -34,7 +37,7 @@ def test_estimate_matches_the_oracle_on_random_plans(lib):
         else:
             xs, ds = 0, 0
         try:
-            want = tu.predict(k, M, w, tf, tb, comm, xs or None, ds or None)
+            want = tu.predict(k, M, w, tf, tb, comm, xs or None, ds or None, ahead)
         except RuntimeError:
             with pytest.raises(kf.KfkbError):
                 kf.kfkb_predict_iteration_ms(k, M, w, tf, tb, *[comm[d] for d in tu.DIRECTIONS], xs, ds)
@@ -42,7 +45,8 @@ def test_estimate_matches_the_oracle_on_random_plans(lib):
         got = kf.kfkb_predict_iteration_ms(k, M, w, tf, tb, *[comm[d] for d in tu.DIRECTIONS], xs, ds)
         assert got == pytest.approx(want, rel=1e-12, abs=1e-12), (k, M, w, comm, xs, ds)
         n += 1
-    assert n > 300
+    kf.kfkb_set_inputs_ahead(2)
+    assert n > 450
 
 
 def test_estimate_closed_forms(lib):

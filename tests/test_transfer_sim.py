@@ -55,7 +55,40 @@ def test_receive_plan_is_a_permutation_feeding_the_order():
         for k in (1, 2, 4):
             for w in (0, 1, 2):
                 order = sch.kfkb_order(k, M, w)
-                plan = ts.receive_plan(order)
-                assert sorted(plan) == sorted(order)
                 d = [0.1] * M
-                ts.simulate(order, k, 1.0, 2.0, d, d, d, d)      # never starves
+                for ahead in (False, True, None):
+                    if ahead is not None:
+                        plan = ts.receive_plan(order, ahead)
+                        assert sorted(plan) == sorted(order)
+                        if not ahead:
+                            assert plan == list(order)
+                    ts.simulate(order, k, 1.0, 2.0, d, d, d, d, inputs_ahead=ahead)      # never starves
+
+
+def test_consumption_order_keeps_a_backward_unit_from_waiting_behind_the_next_inputs():
+    """Receives of one stream complete one after the other (Section 5.3).  With inputs ahead the k input transfers of
+    the next forward unit sit in front of the first upstream gradient of the current backward unit; in consumption
+    order they follow it and arrive while the backwards run.  Worked case: k = 2, M = 4, every transfer 3, F = 1, B = 2.
+    Consumption order: X0 3, X1 6 | F0 3-4, F1 6-7 | Y0 sent 7, Y1 sent 10 | dY0 10, dY1 13 | B0 10-12, B1 13-15 |
+    X2 16, X3 19 (behind dY1) | F2 16-17, F3 19-20 | Y2 sent 20 (the send stream carried dX0 until 15, dX1 until 18;
+    Y2 goes 18-21: F2 ended 17) ...  The exact totals are left to the simulator; what the rule fixes is the ORDER of
+    arrivals, checked here, and that the first backward starts earlier than with inputs ahead."""
+    M, k, d = 4, 2, [3.0] * 4
+    order = sch.kfkb_order(k, M, 0)
+    cons = ts.simulate(order, k, 1.0, 2.0, d, d, d, d, inputs_ahead=False)
+    ahead = ts.simulate(order, k, 1.0, 2.0, d, d, d, d, inputs_ahead=True)
+    i_b0 = order.index((sch.B, 0))
+    # consumption order: dY0 is the third receive: it starts when Y0 has been sent (F0 3-4, sent at 7) -> arrives 10
+    assert cons["start"][i_b0] == pytest.approx(10.0)
+    # inputs ahead: X2 and X3 (3 each, from 6 on) come first: dY0 is received 12-15
+    assert ahead["start"][i_b0] == pytest.approx(15.0)
+    assert cons["total"] < ahead["total"]
+
+
+def test_default_receive_list_is_inputs_ahead_for_1f1b_only():
+    d = [0.7] * 8
+    for k, ahead in ((1, True), (2, False), (4, False)):
+        order = sch.kfkb_order(k, 8, 0)
+        a = ts.simulate(order, k, 1.0, 2.0, d, d, d, d)
+        b = ts.simulate(order, k, 1.0, 2.0, d, d, d, d, inputs_ahead=ahead)
+        assert a["start"] == b["start"] and a["total"] == b["total"]
