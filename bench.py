@@ -52,6 +52,14 @@ def stage_flops(L, b, T, H, causal=True, megatron=False):
     return 3.0 * L * (b * T) * (24.0 * H * H + 4.0 * T * H * c)
 
 
+_T0 = time.time()
+
+
+def progress(msg):
+    """Phase lines on stderr (the result is the one JSON line on stdout): a run of minutes is not silent."""
+    print("[bench %6.1f s] %s" % (time.time() - _T0, msg), file=sys.stderr, flush=True)
+
+
 def delays_for(synth, model, M, step_index, n_steps, seed0=4242):
     """Delays of one iteration, the same for every k: drawn per (iteration, direction, micro-batch)."""
     if model == "none":
@@ -103,6 +111,8 @@ class Run:
         kf.stage_set_wgrad_stream(self.wgrad_stream)
         if args.inputs_ahead >= 0:
             kf.kfkb_set_inputs_ahead(args.inputs_ahead)
+        if args.send_copy_blocks >= 0:
+            kf.stage_set_send_copy_blocks(args.send_copy_blocks)
         if args.wstep_window > 0:
             kf.stage_set_wstep_window(args.wstep_window)
         self.delay_model = args.delay or w["delay"]
@@ -266,6 +276,7 @@ def main():
                          "when the first is the default workload, else none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--inputs-ahead", type=int, default=-1, help="receive order (kfkb_set_inputs_ahead): 0 consumption order, 1 stage inputs one schedule unit ahead, 2 by k; -1 keeps the library default")
+    ap.add_argument("--send-copy-blocks", type=int, default=-1, help="sends: 0 the runtime's device-to-host copy, n > 0 the library's copy kernel with n workgroups (stage_set_send_copy_blocks); -1 keeps the library default")
     ap.add_argument("--wstep-window", type=int, default=0,
                     help="most micro-batches whose gradient accumulation goes into one W step (stage_set_wstep_window); "
                          "1: every backward accumulates by itself; 0 (default): the library's default, 8")
@@ -324,14 +335,17 @@ def main():
 
     def measure(name, steps, warmup, with_extras):
         w = workload(name)
+        progress("%s: setting up weights, inputs and the stage" % name)
         run = Run(name, w, args, kf, synth, np)
         scan_steps = args.scan_steps or max(3, steps // 5)
         per_k = {}
         for k_req in w["ks"]:
             k, row = run.timed(k_req, 1, scan_steps, torch)
             per_k[k] = row
+            progress("%s: scan k = %d: %.1f ms per iteration (%d steps, delay %s)" % (name, k, row["ms_per_step"], scan_steps, run.delay_model))
         best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
         _, head = run.timed(best_k, warmup, steps, torch)
+        progress("%s: k = %d, %d warm-up + %d timed steps: %.1f ms per iteration" % (name, best_k, warmup, steps, head["ms_per_step"]))
         k1 = per_k.get(1)
         res = dict(run=run, w=w, per_k=per_k, best_k=best_k, head=head,
                    best_k_over_k1=(head["samples_per_s"] / k1["samples_per_s"]) if k1 else None)
@@ -391,6 +405,7 @@ def main():
         kf.kfkb_tuner_config(2, 2, cands)
         kf.stage_set_delays(None, None, None, None)
         kf.stage_tuner_calibrate(M, 2)
+        progress("tuner calibrated (every candidate k run twice without delay)")
         chosen = []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
@@ -402,11 +417,15 @@ def main():
         dt_s = time.perf_counter() - t0
         adaptive = dict(ms_per_step=1e3 * dt_s / args.steps, samples_per_s=M * b * args.steps / dt_s, k_per_step=chosen,
                         window=2, interval=2, candidates=cands)
+        progress("adaptive k: %.1f ms per iteration, k per step %s" % (adaptive["ms_per_step"], chosen))
 
     prof_steps = args.profile_steps or (2 if w.get("tiled") else args.steps)
     roofline, kernels = kernel_pass(run, best_k, prof_steps, args)
+    progress("per-kernel pass done (%d steps on one lane)" % prof_steps)
 
     cpu = None if args.no_cpu_baseline else cpu_baseline(run, np)
+    if cpu is not None:
+        progress("CPU baseline (the oracle) timed")
 
     out = {
         "metric": "stage fwd+bwd samples/sec (kFkB iteration, best k of 1,2,4,8 under the workload's transfer delays)",

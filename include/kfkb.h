@@ -245,6 +245,12 @@ int stage_set_wstep_window(int max_microbatches);
  * kfkb_predict_iteration_ms and the tuner; takes effect at the next run_kFkB.  Returns the previous mode, or
  * KFKB_E_ARG for a mode outside 0 .. 2. */
 int kfkb_set_inputs_ahead(int mode);
+/* How an output (Y_mb, dX_mb) is copied to the caller's pinned host array once its injected delay has passed (the
+ * "send" of paper Section 5.3 on this one GPU): by a copy kernel of the library with `blocks` workgroups (1 .. 4096,
+ * default 8) that writes the array through its device view, or, with 0, by the runtime's device-to-host copy.  Arrays
+ * that have no device view (not pinned) always take the runtime's copy.  Changes timing, never a result.  Takes
+ * effect at the next send.  Returns the previous setting; KFKB_E_STATE before stage_init, KFKB_E_ARG outside the range. */
+int stage_set_send_copy_blocks(int blocks);
 /* Tile choice of the 16-bit matrix products: 256 x 256 tiles are used where the product divides into at least
  * `tiles` of them (default 192: three quarters of the 256 CUs get a tile), 128 x 128 tiles otherwise.  Process-wide,
  * host-only; returns the previous value.  A product's result does not depend on the tile shape beyond fp32

@@ -171,6 +171,7 @@ hipError_t launch_transpose(int dt, const void* in, void* out, int rows, int col
 // bf16 weight operand B[N][K] of an NT GEMM -> chunk-major [K/32][N][32]; transposed: src holds B^T as [K][N]
 hipError_t launch_tile_weights(const void* src, void* dst, int N, int K, bool transposed, hipStream_t s);
 hipError_t launch_delay(int64_t ns, hipStream_t s);
+hipError_t launch_send_copy(void* dst_device_view_of_host, const void* src, size_t bytes, int blocks, hipStream_t s);
 // one device clock reading into *stamp, and a wait until `ns` after that reading (at most `ns` from its own start,
 // whatever the stamp holds; at most two seconds)
 hipError_t launch_clock_stamp(long long* stamp, hipStream_t s);

@@ -541,6 +541,17 @@ __global__ void delay_kernel(long long ticks) {
   while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
 }
 
+// Device -> pinned host copy of a boundary tensor (the "send" of an output), 16 bytes per lane and step.  The
+// destination is written once and never read here: stores go past the caches.
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+__global__ void __launch_bounds__(256) send_copy_kernel(const u32x4_t* __restrict__ src, u32x4_t* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+    const u32x4_t v = __builtin_nontemporal_load(src + i);
+    __builtin_nontemporal_store(v, dst + i);
+  }
+}
+
 // The device wall clock, for a delay that counts from an event on another stream: the producer's stream stamps
 // the clock when it is done, the transfer's stream waits until `ticks` after that stamp.  The wait also ends
 // `ticks` after its own start, so it is bounded whatever the stamp holds.
@@ -731,6 +742,13 @@ hipError_t launch_delay(int64_t ns, hipStream_t s) {
   if (ns <= 0) return hipSuccess;
   if (ns > 2000000000LL) ns = 2000000000LL;                   // never spin longer than two seconds
   hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, s, (long long)(ns / 10));
+  return hipGetLastError();
+}
+
+hipError_t launch_send_copy(void* dst_device_view_of_host, const void* src, size_t bytes, int blocks, hipStream_t s) {
+  if (bytes == 0) return hipSuccess;
+  if ((bytes & 15) != 0 || (((uintptr_t)dst_device_view_of_host | (uintptr_t)src) & 15) != 0 || blocks < 1) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(send_copy_kernel, dim3(blocks), dim3(256), 0, s, (const u32x4_t*)src, (u32x4_t*)dst_device_view_of_host, bytes / 16);
   return hipGetLastError();
 }
 

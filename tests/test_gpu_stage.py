@@ -259,6 +259,33 @@ def test_lanes_and_w_step_placement_change_timing_not_results(dt):
         st.close()
 
 
+@pytest.mark.parametrize("dt", [kf.F32, kf.BF16])
+def test_send_copy_path_changes_no_bit(dt):
+    """Outputs reach the pinned host arrays through the library's copy kernel (any number of workgroups, also more
+    than there are 16-byte pieces to copy) or through the runtime's copy: the same bits, compared with the oracle
+    once; the setter checks its range."""
+    L, H, heads, T, b, M = (2, 128, 2, 64, 2, 4) if dt == kf.F32 else (2, 128, 2, 96, 3, 4)
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=2)
+    assert kf.stage_set_send_copy_blocks(8) == 8           # the default
+    ref = None
+    for blocks_n in (8, 0, 1, 3, 4096):
+        kf.stage_set_send_copy_blocks(blocks_n)
+        st.h_out.fill_(7.0); st.h_ingrad.fill_(7.0)        # stale values must be overwritten by every path
+        G, Y, dX, order = _run(st, 2, M)
+        got = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+        if ref is None:
+            ref = got
+            _check_against_oracle(dt, st, blocks, xs, dys, heads, 1, G, Y, dX, order, 2)
+        for a, b_ in zip(ref, got):
+            assert torch.equal(a, b_), blocks_n
+    for bad in (-1, 4097):
+        with pytest.raises(kf.KfkbError) as e:
+            kf.stage_set_send_copy_blocks(bad)
+        assert e.value.code == -1
+    assert kf.stage_set_send_copy_blocks(8) == 4096
+    st.close()
+
+
 @pytest.mark.parametrize("dt,L,H,heads,T,b,M", [(kf.F32, 2, 128, 4, 64, 2, 6), (kf.BF16, 3, 128, 2, 96, 3, 6)])
 def test_recomputation_keeps_every_bit_and_lets_a_larger_k_in(dt, L, H, heads, T, b, M):
     """Activation recomputation (paper Section 2.2): the LayerNorm and GELU outputs are formed again in the backward
