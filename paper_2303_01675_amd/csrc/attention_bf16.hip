@@ -75,6 +75,21 @@ struct TileIO {
       *reinterpret_cast<h16x8*>(tile + (row * CH + (c ^ sw(row))) * 8) = r[i];
     }
   }
+  // The same tile filled by loads that write LDS (no staging registers, no LDS stores).  One instruction of a wave
+  // fills 64 consecutive 16-byte places of the tile; place P holds chunk (P % CH) ^ sw(P / CH) of row P / CH, so the
+  // swizzle is applied on the global side.  A tile is NI instructions per wave: instruction i of wave w covers places
+  // (i * 4 + w) * 64 ... + 63.  voff(): this lane's byte offset from the first row of the tile; rows at or past the
+  // resource's end read as zero.
+  static constexpr int NI = (64 * CH) / 256;
+  static __device__ __forceinline__ int dma_voff(int i, int wave, int lane, size_t ld) {
+    const int place = (i * 4 + wave) * 64 + lane;
+    const int row = place / CH, c = (place % CH) ^ sw(row);
+    return (int)((size_t)row * ld * sizeof(h16_t)) + c * 16;
+  }
+  static __device__ __forceinline__ void dma_tile(const i32x4& rsrc, const int (&voff)[NI], int soff, unsigned lds_tile, int wave) {
+#pragma unroll
+    for (int i = 0; i < NI; i++) dma16b(rsrc, voff[i], soff, lds_tile + (unsigned)((i * 4 + wave) * 1024));
+  }
   // 8 reduction-contiguous values of row `row`, chunk `chunk`
   static __device__ __forceinline__ h16x8 frag(const h16_t* tile, int row, int chunk) {
     return *reinterpret_cast<const h16x8*>(tile + (row * CH + (chunk ^ sw(row))) * 8);
@@ -140,7 +155,7 @@ __device__ __forceinline__ void block_to_work(int& rb, int& bh, int pair) {
 // forward
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restrict__ qkv, h16_t* __restrict__ o,
+__global__ void __launch_bounds__(256, 2) attn_fwd_h16_kernel(const h16_t* __restrict__ qkv, h16_t* __restrict__ o,
                                                             float* __restrict__ lse, int T, int H, int heads,
                                                             int causal, float scale_log2, int pair) {
   using IO = TileIO<D>;
@@ -173,17 +188,28 @@ __global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restri
   for (int t = 0; t < D / 32; t++) oacc[t] = zero16();
   float mrun = -INFINITY, lsum = 0.f;
 
-  h16x8 rk[IO::NL], rv[IO::NL];
-  IO::load(rk, base, ld, 0, T - 1, H + hd * D);
-  IO::load(rv, base, ld, 0, T - 1, 2 * H + hd * D);
-  IO::store(Ks, rk);
-  IO::store(Vs, rv);
+  // K and V tiles arrive through loads that write LDS; rows past the end of the sequence read as zero (they are
+  // masked below, and a zero V row times a zero weight stays zero)
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const size_t row_bytes = ld * sizeof(h16_t);
+  const i32x4 rk = make_rsrc(base + H + hd * D, (size_t)(T - 1) * row_bytes + D * sizeof(h16_t));
+  const i32x4 rv = make_rsrc(base + 2 * H + hd * D, (size_t)(T - 1) * row_bytes + D * sizeof(h16_t));
+  int voff[IO::NI];
+#pragma unroll
+  for (int q = 0; q < IO::NI; q++) voff[q] = IO::dma_voff(q, wv, lane, ld);
+  const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+  const unsigned lds_v = lds_k + 2 * 64 * D * (unsigned)sizeof(h16_t);
+  constexpr unsigned TILE_B = 64 * D * sizeof(h16_t);
+  IO::dma_tile(rk, voff, 0, lds_k, wv);
+  IO::dma_tile(rv, voff, 0, lds_v, wv);
+  wait_vmcnt<0>();
   __syncthreads();
   for (int kb = 0; kb < nkv; kb++) {
     const int cur = kb & 1, j0 = kb * 64;
-    if (kb + 1 < nkv) {
-      IO::load(rk, base, ld, j0 + 64, T - 1, H + hd * D);
-      IO::load(rv, base, ld, j0 + 64, T - 1, 2 * H + hd * D);
+    if (kb + 1 < nkv) {                              // the other buffer was last read before the barrier that ended step kb - 1
+      const int soff = (int)((size_t)(j0 + 64) * row_bytes);
+      IO::dma_tile(rk, voff, soff, lds_k + (cur ^ 1) * TILE_B, wv);
+      IO::dma_tile(rv, voff, soff, lds_v + (cur ^ 1) * TILE_B, wv);
     }
     const h16_t* Kt = Ks + cur * 64 * D;
     const h16_t* Vt = Vs + cur * 64 * D;
@@ -248,10 +274,7 @@ __global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restri
       lsum = lsum * alpha + ps;
       mrun = mnew;
     }
-    if (kb + 1 < nkv) {
-      IO::store(Ks + (cur ^ 1) * 64 * D, rk);
-      IO::store(Vs + (cur ^ 1) * 64 * D, rv);
-    }
+    wait_vmcnt<0>();                                 // this wave's part of the next tiles has landed
     __syncthreads();
   }
   lsum += __shfl_xor(lsum, 32, 64);
@@ -275,7 +298,7 @@ __global__ void __launch_bounds__(256) attn_fwd_h16_kernel(const h16_t* __restri
 // backward, dQ: own rows = queries, streamed rows = keys
 // ------------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(256) attn_bwd_dq_h16_kernel(const h16_t* __restrict__ qkv, const h16_t* __restrict__ o,
+__global__ void __launch_bounds__(256, 2) attn_bwd_dq_h16_kernel(const h16_t* __restrict__ qkv, const h16_t* __restrict__ o,
                                                                const h16_t* __restrict__ d_o,
                                                                const float* __restrict__ lse, float* __restrict__ dsum,
                                                                h16_t* __restrict__ dqkv, int T, int H, int heads,
@@ -323,17 +346,27 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_h16_kernel(const h16_t* __res
 #pragma unroll
   for (int t = 0; t < D / 32; t++) dq[t] = zero16();
 
-  h16x8 rk[IO::NL], rv[IO::NL];
-  IO::load(rk, base, ld, 0, T - 1, H + hd * D);
-  IO::load(rv, base, ld, 0, T - 1, 2 * H + hd * D);
-  IO::store(Ks, rk);
-  IO::store(Vs, rv);
+  // K and V tiles arrive through loads that write LDS, as in the forward kernel
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const size_t row_bytes = ld * sizeof(h16_t);
+  const i32x4 rk = make_rsrc(base + H + hd * D, (size_t)(T - 1) * row_bytes + D * sizeof(h16_t));
+  const i32x4 rv = make_rsrc(base + 2 * H + hd * D, (size_t)(T - 1) * row_bytes + D * sizeof(h16_t));
+  int voff[IO::NI];
+#pragma unroll
+  for (int q = 0; q < IO::NI; q++) voff[q] = IO::dma_voff(q, wv, lane, ld);
+  const unsigned lds_k = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+  const unsigned lds_v = lds_k + 2 * 64 * D * (unsigned)sizeof(h16_t);
+  constexpr unsigned TILE_B = 64 * D * sizeof(h16_t);
+  IO::dma_tile(rk, voff, 0, lds_k, wv);
+  IO::dma_tile(rv, voff, 0, lds_v, wv);
+  wait_vmcnt<0>();
   __syncthreads();
   for (int kb = 0; kb < nkv; kb++) {
     const int cur = kb & 1, j0 = kb * 64;
     if (kb + 1 < nkv) {
-      IO::load(rk, base, ld, j0 + 64, T - 1, H + hd * D);
-      IO::load(rv, base, ld, j0 + 64, T - 1, 2 * H + hd * D);
+      const int soff = (int)((size_t)(j0 + 64) * row_bytes);
+      IO::dma_tile(rk, voff, soff, lds_k + (cur ^ 1) * TILE_B, wv);
+      IO::dma_tile(rv, voff, soff, lds_v + (cur ^ 1) * TILE_B, wv);
     }
     const h16_t* Kt = Ks + cur * 64 * D;
     const h16_t* Vt = Vs + cur * 64 * D;
@@ -389,10 +422,7 @@ __global__ void __launch_bounds__(256) attn_bwd_dq_h16_kernel(const h16_t* __res
           __builtin_amdgcn_sched_barrier(0);
         }
     }
-    if (kb + 1 < nkv) {
-      IO::store(Ks + (cur ^ 1) * 64 * D, rk);
-      IO::store(Vs + (cur ^ 1) * 64 * D, rv);
-    }
+    wait_vmcnt<0>();
     __syncthreads();
   }
   if (i < T) {
@@ -453,7 +483,17 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_h16_kernel(const h16_t* __re
 
   const int nq = (T + 63) / 64;
   const int ib0 = causal ? j0 / 64 : 0;
-  h16x8 rq[IO::NL], ro[IO::NL];
+  // Q and dO tiles arrive through loads that write LDS (rows past the end of the sequence read as zero and are
+  // masked below); the 2 x 64 row statistics of a tile go through a register
+  const int wv = __builtin_amdgcn_readfirstlane(wave);
+  const i32x4 rq = make_rsrc(base + hd * D, (size_t)(T - 1) * ld * sizeof(h16_t) + D * sizeof(h16_t));
+  const i32x4 ro = make_rsrc(dobase + hd * D, (size_t)(T - 1) * H * sizeof(h16_t) + D * sizeof(h16_t));
+  int voffq[IO::NI], voffo[IO::NI];
+#pragma unroll
+  for (int q = 0; q < IO::NI; q++) { voffq[q] = IO::dma_voff(q, wv, lane, ld); voffo[q] = IO::dma_voff(q, wv, lane, (size_t)H); }
+  const unsigned lds_q = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+  const unsigned lds_o = lds_q + 2 * 64 * D * (unsigned)sizeof(h16_t);
+  constexpr unsigned TILE_B = 64 * D * sizeof(h16_t);
   float rstat = 0.f;
   auto load_stats = [&](int i0) {
     if (threadIdx.x < 64) rstat = lbase[min(i0 + (int)threadIdx.x, T - 1)] * kLog2e;
@@ -464,45 +504,50 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_h16_kernel(const h16_t* __re
     else if (threadIdx.x < 128) Ss[st * 64 + threadIdx.x - 64] = rstat;
   };
   if (ib0 < nq) {
-    IO::load(rq, base, ld, ib0 * 64, T - 1, hd * D);
-    IO::load(ro, dobase, (size_t)H, ib0 * 64, T - 1, hd * D);
+    IO::dma_tile(rq, voffq, (int)((size_t)ib0 * 64 * ld * sizeof(h16_t)), lds_q, wv);
+    IO::dma_tile(ro, voffo, (int)((size_t)ib0 * 64 * H * sizeof(h16_t)), lds_o, wv);
     load_stats(ib0 * 64);
-    IO::store(Qs, rq);
-    IO::store(Os, ro);
     store_stats(0);
   }
+  wait_vmcnt<0>();
   __syncthreads();
   for (int ib = ib0; ib < nq; ib++) {
     const int cur = (ib - ib0) & 1, i0 = ib * 64;
     if (ib + 1 < nq) {
-      IO::load(rq, base, ld, i0 + 64, T - 1, hd * D);
-      IO::load(ro, dobase, (size_t)H, i0 + 64, T - 1, hd * D);
+      IO::dma_tile(rq, voffq, (int)((size_t)(i0 + 64) * ld * sizeof(h16_t)), lds_q + (cur ^ 1) * TILE_B, wv);
+      IO::dma_tile(ro, voffo, (int)((size_t)(i0 + 64) * H * sizeof(h16_t)), lds_o + (cur ^ 1) * TILE_B, wv);
       load_stats(i0 + 64);
     }
     const h16_t* Qt = Qs + cur * 64 * D;
     const h16_t* Ot = Os + cur * 64 * D;
     if (!(causal && i0 + 63 < jw0)) {               // wave-uniform: some query of the tile sees these keys
       f32x16 st[2] = {zero16(), zero16()}, dp[2] = {zero16(), zero16()};
-      // fragments are requested eight at a time, ahead of the MFMAs that use them: one LDS latency per eight
-      // MFMAs instead of one per MFMA
+      // Fragments are requested eight at a time, one group AHEAD of the MFMAs that use them (this kernel runs one
+      // wave per SIMD, so nothing else hides the LDS latency): group g covers query half g / GD and head-dimension
+      // chunks (g % GD) * 4 .. + 3.
+      constexpr int GD = D / 64, NG1 = 2 * GD;
+      h16x8 qa[2][4], oa[2][4];
+      auto load1 = [&](int g, h16x8 (&q4)[4], h16x8 (&o4)[4]) {
+        const int it = g / GD, d0 = (g % GD) * 4;
 #pragma unroll
-      for (int it = 0; it < 2; it++)
-#pragma unroll
-        for (int d0 = 0; d0 < D / 16; d0 += 4) {
-          h16x8 qa[4], oa[4];
-#pragma unroll
-          for (int ds = 0; ds < 4; ds++) {
-            qa[ds] = IO::frag(Qt, it * 32 + l32, (d0 + ds) * 2 + hh);
-            oa[ds] = IO::frag(Ot, it * 32 + l32, (d0 + ds) * 2 + hh);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int ds = 0; ds < 4; ds++) {
-            st[it] = KFKB_MFMA_H16(qa[ds], kf[d0 + ds], st[it]);
-            dp[it] = KFKB_MFMA_H16(oa[ds], vf[d0 + ds], dp[it]);
-          }
-          __builtin_amdgcn_sched_barrier(0);
+        for (int ds = 0; ds < 4; ds++) {
+          q4[ds] = IO::frag(Qt, it * 32 + l32, (d0 + ds) * 2 + hh);
+          o4[ds] = IO::frag(Ot, it * 32 + l32, (d0 + ds) * 2 + hh);
         }
+      };
+      load1(0, qa[0], oa[0]);
+#pragma unroll
+      for (int g = 0; g < NG1; g++) {
+        if (g + 1 < NG1) load1(g + 1, qa[(g + 1) & 1], oa[(g + 1) & 1]);
+        __builtin_amdgcn_sched_barrier(0);
+        const int it = g / GD, d0 = (g % GD) * 4;
+#pragma unroll
+        for (int ds = 0; ds < 4; ds++) {
+          st[it] = KFKB_MFMA_H16(qa[g & 1][ds], kf[d0 + ds], st[it]);
+          dp[it] = KFKB_MFMA_H16(oa[g & 1][ds], vf[d0 + ds], dp[it]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (i0 + 63 >= T || jw0 + 31 >= T || (causal && jw0 + 31 > i0)) {
 #pragma unroll
         for (int it = 0; it < 2; it++)
@@ -527,32 +572,34 @@ __global__ void __launch_bounds__(256) attn_bwd_dkv_h16_kernel(const h16_t* __re
             dp[it][q * 4 + e] = p * (dp[it][q * 4 + e] - sv[e]);
           }
         }
+      // second half: groups of sixteen streamed rows, their transposed fragments again one group ahead
+      h16x8 ot[2][D / 32], qt[2][D / 32];
+      auto load3 = [&](int g, h16x8 (&o4)[D / 32], h16x8 (&q4)[D / 32]) {
+        const int it = g >> 1, t16 = g & 1;
 #pragma unroll
-      for (int it = 0; it < 2; it++)
-#pragma unroll
-        for (int t16 = 0; t16 < 2; t16++) {
-          h16x8 ot[D / 32], qt[D / 32];              // again requested together, ahead of their MFMAs
-#pragma unroll
-          for (int t = 0; t < D / 32; t++) {
-            ot[t] = IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
-            qt[t] = IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
-          }
-          const h16x8 pb = pack8(st[it], t16 * 8);
-          const h16x8 dsb = pack8(dp[it], t16 * 8);
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int t = 0; t < D / 32; t++) {
-            dv[t] = KFKB_MFMA_H16(ot[t], pb, dv[t]);
-            dk[t] = KFKB_MFMA_H16(qt[t], dsb, dk[t]);
-          }
-          __builtin_amdgcn_sched_barrier(0);
+        for (int t = 0; t < D / 32; t++) {
+          o4[t] = IO::frag_tr(Ot, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
+          q4[t] = IO::frag_tr(Qt, it * 32 + t16 * 16 + tr_row, t * 32 + tr_col);
         }
+      };
+      load3(0, ot[0], qt[0]);
+#pragma unroll
+      for (int g = 0; g < 4; g++) {
+        const int it = g >> 1, t16 = g & 1;
+        if (g + 1 < 4) load3(g + 1, ot[(g + 1) & 1], qt[(g + 1) & 1]);
+        const h16x8 pb = pack8(st[it], t16 * 8);
+        const h16x8 dsb = pack8(dp[it], t16 * 8);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int t = 0; t < D / 32; t++) {
+          dv[t] = KFKB_MFMA_H16(ot[g & 1][t], pb, dv[t]);
+          dk[t] = KFKB_MFMA_H16(qt[g & 1][t], dsb, dk[t]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    if (ib + 1 < nq) {
-      IO::store(Qs + (cur ^ 1) * 64 * D, rq);
-      IO::store(Os + (cur ^ 1) * 64 * D, ro);
-      store_stats(cur ^ 1);
-    }
+    if (ib + 1 < nq) store_stats(cur ^ 1);
+    wait_vmcnt<0>();
     __syncthreads();
   }
   if (j < T) {

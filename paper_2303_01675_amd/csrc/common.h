@@ -108,6 +108,31 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// ---- loads that write LDS directly ---------------------------------------------------------------
+// buffer_load_dwordx4 ... lds: lane l of the wave moves 16 bytes from (resource base + voff + soff) to LDS byte address
+// lds_addr + 16 l; bytes past the resource's size read as zero.  Issued through inline assembly so that the compiler
+// does not serialise every later LDS read behind them; the caller counts them with wait_vmcnt before the barrier
+// that publishes the data.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void dma16b(i32x4 rsrc, int voff, int soff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "m0");
+}
+__device__ __forceinline__ i32x4 make_rsrc(const void* p, size_t bytes) {
+  const unsigned long long a = (unsigned long long)p;
+  i32x4 r;
+  r[0] = __builtin_amdgcn_readfirstlane((int)(a & 0xffffffffu));
+  r[1] = __builtin_amdgcn_readfirstlane((int)(a >> 32));
+  r[2] = __builtin_amdgcn_readfirstlane((int)(bytes > 0xFFFFFFFFull ? 0xFFFFFFFFull : bytes));
+  r[3] = 0x00020000;
+  return r;
+}
+template <int N> __device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "");
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
+}
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
 // ---- GELU, tanh form: 0.5 u (1 + tanh(z)), z = c0 (u + c1 u^3) ---------------------------------
 // With s = 1 / (1 + exp(-2 z)): 0.5 (1 + tanh z) = s and 1 - tanh^2 z = 4 s (1 - s), hence
 //   gelu(u) = u s,   gelu'(u) = s + u s (1 - s) 2 z'(u),   2 z' = 2 c0 (1 + 3 c1 u^2).

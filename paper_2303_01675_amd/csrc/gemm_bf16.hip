@@ -118,25 +118,7 @@ __device__ __forceinline__ void epilogue_quad(const f32x16& acc, int q, int m, i
 
 constexpr int CK_ = 32;            // depth of a chunk
 constexpr int RING = 4;            // chunks in LDS
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ void dma16b(i32x4 rsrc, int voff, int soff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds" :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "m0");
-}
-__device__ __forceinline__ i32x4 make_rsrc(const void* p, size_t bytes) {
-  const unsigned long long a = (unsigned long long)p;
-  i32x4 r;
-  r[0] = __builtin_amdgcn_readfirstlane((int)(a & 0xffffffffu));
-  r[1] = __builtin_amdgcn_readfirstlane((int)(a >> 32));
-  r[2] = __builtin_amdgcn_readfirstlane((int)(bytes > 0xFFFFFFFFull ? 0xFFFFFFFFull : bytes));
-  r[3] = 0x00020000;
-  return r;
-}
-template <int N> __device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "");
-  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | 0x0070 | 0x0F00);
-}
-__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // ------------------------------------------------------------------------------------------------
 // The main loop shared by the NT and TN kernels.  LAYOUT owns the LDS rings, the DMA source offsets and the
