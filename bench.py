@@ -111,6 +111,8 @@ class Run:
         kf.stage_set_wgrad_stream(self.wgrad_stream)
         if args.inputs_ahead >= 0:
             kf.kfkb_set_inputs_ahead(args.inputs_ahead)
+        if args.mid_tiles >= 0:
+            kf.kfkb_set_mid_tiles(args.mid_tiles)
         if args.send_copy_blocks >= 0:
             kf.stage_set_send_copy_blocks(args.send_copy_blocks)
         if args.wstep_window > 0:
@@ -276,6 +278,7 @@ def main():
                          "when the first is the default workload, else none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--inputs-ahead", type=int, default=-1, help="receive order (kfkb_set_inputs_ahead): 0 consumption order, 1 stage inputs one schedule unit ahead, 2 by k; -1 keeps the library default")
+    ap.add_argument("--mid-tiles", type=int, default=-1, help="128 x 256 tiles for the forward / input-gradient products (kfkb_set_mid_tiles): 0 never, 1 where they rate best, 2 wherever they fit; -1 keeps the library default")
     ap.add_argument("--send-copy-blocks", type=int, default=-1, help="sends: 0 the runtime's device-to-host copy, n > 0 the library's copy kernel with n workgroups (stage_set_send_copy_blocks); -1 keeps the library default")
     ap.add_argument("--wstep-window", type=int, default=0,
                     help="most micro-batches whose gradient accumulation goes into one W step (stage_set_wstep_window); "

@@ -256,6 +256,12 @@ int stage_set_send_copy_blocks(int blocks);
  * host-only; returns the previous value.  A product's result does not depend on the tile shape beyond fp32
  * rounding order.  KFKB_E_ARG for tiles < 1. */
 int kfkb_set_big_tile_min(int tiles);
+/* 128 x 256 tiles for NT products whose B operand is chunk-major (the stage's forward and input-gradient products;
+ * K % 64 == 0, N % 256 == 0): mode 0 never, 1 (default) where the shape rates best — share of the CU slots its tiles
+ * fill over whole rounds of 256, times `rate_percent` / 100, the rate such a tile reaches of a 256 x 256 tile's (default
+ * 90; 128 x 128 tiles count 84) —, 2 wherever they fit.  Process-wide, host-only; returns the previous mode.  A
+ * product's result does not depend on the tile shape beyond fp32 rounding order.  KFKB_E_ARG outside the ranges. */
+int kfkb_set_mid_tiles(int mode, int rate_percent);
 int stage_sync(void);                     /* waits for both compute lanes, the send and the receive stream */
 int stage_sync_timeout(double seconds);   /* same, polling; KFKB_E_TIMEOUT if not done in time */
 int stage_destroy(void);

@@ -16,7 +16,7 @@ __all__ = [
     "run_pipeline_kFkB", "stage_get_pipeline_order",
     "stage_config", "stage_init", "stage_param_count", "stage_activation_bytes", "stage_workspace_bytes",
     "stage_bind", "stage_set_delays", "stage_refresh_weights", "stage_forward", "stage_backward", "run_kFkB",
-    "stage_last_k", "stage_side_streams_overlap", "stage_zero_grads", "stage_set_wgrad_stream", "stage_set_compute_lanes", "stage_set_fused_w_reductions", "kfkb_set_big_tile_min", "stage_set_wstep_window", "kfkb_set_inputs_ahead", "stage_set_send_copy_blocks", "stage_sync", "stage_sync_timeout", "stage_destroy", "stage_get_order",
+    "stage_last_k", "stage_side_streams_overlap", "stage_zero_grads", "stage_set_wgrad_stream", "stage_set_compute_lanes", "stage_set_fused_w_reductions", "kfkb_set_big_tile_min", "kfkb_set_mid_tiles", "stage_set_wstep_window", "kfkb_set_inputs_ahead", "stage_set_send_copy_blocks", "stage_sync", "stage_sync_timeout", "stage_destroy", "stage_get_order",
     "stage_last_run_ms", "StageBuffers", "kfkb_profile", "kfkb_profile_report",
     "kfkb_op_gemm", "kfkb_op_tile_weights", "kfkb_op_gemm_nt_tiled", "kfkb_op_layernorm_fwd", "kfkb_op_layernorm_bwd", "kfkb_op_colsum_accum",
     "kfkb_op_colsum_accum_static",
@@ -110,6 +110,7 @@ def load_library():
         "kfkb_set_big_tile_min": (i, [i]),
         "stage_set_wstep_window": (i, [i]),
         "kfkb_set_inputs_ahead": (i, [i]),
+        "kfkb_set_mid_tiles": (i, [i, i]),
         "stage_set_send_copy_blocks": (i, [i]),
         "stage_sync": (i, []),
         "stage_sync_timeout": (i, [C.c_double]),
@@ -364,6 +365,10 @@ def kfkb_set_big_tile_min(tiles):
 
 def stage_set_send_copy_blocks(blocks):
     return _check(load_library().stage_set_send_copy_blocks(int(blocks)))
+
+
+def kfkb_set_mid_tiles(mode, rate_percent=90):
+    return _check(load_library().kfkb_set_mid_tiles(int(mode), int(rate_percent)))
 
 
 def kfkb_set_inputs_ahead(mode):

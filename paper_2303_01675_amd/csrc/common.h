@@ -243,6 +243,8 @@ size_t colsum_scratch_floats(int rows, int N);   // floats of `scratch` that lau
 // fewest 256 x 256 tiles a product must divide into before they are preferred over 128 x 128 tiles
 // (kfkb_set_big_tile_min)
 extern int g_big_tile_min;
+extern int g_mid_tile_mode;      // 128 x 256 tiles for NT products with a chunk-major B: 0 never, 1 where they rate best, 2 wherever they fit
+extern int g_mid_tile_rate;      // what such a tile reaches of a 256 x 256 tile's rate, in percent
 const char* gemm_bf16_check(const GemmArgs& g);                  // NULL if the shape is supported (either 16-bit type)
 
 hipError_t launch_attention_fwd_f32(const float* qkv, float* o, float* lse, int b, int T, int H, int heads,

@@ -41,6 +41,7 @@ void prof_key_name_bf16(int key, char* out, size_t cap, int* bound) {
     const int r = key - (tn ? PK_GEMM_TN : PK_GEMM_NT);
     *bound = 0;
     if (tn && (r == 300 || r == 301)) { snprintf(out, cap, "gemm_bf16_tn_grouped_kernel<%d,%d>", r == 301 ? 256 : 128, r == 301 ? 256 : 128); return; }
+    if (!tn && r >= 400) { snprintf(out, cap, "gemm_bf16_nt_kernel<128,256,%s>", epi[r - 400]); return; }
     const bool staged = r >= 200;
     const int tile = (r % 200) >= 100 ? 256 : 128;
     snprintf(out, cap, "gemm_bf16_%s_kernel<%d,%d,%s>", tn ? (staged ? "tn_staged" : "tn") : "nt", tile, tile, epi[r % 100]);
@@ -67,6 +68,8 @@ void prof_key_name_bf16(int key, char* out, size_t cap, int* bound) {
 
 namespace kfkb {
 int g_big_tile_min = 192;
+int g_mid_tile_mode = 1;
+int g_mid_tile_rate = 90;
 bool prof_acquire(int key, double work, hipEvent_t* e0, hipEvent_t* e1) {
   if (!g_prof_on) return false;
   while (g_prof_pool.size() < g_prof_next + 2) {
@@ -1929,6 +1932,15 @@ int kfkb_set_inputs_ahead(int mode) {
   if (mode < 0 || mode > 2) return fail(KFKB_E_ARG, "kfkb_set_inputs_ahead: mode is 0, 1 or 2 (by k) (got %d)", mode);
   const int prev = g_inputs_ahead_mode;
   g_inputs_ahead_mode = mode;
+  return prev;
+}
+
+int kfkb_set_mid_tiles(int mode, int rate_percent) {
+  if (mode < 0 || mode > 2 || rate_percent < 1 || rate_percent > 100)
+    return fail(KFKB_E_ARG, "kfkb_set_mid_tiles: mode 0 .. 2 and rate 1 .. 100 percent (got %d, %d)", mode, rate_percent);
+  const int prev = kfkb::g_mid_tile_mode;
+  kfkb::g_mid_tile_mode = mode;
+  kfkb::g_mid_tile_rate = rate_percent;
   return prev;
 }
 

@@ -260,10 +260,12 @@ struct NtLayout32 {
 template <int BM, int BN>
 struct NtLayout64 {
   static constexpr int TM = BM / 64, TN = BN / 64, A_SLICE = BM * 64, B_SLOT = BN * CK_, A_RING = 3;
-  static_assert(TM == TN, "one DMA instruction per MFMA group");
-  static constexpr int PERIOD = 12, WAIT_PRO = 5 * TN, WAIT_MID = 4 * TN;
+  // Per chunk and wave: TN pieces of B (one per MFMA group of the first k-step) and TM pieces of A (on the first TM
+  // groups of the second k-step): a tile may be narrower in M than in N, not the other way round.
+  static_assert(TM <= TN, "the A pieces of a chunk ride on the first TM groups of its second k-step");
+  static constexpr int PERIOD = 12, WAIT_PRO = 3 * TM + 2 * TN, WAIT_MID = 2 * TM + 2 * TN;
   static constexpr size_t LDS_BYTES = (size_t)(A_RING * A_SLICE + RING * B_SLOT) * 2;
-  i32x4 ra, rb; unsigned lds0; int wave, nk, ns, sb; int voa[2 * TN], vob[TN];
+  i32x4 ra, rb; unsigned lds0; int wave, nk, ns, sb; int voa[2 * TM], vob[TN];
   const h16_t* fa_base[4]; const h16_t* fb_base[2];
   __device__ __forceinline__ void init(char* smem, const h16_t* A, const h16_t* B, int M, int N, int K, int m0, int n0, int lane, int wave_) {
     wave = wave_; nk = K / CK_; ns = K / 64; sb = N * CK_ * 2;       // bytes from one chunk of B to the next
@@ -272,7 +274,7 @@ struct NtLayout64 {
     // A: instruction g = i * 4 + wave covers rows 8 g .. 8 g + 7, lane l row l / 8, physical piece l % 8
     const int arow = lane >> 3, apiece = (lane & 7) ^ (((wave & 1) << 2) | (lane >> 4));
 #pragma unroll
-    for (int i = 0; i < 2 * TN; i++) voa[i] = ((m0 + (i * 4 + wave) * 8 + arow) * K + apiece * 8) * 2;
+    for (int i = 0; i < 2 * TM; i++) voa[i] = ((m0 + (i * 4 + wave) * 8 + arow) * K + apiece * 8) * 2;
     const int brow = lane >> 2, bpiece = (lane & 3) ^ ((lane >> 4) & 3);
 #pragma unroll
     for (int i = 0; i < TN; i++) vob[i] = ((n0 + (i * 4 + wave) * 16 + brow) * CK_ + bpiece * 8) * 2;
@@ -295,24 +297,25 @@ struct NtLayout64 {
   // of A slices and B of chunks c+2 and c+3 when chunk c reaches its middle.
   __device__ __forceinline__ void prologue() {
 #pragma unroll
-    for (int i = 0; i < 2 * TN; i++) dma_a(i, 0, 0);
+    for (int i = 0; i < 2 * TM; i++) dma_a(i, 0, 0);
 #pragma unroll
     for (int i = 0; i < TN; i++) dma_b(i, 0, 0);
 #pragma unroll
-    for (int i = 0; i < TN; i++) dma_a(i, 1, 1);
+    for (int i = 0; i < TM; i++) dma_a(i, 1, 1);
 #pragma unroll
     for (int i = 0; i < TN; i++) dma_b(i, 1, 1);
 #pragma unroll
-    for (int i = 0; i < TN; i++) dma_a(TN + i, 1, 1);
+    for (int i = 0; i < TM; i++) dma_a(TM + i, 1, 1);
 #pragma unroll
     for (int i = 0; i < TN; i++) dma_b(i, 2, 2);
 #pragma unroll
-    for (int i = 0; i < TN; i++) dma_a(i, 2, 2);
+    for (int i = 0; i < TM; i++) dma_a(i, 2, 2);
   }
   __device__ __forceinline__ void dma0(int j, int kc, int pc) { dma_b(j, kc + 3, (pc + 3) & 3); }
   __device__ __forceinline__ void dma1(int j, int kc, int pc) {
+    if (j >= TM) return;
     if (pc & 1) dma_a(j, (kc >> 1) + 3, (pc >> 1) % 3);
-    else dma_a(TN + j, (kc >> 1) + 2, ((pc >> 1) + 2) % 3);
+    else dma_a(TM + j, (kc >> 1) + 2, ((pc >> 1) + 2) % 3);
   }
   __device__ __forceinline__ h16x8 rd_a(int pc, int ks, int i) {
     return *reinterpret_cast<const h16x8*>(fa_base[(pc & 1) * 2 + ks] + ((pc >> 1) % 3) * A_SLICE + i * 32 * 64);
@@ -1082,7 +1085,7 @@ static hipError_t launch_nt_bt(const GemmArgs& g, hipStream_t s) {
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_NT + (BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
+  klaunch(kern, dim3(grid), dim3(256), smem, s, PK_GEMM_NT + (BM != BN ? 400 : BM == 256 ? 100 : 0) + EPI, 2.0 * g.M * g.N * g.K, g.M, g.N, g.K,
           (const h16_t*)g.A, (const h16_t*)g.B, (const h16_t*)g.bias, (const h16_t*)g.residual, (h16_t*)g.C,
           (h16_t*)g.C2, g.Cacc, tiles_m, tiles_n);
   return hipGetLastError();
@@ -1220,9 +1223,30 @@ static bool use_big_tiles(int M, int N, bool m_must_divide) {
   return tiles >= big_tile_min();
 }
 
+// Tile shape of an NT product.  256 x 256 tiles where they give most CUs a tile (use_big_tiles).  Otherwise, for a
+// chunk-major B, 128 x 256 tiles where they use the CUs better than 128 x 128 tiles would: a shape is rated by the
+// share of CU slots its tiles fill over whole rounds of 256, times what a tile of that shape reaches of a
+// 256 x 256 tile's rate (g_mid_tile_rate / 100 for 128 x 256, 0.84 for 128 x 128; measured 1430 - 1480, 1300 - 1330 and
+// 1210 - 1260 TFLOP/s on products that fill their rounds: 1, 0.9, 0.84).
+static double round_fill(long tiles) { return (double)tiles / (double)(((tiles + 255) / 256) * 256); }
+static int nt_tile_shape(const GemmArgs& g) {                     // 2: 256 x 256, 1: 128 x 256, 0: 128 x 128
+  const bool mid_ok = g.b_tiled && g.N % 256 == 0 && g.K % 64 == 0 && g_mid_tile_mode != 0;
+  if (mid_ok && g_mid_tile_mode == 2) return 1;
+  const bool big_ok = use_big_tiles(g.M, g.N, false);
+  if (!mid_ok) return big_ok ? 2 : 0;
+  const long tm = (g.M + 127) / 128;
+  const double big = round_fill((long)((g.M + 255) / 256) * (g.N / 256));
+  const double mid = round_fill(tm * (g.N / 256)) * g_mid_tile_rate / 100.0;
+  const double small = round_fill(tm * (g.N / 128)) * 0.84;
+  if (big_ok) return big >= mid ? 2 : 1;       // 128 x 128 tiles only where 256 x 256 would leave a quarter of the CUs idle
+  return mid > small ? 1 : 0;
+}
+
 template <int EPI>
 static hipError_t launch_nt_epi(const GemmArgs& g, hipStream_t s) {
-  if (use_big_tiles(g.M, g.N, false)) return launch_nt<256, 256, EPI>(g, s);
+  const int shape = nt_tile_shape(g);
+  if (shape == 2) return launch_nt<256, 256, EPI>(g, s);
+  if (shape == 1) return launch_nt_bt<128, 256, EPI, true>(g, s);
   return launch_nt<128, 128, EPI>(g, s);
 }
 

@@ -147,10 +147,16 @@ def test_gemm_bf16_nt(dt, epi, M, N, K):
 @pytest.mark.parametrize("M,N,K,tiled", [(128, 128, 64, 1), (300, 384, 448, 2), (515, 256, 832, 1), (2048 + 77, 2048, 1024, 2),
                                          (4096 - 3, 4096, 128, 1), (4096, 1024, 768, 2), (1000, 1024, 1024, 1),
                                          (2048, 512, 1536, 2)])
-def test_gemm_bf16_nt_chunk_major_weights(epi, M, N, K, tiled):
+@pytest.mark.parametrize("mid", [0, 2])
+def test_gemm_bf16_nt_chunk_major_weights(epi, M, N, K, tiled, mid):
     """The NT kernel that reads B chunk-major (and A in 64-deep slices): reduction lengths below, at and
-    beyond one period of its LDS rings (12 chunks of 32), ragged M, both tile sizes."""
-    got, ref = _gemm_case(kf.BF16, kf.GEMM_NT, epi, M, N, K, tiled=tiled)
+    beyond one period of its LDS rings (12 chunks of 32), ragged M, the square tile sizes (mid = 0) and the
+    128 x 256 tiles wherever N allows them (mid = 2)."""
+    kf.kfkb_set_mid_tiles(mid)
+    try:
+        got, ref = _gemm_case(kf.BF16, kf.GEMM_NT, epi, M, N, K, tiled=tiled)
+    finally:
+        kf.kfkb_set_mid_tiles(1)
     for g, r in zip(got, ref):
         assert_close(g, r, kf.BF16 if epi != kf.EPI_ACCUM else kf.F32, "gemm bf16 NT chunk-major epi %d" % epi,
                      factor=1 if epi != kf.EPI_ACCUM else 10)

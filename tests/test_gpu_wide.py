@@ -41,7 +41,7 @@ def _run(st, k, M):
     return st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone()
 
 
-@pytest.mark.parametrize("tiles", ["own-tile-choice", "big-tiles"])
+@pytest.mark.parametrize("tiles", ["own-tile-choice", "big-tiles", "mid-tiles"])
 @pytest.mark.parametrize("name", list(CASES))
 def test_wide_stage_matches_oracle_and_is_identical_for_every_k(name, tiles):
     c = CASES[name]
@@ -49,6 +49,7 @@ def test_wide_stage_matches_oracle_and_is_identical_for_every_k(name, tiles):
     blocks = synth.stage_weights_tiled(L, H, 4 * H, "bf16")
     xs, dys = _inputs(c, M)
     prev = kf.kfkb_set_big_tile_min(1 if tiles == "big-tiles" else 192)
+    kf.kfkb_set_mid_tiles(2 if tiles == "mid-tiles" else 1)      # 128 x 256 tiles for every forward / input-gradient product
     try:
         st = kf.StageBuffers(blocks, kf.BF16, heads, T, b, M, M)
         st.set_inputs(xs, dys)
@@ -90,6 +91,7 @@ def test_wide_stage_matches_oracle_and_is_identical_for_every_k(name, tiles):
         one.close()
     finally:
         kf.kfkb_set_big_tile_min(prev)
+        kf.kfkb_set_mid_tiles(1)
         kf.stage_destroy()
 
 
@@ -137,10 +139,12 @@ def _rows(seed, n, M):
 
 @pytest.mark.parametrize("M,N,K,big", [(2048 + 77, 4096, 8192, 0), (4096, 4096, 8192, 1),       # 16 x 16 large tiles
                                        (1000, 2048, 16384, 0), (512 + 9, 2048, 16384, 1),
-                                       (300, 1024, 32768, 0), (1536 + 77, 8192, 32768, 1)])      # very wide stage: fc2 / fc1 input gradient
+                                       (300, 1024, 32768, 0), (1536 + 77, 8192, 32768, 1),       # very wide stage: fc2 / fc1 input gradient
+                                       (2048, 4096, 16384, 2), (1000 + 3, 2048, 8192, 2), (4096, 2048, 6144, 2)])   # 128 x 256 tiles
 def test_chunk_major_nt_product_at_the_reduction_lengths_of_the_larger_stages(M, N, K, big):
-    """The NT kernel the stage uses (B chunk-major, A in 64-deep slices) at K = 8192, 16384 and 32768, both tile
-    shapes; the oracle side is the textbook product of about 64 sampled output rows, all columns."""
+    """The NT kernel the stage uses (B chunk-major, A in 64-deep slices) at K = 8192, 16384 and 32768, the two square
+    tile shapes (big = 0, 1) and the 128 x 256 tiles of the 1.3B-class and wide stages (big = 2); the oracle side is
+    the textbook product of about 64 sampled output rows, all columns."""
     from _util import dev, host, rnd
     dt = kf.BF16
     A = rnd(80, (M, K), dt)
@@ -156,10 +160,12 @@ def test_chunk_major_nt_product_at_the_reduction_lengths_of_the_larger_stages(M,
     Bd = torch.from_numpy(B).to(torch.bfloat16).cuda()
     kf.kfkb_op_tile_weights(Bd, Bt, N, K, False)
     Cout = torch.zeros(M, N, dtype=torch.bfloat16, device="cuda")
-    prev = kf.kfkb_set_big_tile_min(1 if big else 1 << 30)
+    prev = kf.kfkb_set_big_tile_min(1 if big == 1 else 1 << 30)
+    kf.kfkb_set_mid_tiles(2 if big == 2 else 0)
     try:
         kf.kfkb_op_gemm_nt_tiled(kf.EPI_BIAS, M, N, K, dev(A, dt), Bt, dev(bias, dt), None, Cout, None, None)
         torch.cuda.synchronize()
     finally:
         kf.kfkb_set_big_tile_min(prev)
+        kf.kfkb_set_mid_tiles(1)
     assert_close(host(Cout[torch.from_numpy(rows).cuda()]), ref + bias, dt, "chunk-major NT rows")

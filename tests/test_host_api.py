@@ -75,3 +75,13 @@ def test_receive_list_mode_is_checked_and_returned(lib):
             kf.kfkb_set_inputs_ahead(bad)
         assert e.value.code == -1
     assert kf.kfkb_set_inputs_ahead(2) == 2
+
+
+def test_mid_tile_setter_is_checked(lib):
+    assert kf.kfkb_set_mid_tiles(0) == 1             # default: where the shape rates best
+    assert kf.kfkb_set_mid_tiles(2, 75) == 0
+    for bad in ((-1, 90), (3, 90), (1, 0), (1, 101)):
+        with pytest.raises(kf.KfkbError) as e:
+            kf.kfkb_set_mid_tiles(*bad)
+        assert e.value.code == -1
+    assert kf.kfkb_set_mid_tiles(1) == 2
