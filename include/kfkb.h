@@ -142,7 +142,8 @@ int stage_config(const kfkb_config_t* cfg);
  * matrices [in, out]; QKV columns ordered [Q | K | V], head j owning columns j*d..(j+1)*d of
  * each third, d = hidden / heads.  Borrowed until stage_destroy.
  * Errors: KFKB_E_ARG for a null pointer, a size < 1, hidden % heads != 0, stage_index outside [0, num_stages), or
- * an unsupported shape: hidden > 8192 (any dtype); 16-bit storage needs hidden % 128 == 0 and d in {64, 128};
+ * an unsupported shape: hidden > 8192 (any dtype); 16-bit storage needs hidden % 128 == 0, d in {64, 128} and
+ * seq * 3 * hidden * 2 bytes < 2 GiB (the attention kernels address a sample's rows with 32-bit byte offsets);
  * fp32 needs hidden % 8 == 0, d <= 128 and seq <= 4096; activation recomputation needs
  * micro_batch * seq * mlp_width % 8 == 0.  KFKB_E_STATE if a stage exists. */
 int stage_init(const void* weights, int layers, int hidden, int heads, int seq);
@@ -407,7 +408,8 @@ int kfkb_op_colsum_accum_static(int dtype, const void* dy, float* out, int rows,
 int kfkb_op_gelu_bwd(int dtype, const void* dg, const void* u, void* du, size_t n, void* stream);
 
 /* Attention over qkv [b*T, 3H] (columns [Q|K|V], head-major inside each third):
- * o [b*T, H], lse fp32 [b, heads, T] = log-sum-exp of the scaled, masked scores. */
+ * o [b*T, H], lse fp32 [b, heads, T] = log-sum-exp of the scaled, masked scores.  16-bit storage: head size 64 or
+ * 128 and T * 3 * H * 2 bytes < 2 GiB; fp32: head size <= 128, T <= 4096; otherwise KFKB_E_ARG. */
 int kfkb_op_attention_fwd(int dtype, const void* qkv, void* o, float* lse, int b, int T, int H, int heads,
                           int causal, void* stream);
 

@@ -673,6 +673,7 @@ static hipError_t bwd_d(const h16_t* qkv, const h16_t* o, const h16_t* d_o, cons
 hipError_t launch_attention_fwd_h16(const h16_t* qkv, h16_t* o, float* lse, int b, int T, int H, int heads,
                                      int causal, hipStream_t s) {
   if (b <= 0 || T <= 0) return hipSuccess;
+  if ((double)T * 3.0 * H * sizeof(h16_t) >= 2147483648.0) return hipErrorInvalidValue;   // 32-bit byte offsets inside a sample
   return (H / heads == 64) ? fwd_d<64>(qkv, o, lse, b, T, H, heads, causal, s)
                            : fwd_d<128>(qkv, o, lse, b, T, H, heads, causal, s);
 }
@@ -681,6 +682,7 @@ hipError_t launch_attention_bwd_h16(const h16_t* qkv, const h16_t* o, const h16_
                                      float* dsum, h16_t* dqkv, int b, int T, int H, int heads, int causal,
                                      hipStream_t s) {
   if (b <= 0 || T <= 0) return hipSuccess;
+  if ((double)T * 3.0 * H * sizeof(h16_t) >= 2147483648.0) return hipErrorInvalidValue;
   return (H / heads == 64) ? bwd_d<64>(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s)
                            : bwd_d<128>(qkv, o, d_o, lse, dsum, dqkv, b, T, H, heads, causal, s);
 }

@@ -1274,6 +1274,8 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   if (c.dtype != KFKB_F32) {
     if (hidden % 128 != 0) return fail(KFKB_E_ARG, "stage_init: 16-bit storage needs hidden %% 128 == 0 (got %d)", hidden);
     if (d != 64 && d != 128) return fail(KFKB_E_ARG, "stage_init: 16-bit storage needs head size 64 or 128 (got %d)", d);
+    if ((double)seq * 3.0 * hidden * 2.0 >= 2147483648.0)
+      return fail(KFKB_E_ARG, "stage_init: seq * 3 * hidden * 2 bytes must stay below 2 GiB for 16-bit storage (seq = %d, hidden = %d)", seq, hidden);
   } else {
     if (hidden % 8 != 0) return fail(KFKB_E_ARG, "stage_init: fp32 needs hidden %% 8 == 0 (got %d)", hidden);
     if (d > 128) return fail(KFKB_E_ARG, "stage_init: fp32 needs head size <= 128 (got %d)", d);
@@ -2159,6 +2161,9 @@ static int check_attn(const char* who, int dtype, int b, int T, int H, int heads
   const int d = H / heads;
   if (dtype != KFKB_F32 && d != 64 && d != 128) return fail(KFKB_E_ARG, "%s: 16-bit storage needs head size 64 or 128 (got %d)", who, d);
   if (dtype == KFKB_F32 && (d > 128 || T > 4096)) return fail(KFKB_E_ARG, "%s: fp32 needs head size <= 128 and T <= 4096", who);
+  // the 16-bit kernels address the rows of one sample's qkv with 32-bit byte offsets
+  if (dtype != KFKB_F32 && (double)T * 3.0 * H * 2.0 >= 2147483648.0)
+    return fail(KFKB_E_ARG, "%s: T * 3 * H * 2 bytes must stay below 2 GiB for 16-bit storage (T = %d, H = %d)", who, T, H);
   return 0;
 }
 

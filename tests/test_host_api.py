@@ -85,3 +85,13 @@ def test_mid_tile_setter_is_checked(lib):
             kf.kfkb_set_mid_tiles(*bad)
         assert e.value.code == -1
     assert kf.kfkb_set_mid_tiles(1) == 2
+
+
+def test_sixteen_bit_attention_refuses_samples_beyond_its_32_bit_offsets(lib):
+    """The 16-bit attention kernels address the rows of one sample with 32-bit byte offsets: T * 3H * 2 < 2 GiB is
+    checked before any launch (host-side; nothing runs)."""
+    for fn, args in ((kf.kfkb_op_attention_fwd, (kf.BF16, None, None, None, 1, 65536, 8192, 64, 1)),
+                     (kf.kfkb_op_attention_bwd, (kf.BF16, None, None, None, None, None, None, 1, 65536, 8192, 64, 1))):
+        with pytest.raises(kf.KfkbError) as e:
+            fn(*args)
+        assert e.value.code == -1 and "2 GiB" in str(e.value)
