@@ -150,7 +150,7 @@ __global__ void __launch_bounds__(256) ln_bwd_dx_kernel(const T* __restrict__ dy
 }
 
 // LayerNorm backward with the parameter-gradient partial sums folded in (rows short enough to keep the
-// per-lane column sums in registers: H <= 2048).  A block owns a run of rows, wave w takes every fourth of
+// per-lane column sums in registers; used for H <= 1024).  A block owns a run of rows, wave w takes every fourth of
 // them; a lane always holds the same columns, so it adds dy and dy * xhat of its rows into registers, the
 // four waves meet in LDS in fixed order and the block writes one partial row [2][H] for the finishing pass.
 template <typename T, int NCH>
@@ -631,9 +631,12 @@ static hipError_t ln_bwd_t(const T* dy, const T* x, const float* mean, const flo
                            const T* dres, T* dx, float* dgamma, float* dbeta, float* scratch, int rows, int H,
                            hipStream_t s) {
   const int nch = nch_for(H);
+  // Rows of up to 1024 values: dx and the partial parameter sums in one pass (fewer launches; the pass is short either
+  // way).  Longer rows: the dx kernel, which gives every CU many rows at a time, then the partial sums (measured at
+  // 4096 rows of 2048: 26 us fused, 19 us in two launches; 1.3B-class stage 272.5 -> 269.0 ms per iteration; at 1024
+  // the two launches were slower, 44.1 -> 44.6 ms on the GPT-2-medium-shaped stage).
   if (nch == 1) return ln_bwd_fused_launch<T, 1>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
   if (nch == 2) return ln_bwd_fused_launch<T, 2>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
-  if (nch == 4) return ln_bwd_fused_launch<T, 4>(dy, x, mean, rstd, gamma, dres, dx, dgamma, dbeta, scratch, rows, H, s);
   const RowShape rs = row_shape(H);
   const int rpb = 4 / rs.wpr;
   const dim3 grid((rows + rpb - 1) / rpb);
@@ -661,7 +664,7 @@ hipError_t launch_ln_bwd(int dt, const void* dy, const void* x, const float* mea
 // The finishing pass of launch_ln_bwd called with dgamma == nullptr: adds the partial sums it left in `scratch`
 // into dgamma / dbeta.  rows and H must be those of that call (they fix the number of partial rows).
 int ln_bwd_partial_rows(int rows, int H) {
-  if (nch_for(H) <= 4) {
+  if (nch_for(H) <= 2) {
     const int rpb = std::max(8, ((rows + 511) / 512 + 3) / 4 * 4);
     return (rows + rpb - 1) / rpb;
   }
