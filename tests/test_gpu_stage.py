@@ -259,6 +259,33 @@ def test_lanes_and_w_step_placement_change_timing_not_results(dt):
         st.close()
 
 
+@pytest.mark.parametrize("dt,lanes", [(kf.F32, 1), (kf.BF16, 2), (kf.BF16, 1)])
+def test_iterations_enqueued_back_to_back_keep_every_bit(dt, lanes):
+    """A training loop (and bench.py) enqueues iteration after iteration without waiting in between: slots, buffers
+    and events are reused while the previous iteration is still running.  Several iterations back to back, with
+    transfer delays, plans changing from one to the next and the host arrays scrubbed before, leave exactly the bits
+    of one synchronised iteration (which is compared with the oracle)."""
+    L, H, heads, T, b, M = (2, 128, 2, 64, 2, 8) if dt == kf.F32 else (3, 128, 2, 96, 2, 8)
+    st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=4)
+    kf.stage_set_compute_lanes(lanes)
+    G, Y, dX, order = _run(st, 2, M)
+    _check_against_oracle(dt, st, blocks, xs, dys, heads, 1, G, Y, dX, order, 2)
+    ref = (st.grads.clone(), st.h_out.clone(), st.h_ingrad.clone())
+    d = np.full(M, 300_000, dtype=np.int64)                     # 0.3 ms per transfer
+    kf.stage_set_delays(d, d, d, d)
+    st.h_out.fill_(3.0); st.h_ingrad.fill_(3.0)
+    for k in (1, 4, 2, 4, 1, 2):                                # no synchronisation between the iterations
+        kf.stage_zero_grads()
+        kf.run_kFkB(k, M, 0)
+    kf.stage_sync()
+    for a, b_ in zip(ref, (st.grads, st.h_out, st.h_ingrad)):
+        assert torch.equal(a, b_)
+    assert [(o, mb) for o, mb, _, _ in kf.stage_get_order()] == sch.kfkb_order(2, M, 0)
+    kf.stage_set_delays(None, None, None, None)
+    kf.stage_set_compute_lanes(2)
+    st.close()
+
+
 @pytest.mark.parametrize("dt", [kf.F32, kf.BF16])
 def test_send_copy_path_changes_no_bit(dt):
     """Outputs reach the pinned host arrays through the library's copy kernel (any number of workgroups, also more
