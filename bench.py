@@ -197,6 +197,8 @@ def kernel_pass(run, k, steps, args):
             roofline["traffic"] = (hit["read_bytes"] + hit["write_bytes"]) * scale
             roofline["traffic_source"] = ("profiles/stage_%s_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, "
                                           "scaled by a 1 GiB copy; x %.2f for the work of a launch in this run)" % (tag, scale))
+            roofline["traffic_level"] = ("bytes between the eight L2s and the fabric: every XCD streams the operand panels of its "
+                                         "own tiles through its own 4 MiB L2, and hits in the memory-side cache are not subtracted")
     except (OSError, ValueError, KeyError):
         pass
     gemm = [s for s in stats if s["name"].startswith("gemm_")]
