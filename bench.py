@@ -294,9 +294,11 @@ def main():
     ap.add_argument("--lanes", type=int, default=0, choices=[0, 1, 2],
                     help="compute lanes: ops in flight at once, within the plan's peak of live micro-batches; 0 (default): "
                          "the library's own choice for the stage's shape (2 for small blocks, 1 for large ones)")
-    ap.add_argument("--adaptive", action="store_true",
+    ap.add_argument("--adaptive", dest="adaptive", action="store_true", default=None,
                     help="also time the same steps under the tuner (run_kFkB_adaptive: moving averages of the measured "
-                         "transfer times, k re-chosen every 2 iterations among the workload's k values)")
+                         "transfer times, k re-chosen every 2 iterations among the workload's k values); on by default for "
+                         "the very wide stage under its drifting delays (the configuration that names an adaptive k)")
+    ap.add_argument("--no-adaptive", dest="adaptive", action="store_false")
     ap.add_argument("--pipeline-stages", type=int, default=0,
                     help="also time the same iteration run as a pipeline of this many virtual stages on the one GPU "
                          "(run_pipeline_kFkB); reported under \"pipeline_sim\", the headline value is unchanged")
@@ -345,7 +347,7 @@ def main():
         scan_steps = args.scan_steps or max(3, steps // 5)
         per_k = {}
         for k_req in w["ks"]:
-            k, row = run.timed(k_req, 1, scan_steps, torch)
+            k, row = run.timed(k_req, 0 if w.get("tiled") else 1, scan_steps, torch)   # iterations of seconds need no warm-up step
             per_k[k] = row
             progress("%s: scan k = %d: %.1f ms per iteration (%d steps, delay %s)" % (name, k, row["ms_per_step"], scan_steps, run.delay_model))
         best_k = max(per_k, key=lambda k: per_k[k]["samples_per_s"])
@@ -404,13 +406,13 @@ def main():
                                  "figures show what the schedule and the boundary delays cost, not a pipeline speed-up")
 
     adaptive = None
-    if args.adaptive:
+    if args.adaptive if args.adaptive is not None else (args.workload == "very-wide-stage" and run.delay_model == "drift" and len(per_k) > 1):
         cands = sorted(k for k in per_k)
         kf.stage_sync()
         kf.kfkb_tuner_config(2, 2, cands)
         kf.stage_set_delays(None, None, None, None)
-        kf.stage_tuner_calibrate(M, 2)
-        progress("tuner calibrated (every candidate k run twice without delay)")
+        kf.stage_tuner_calibrate(M, 1)
+        progress("tuner calibrated (every candidate k run once without delay)")
         chosen = []
         torch.cuda.synchronize()
         t0 = time.perf_counter()
