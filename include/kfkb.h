@@ -206,7 +206,7 @@ int stage_last_k(void);
 int stage_side_streams_overlap(void);
 int stage_zero_grads(void);               /* enqueues a fill of grad_accum on the compute stream */
 /* Compute lanes.  Default: 2 where one block's matrix products are small enough to leave the chip partly idle
- * (24 * tokens * hidden^2 < 6e11 flops per block forward), 1 above that, where kernels of two streams only take
+ * (24 * tokens * hidden^2 < 2e12 flops per block forward), 1 above that, where kernels of two streams only take
  * each other's CUs.  run_kFkB admits ops in schedule order, up to `lanes` at a time and only while
  * an activation slot is free, so the plan's peak of live micro-batches (paper sections 3.1, 4.2: larger k holds
  * more activations) is never exceeded; the blocks of the ops in flight are enqueued in turn on one stream per

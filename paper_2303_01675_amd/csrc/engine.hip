@@ -1330,12 +1330,13 @@ int stage_init(const void* weights, int layers, int hidden, int heads, int seq) 
   HIPCHK(hipEventCreate(&g.ev_run_end));
   // How much of the chip one op's kernels fill decides how ops are best run.  A block whose matrix products are a
   // few hundred GFLOP leaves gaps (launch latency, partly filled rounds of tiles, memory-bound row kernels) that a
-  // second micro-batch in flight and W steps beside the chain fill: two lanes.  From about 0.6 TFLOP per block
+  // second micro-batch in flight and W steps beside the chain fill: two lanes.  From about 2 TFLOP per block
   // forward on, every kernel runs many rounds of tiles on all CUs, kernels of two streams only take each other's
-  // CUs and cache, and one op at a time with its W steps behind its chain is faster (measured: hidden 2048 with
-  // 4096 tokens 298 against 316 ms per iteration for two lanes, hidden 4096 with 2048 tokens 366 against 357,
-  // hidden 8192 with 4096 tokens 2430 against 2290).  stage_set_compute_lanes / stage_set_wgrad_stream override.
-  const bool big_ops = 24.0 * (double)g.m * (double)g.H * (double)g.H >= 6.0e11;
+  // CUs and cache, and one op at a time with its W steps behind its chain is faster (measured, two lanes against
+  // one, ms per iteration: hidden 2048 with 4096 tokens, 0.41 TFLOP, 268 / 290; hidden 4096 with 2048 tokens,
+  // 0.82 TFLOP, 308 / 313; hidden 8192 with 4096 tokens, 6.6 TFLOP, 1156 / 1090 for 32 micro-batches).
+  // stage_set_compute_lanes / stage_set_wgrad_stream override.
+  const bool big_ops = 24.0 * (double)g.m * (double)g.H * (double)g.H >= 2.0e12;
   g.lanes = big_ops ? 1 : 2;
   g.wgrad_overlap = !big_ops;
   g.inited = true;
