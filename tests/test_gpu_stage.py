@@ -58,11 +58,12 @@ def test_tiny_stage_fp32_matches_oracle_for_k1_and_k2(causal):
     st.close()
 
 
-@pytest.mark.parametrize("H,heads,T,b", [(128, 2, 96, 3), (256, 2, 160, 2)])
-def test_small_stage_fp16_matches_oracle(H, heads, T, b):
+@pytest.mark.parametrize("H,heads,T,b,mid", [(128, 2, 96, 3, 1), (256, 2, 160, 2, 1), (256, 2, 160, 2, 2)])
+def test_small_stage_fp16_matches_oracle(H, heads, T, b, mid):
     """fp16 storage (the paper's precision) through the same kernels as bf16: the tighter fp16 bar per tensor, and
-    bit-identical results for every k."""
+    bit-identical results for every k; mid = 2 puts every product whose width allows it on the 128 x 256 tiles."""
     dt, L, M = kf.F16, 2, 4
+    kf.kfkb_set_mid_tiles(mid)
     st, blocks, xs, dys = _make(dt, L, H, heads, T, b, M, k_max=4)
     ref = None
     for k in (1, 2, 4):
@@ -73,6 +74,7 @@ def test_small_stage_fp16_matches_oracle(H, heads, T, b):
             ref = cur
         for a, b_ in zip(ref, cur):
             assert torch.equal(a, b_)
+    kf.kfkb_set_mid_tiles(1)
     st.close()
 
 
