@@ -316,7 +316,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build drives one pipeline stage on ONE GPU; --gpus %d is not supported "
-              "(how the path shards over stages is described in DESIGN.md)" % args.gpus, file=sys.stderr)
+              "(a pipeline puts one such stage on every GPU; no collective is involved)" % args.gpus, file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
